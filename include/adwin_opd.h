@@ -1,0 +1,183 @@
+/*
+ * libadwin_opd -- teacher-anchored per-token supervision for on-policy distillation
+ * over ragged student rollouts, for one AMD MI355X (gfx950).
+ *
+ * What is computed (paper: ADWIN, "Adaptive Windows for Horizon-Aware On-Policy
+ * Distillation"):
+ *   - Sec. 4.1, synchronous path: the OPD loss is evaluated only on the first
+ *     n_i = min(window_i, len_i) response positions of rollout i.
+ *   - Eq. 2 at token level: KL_t = KL(softmax(W_s h_s[t]) || softmax(W_t h_t[t])),
+ *     student first, teacher frozen, temperature 1 (App. B.1, OPD table).
+ *   - Sec. 2.3 / App. A.1: sampled step cost c_t = log p_s(y_t) - log p_t(y_t).
+ *   - Eq. 4 in expectation over y_t ~ p_s (equivalently dKL_t/dz_s with the teacher
+ *     constant, App. A.1): dz_t = p_s * ((z_s - z_t) - E_{p_s}[z_s - z_t]);
+ *     g_t = dz_t W_s is the gradient with respect to the student hidden state.
+ *   - Sec. 4.2: alignment rho = cos(prefix-window gradient, full-rollout gradient),
+ *     per rollout and after batch aggregation (Fig. 5: "macro" and "micro").
+ *
+ * Conventions common to every entry point
+ *   - extern "C"; every function returns an int status: 0 = ADWIN_OK, negative =
+ *     error.  Nothing throws, aborts or exits.  On an argument error no output
+ *     buffer is touched and nothing is enqueued.
+ *   - "host" pointers are ordinary CPU memory read synchronously during the call;
+ *     "device" pointers are HIP device memory on the current device, owned by the
+ *     caller, row-major and contiguous, 16-byte aligned.
+ *   - The library allocates no device memory and keeps no state between calls.  All
+ *     scratch comes from the caller's workspace (size from *_workspace_bytes).
+ *   - Work is enqueued on the caller's HIP stream (`hip_stream` is a hipStream_t, NULL
+ *     = default stream) and the call returns without synchronising.  Outputs are
+ *     defined once the stream has drained and the status was ADWIN_OK.
+ *   - Row t of the packed [T, .] arrays holds the hidden state (or logits) of the
+ *     context (x, y_<t) and ids[t] = y_t: the caller has already applied the
+ *     next-token shift and dropped prompt positions.
+ *   - Results are deterministic: no floating-point atomics are used.
+ */
+#ifndef ADWIN_OPD_H
+#define ADWIN_OPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define ADWIN_OK            0
+#define ADWIN_E_NULL       -1  /* a required pointer is NULL                                  */
+#define ADWIN_E_SHAPE      -2  /* T,B,V,H out of range: see adwin_opd_problem                  */
+#define ADWIN_E_OFFSETS    -3  /* offsets[0]!=0, decreasing, or offsets[B]!=T                   */
+#define ADWIN_E_WINDOW     -4  /* a window is negative                                         */
+#define ADWIN_E_ALIGN      -5  /* a device pointer is not 16-byte aligned                      */
+#define ADWIN_E_WORKSPACE  -6  /* workspace NULL, misaligned (256 B) or too small              */
+#define ADWIN_E_MODE       -7  /* unknown mode / reduction / dh_dtype, or struct_bytes mismatch */
+#define ADWIN_E_HIP        -8  /* a HIP call or kernel launch failed                           */
+
+/* mode */
+#define ADWIN_PREFIX_ONLY      0  /* compute the admitted rows only                            */
+#define ADWIN_PREFIX_AND_FULL  1  /* probe audit: compute every row, both losses, alignment    */
+
+/* reduction: weight alpha of one token's KL in the batch objective                            */
+#define ADWIN_RED_SEQ_MEAN     0  /* alpha^p_i = 1/(B n_i),  alpha^f_i = 1/(B len_i)  (default) */
+#define ADWIN_RED_SUM          1  /* alpha = 1                                                 */
+#define ADWIN_RED_TOKEN_MEAN   2  /* alpha^p = 1/N_adm,      alpha^f = 1/T                     */
+
+/* dh_dtype */
+#define ADWIN_DT_BF16  0
+#define ADWIN_DT_F32   1
+
+/* bits of *status_dev (device-detected input faults; the call still completes) */
+#define ADWIN_DEV_BAD_ID     1u  /* some ids[t] on a computed row is outside [0, V): c_t = 0 there */
+#define ADWIN_DEV_NONFINITE  2u  /* a computed row produced a non-finite log-sum-exp            */
+
+/*
+ * Problem description for the fused path (hidden states in, Sec. 4.1 / 4.2).
+ * Limits: 1 <= B; 0 <= T < 2^31; V a positive multiple of 8; H_s and H_t positive
+ * multiples of 64 (the k-extent of one staged MFMA tile).
+ */
+typedef struct adwin_opd_problem {
+  size_t  struct_bytes;      /* sizeof(adwin_opd_problem), checked                            */
+  int64_t T;                 /* packed rows                                                    */
+  int32_t B, V, H_s, H_t;
+  const int64_t* offsets;    /* host  [B+1]  offsets[0]==0, non-decreasing, offsets[B]==T      */
+  const int32_t* window;     /* host  [B]    >= 0 ; n_i = min(window[i], len_i)                */
+  const void* h_s;           /* device bf16 [T, H_s]                                           */
+  const void* h_t;           /* device bf16 [T, H_t]                                           */
+  const void* W_s;           /* device bf16 [V, H_s]  (LM head, z = W h, no bias)              */
+  const void* W_t;           /* device bf16 [V, H_t]                                           */
+  const int32_t* ids;        /* device [T] sampled token y_t; may be NULL (then c is zero)     */
+  int32_t mode;              /* ADWIN_PREFIX_ONLY | ADWIN_PREFIX_AND_FULL                      */
+  int32_t reduction;         /* ADWIN_RED_*                                                    */
+  float   grad_scale;        /* extra multiplier on dh_prefix / dh_full                        */
+  int32_t dh_dtype;          /* ADWIN_DT_BF16 | ADWIN_DT_F32: element type of dh_*             */
+  /* device outputs; NULL = not wanted */
+  float* kl;                 /* [T] KL_t, 0 on rows not computed                               */
+  float* c;                  /* [T] c_t,  0 on rows not computed or when ids==NULL             */
+  void*  dh_prefix;          /* [T, H_s] grad_scale*alpha^p_i*g_t on admitted rows, else 0      */
+  void*  dh_full;            /* [T, H_s] grad_scale*alpha^f_i*g_t (mode PREFIX_AND_FULL only)   */
+  float* loss_prefix;        /* [B] mean KL over the window (0 if n_i == 0)                    */
+  float* loss_full;          /* [B] mean KL over the rollout (zeros in PREFIX_ONLY)            */
+  float* rho_pooled;         /* [B] cos(sum_t dh_prefix[t], sum_t dh_full[t]) over rollout i    */
+  float* rho_field;          /* [B] cos of the two [len_i, H_s] gradient arrays of rollout i    */
+  float* batch;              /* [8] L^p, L^f, pooled micro, field micro, pooled macro, field   */
+                             /*     macro, 0, 0 (alignment entries zero in PREFIX_ONLY)        */
+  int32_t* n_out;            /* [B] n_i                                                        */
+  int64_t* n_adm_out;        /* [1] N_adm = sum n_i                                            */
+  uint32_t* status_dev;      /* [1] OR of ADWIN_DEV_* bits                                     */
+} adwin_opd_problem;
+
+/*
+ * Problem description for the logits-given path: log-softmax, reverse KL and the
+ * loss gradient with respect to the student logits, no LM-head contraction.
+ * Admitted rows only (Sec. 4.1).  Limits as above; V a positive multiple of 8.
+ */
+typedef struct adwin_opd_logits_problem {
+  size_t  struct_bytes;
+  int64_t T;
+  int32_t B, V;
+  const int64_t* offsets;    /* host [B+1]                                                     */
+  const int32_t* window;     /* host [B]                                                       */
+  const void* z_s;           /* device bf16 [T, V] student logits                              */
+  const void* z_t;           /* device bf16 [T, V] teacher logits                              */
+  const int32_t* ids;        /* device [T] or NULL                                             */
+  int32_t reduction;
+  float   grad_scale;
+  float* kl;                 /* [T]                                                            */
+  float* c;                  /* [T]                                                            */
+  void*  dz;                 /* device bf16 [T, V]: grad_scale*alpha^p_i*p_s*((z_s-z_t)-mu_t)   */
+                             /* on admitted rows, 0 elsewhere                                  */
+  float* loss_prefix;        /* [B]                                                            */
+  float* batch;              /* [8] L^p then zeros                                             */
+  int32_t* n_out;            /* [B]                                                            */
+  int64_t* n_adm_out;        /* [1]                                                            */
+  uint32_t* status_dev;      /* [1]                                                            */
+} adwin_opd_logits_problem;
+
+/* Library version: major*10000 + minor*100 + patch.  Pure host. */
+int adwin_opd_version(void);
+
+/* Static, NUL-terminated description of a status code.  Pure host. */
+const char* adwin_opd_strerror(int status);
+
+/*
+ * Integer bookkeeping of Sec. 4.1 on the host (no GPU needed): validates T, B,
+ * offsets, window and writes
+ *   n[B]          n_i = min(window[i], len_i)
+ *   row_list[N]   packed indices of the admitted rows, ascending   (may be NULL)
+ *   row_seq[N]    rollout of each admitted row                     (may be NULL)
+ *   *n_adm        N = sum n_i
+ * row_list / row_seq must have room for min(T, sum window) entries; call once with
+ * both NULL to learn N.  All pointers are host memory.
+ */
+int adwin_opd_plan_host(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
+                        int32_t* n, int64_t* row_list, int32_t* row_seq, int64_t* n_adm);
+
+/* Bytes of device workspace adwin_opd_fused needs for this problem.  Pure host; reads
+ * shapes, mode, offsets and window only. */
+int adwin_opd_workspace_bytes(const adwin_opd_problem* p, size_t* bytes);
+
+/*
+ * Fused path (Sec. 4.1 loss on the prefix; Sec. 4.2 probe audit in mode
+ * PREFIX_AND_FULL): LM-head projections, full-vocabulary log-softmax, KL_t, c_t,
+ * g_t, window losses, dh_prefix / dh_full and the alignment scores.  The [rows, V]
+ * logit matrix is never stored.  `workspace` is device memory, 256-byte aligned,
+ * at least adwin_opd_workspace_bytes() long; its contents are scratch.
+ */
+int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* Bytes of device workspace adwin_opd_from_logits needs.  Pure host. */
+int adwin_opd_logits_workspace_bytes(const adwin_opd_logits_problem* p, size_t* bytes);
+
+/*
+ * Logits-given path: same per-token mathematics with z_s, z_t read from memory
+ * (Eq. 2 at token level, c_t, and the logit gradient of Eq. 4 in expectation),
+ * followed by the window losses.  Bandwidth-bound.
+ */
+int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADWIN_OPD_H */

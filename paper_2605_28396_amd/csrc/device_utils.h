@@ -1,0 +1,75 @@
+// Small device helpers: bf16 packing, wave/block reductions, segment lookup.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adwin {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2   = 0.6931471805599453f;
+constexpr float kNegBig = -1.0e30f;   // finite stand-in for -inf in running maxima
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// round-to-nearest-even fp32 -> bf16 pair packed in one 32-bit word (lo = a, hi = b)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// streaming 16-byte store that bypasses cache allocation
+__device__ __forceinline__ void nt_store16(uint4* p, const uint4& v) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, (u32x4*)p);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Merge two online-softmax partials (m, Z [, A]) into the first.
+__device__ __forceinline__ void merge_mz(float& m, float& Z, float m2, float Z2) {
+  const float mn = fmaxf(m, m2);
+  Z = Z * fast_exp2((m - mn) * kLog2e) + Z2 * fast_exp2((m2 - mn) * kLog2e);
+  m = mn;
+}
+__device__ __forceinline__ void merge_mza(float& m, float& Z, float& A, float m2, float Z2,
+                                          float A2) {
+  const float mn = fmaxf(m, m2);
+  const float s1 = fast_exp2((m - mn) * kLog2e), s2 = fast_exp2((m2 - mn) * kLog2e);
+  Z = Z * s1 + Z2 * s2;
+  A = A * s1 + A2 * s2;
+  m = mn;
+}
+
+// Largest i in [0, n) with a[i] <= x, for non-decreasing a with a[0] <= x.
+template <typename T>
+__device__ __forceinline__ int last_le(const T* a, int n, T x) {
+  int lo = 0, hi = n;  // invariant: a[lo] <= x, answer in [lo, hi)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a[mid] <= x) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+}  // namespace adwin

@@ -1,0 +1,776 @@
+// Fused path: LM-head projections on bf16 MFMA, full-vocabulary online log-sum-exp,
+// per-token reverse KL (Eq. 2 at token level), logit gradient (Eq. 4 in expectation,
+// App. A.1) and its contraction with W_s back to the student hidden state.
+//
+// Pass 1 (stats)  : for a 256-token tile, walk vocabulary tiles of 128; per tile two MFMA
+//                   GEMMs (teacher, student) into fp32 accumulators, then an in-register
+//                   online update of (m_s, Z_s, A = sum e^{z_s-m_s}(z_s-z_t), m_t, Z_t).
+// Merge           : per row: lse_s, lse_t, mu = A/Z_s, KL_t = mu - lse_s + lse_t, c_t.
+// Pass 2 (dz)     : same GEMMs again, dz = p_s((z_s-z_t) - mu) rounded to bf16 into a
+//                   bounded row slab (never the logits, never a full [rows, V] array).
+// Pass 3 (grad)   : g = dz W_s as an MFMA GEMM over the slab with k = vocabulary.
+// Finalize        : scale by grad_scale*alpha, scatter to dh_prefix / dh_full, row norms.
+//
+// MFMA operand roles: v_mfma_f32_32x32x16_bf16 computes D[i][j] += sum_k A[i][k] B[k][j]
+// with i in registers and j = lane % 32.  In the logit passes A = W tile (i = vocabulary)
+// and B = h tile (j = token), so each lane owns one token column and the reduction over
+// the vocabulary runs down its own registers with no cross-lane traffic.
+#include <vector>
+
+#include "device_utils.h"
+#include "plan_device.h"
+
+namespace adwin {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kRowBytes = kBK * 2;   // 128 B of k per staged row
+
+// ---------------------------------------------------------------------------------------
+// Staging of [ROWS x 64] bf16 tiles: global -> registers -> LDS.  Thread t moves the
+// 16-byte chunk (t & 7) of rows (t >> 3) + 32 i.  Chunk c of row r is stored at chunk
+// position c ^ (r & 7), so that the 32 rows one MFMA fragment read touches spread over
+// all LDS banks.
+// ---------------------------------------------------------------------------------------
+template <int ROWS>
+struct RowStager {
+  static constexpr int N = ROWS / 32;
+  const uint4* p[N];
+  uint4 v[N];
+  __device__ __forceinline__ void issue(int kt) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = p[i][kt * 8];
+  }
+  __device__ __forceinline__ void commit(char* tile, int thread_off) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) *(uint4*)(tile + thread_off + i * 32 * kRowBytes) = v[i];
+  }
+};
+
+__device__ __forceinline__ int stage_thread_off(int tid) {
+  const int r = tid >> 3, c = tid & 7;
+  return r * kRowBytes + ((c ^ (r & 7)) << 4);
+}
+
+// acc[FM][FN] += A_tile(wave rows) * B_tile(wave rows)^T for one staged k-step of 64.
+template <int FM, int FN>
+__device__ __forceinline__ void mma_stage(f32x16 (&acc)[FM][FN], const char* tA, const char* tB,
+                                          int lane) {
+  const int row_off = (lane & 31) * kRowBytes;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int sw = ((kk * 2 + (lane >> 5)) ^ (lane & 7)) << 4;
+    bf16x8 a[FM], b[FN];
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm)
+      a[fm] = *(const bf16x8*)(tA + fm * 32 * kRowBytes + row_off + sw);
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+      b[fn] = *(const bf16x8*)(tB + fn * 32 * kRowBytes + row_off + sw);
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn)
+        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[fm], b[fn], acc[fm][fn], 0, 0, 0);
+  }
+}
+
+// Double-buffered k loop.  ldsA/ldsB: stage 0 tiles; stage 1 follows at `stage_bytes`.
+// waveA/waveB: byte offset of this wave's rows inside the A/B tile.
+template <int RA, int RB, int FM, int FN>
+__device__ __forceinline__ void gemm_kloop(f32x16 (&acc)[FM][FN], RowStager<RA>& sa,
+                                           RowStager<RB>& sb, int kt0, int nk, char* lds,
+                                           int stage_bytes, int waveA, int waveB, int tid) {
+  constexpr int kOffB = RA * kRowBytes;
+  const int toff = stage_thread_off(tid);
+  const int lane = tid & 63;
+  sa.issue(kt0);
+  sb.issue(kt0);
+  sa.commit(lds, toff);
+  sb.commit(lds + kOffB, toff);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    char* cur = lds + (kt & 1) * stage_bytes;
+    char* nxt = lds + ((kt + 1) & 1) * stage_bytes;
+    const bool more = kt + 1 < nk;
+    if (more) {
+      sa.issue(kt0 + kt + 1);
+      sb.issue(kt0 + kt + 1);
+    }
+    mma_stage<FM, FN>(acc, cur + waveA, cur + kOffB + waveB, lane);
+    if (more) {
+      sa.commit(nxt, toff);
+      sb.commit(nxt + kOffB, toff);
+    }
+    __syncthreads();
+  }
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
+// virtual ids so that the tiles sharing operands also share an L2.
+__device__ __forceinline__ int xcd_contiguous_id(int bid, int nb) {
+  const int xcd = bid & 7, loc = bid >> 3;
+  const int base = nb >> 3, rem = nb & 7;
+  return xcd * base + (xcd < rem ? xcd : rem) + loc;
+}
+
+// ---------------------------------------------------------------------------------------
+// Logit passes
+// ---------------------------------------------------------------------------------------
+struct LogitPassArgs {
+  const __bf16* h_s; const __bf16* h_t; const __bf16* W_s; const __bf16* W_t;
+  int H_s, H_t, V;
+  const int32_t* row_idx;      // [n_pad]
+  int64_t n_pad;
+  int tile0;                   // first token tile of this launch
+  int n_tiles;                 // token tiles in this launch
+  int strips;                  // vocabulary strips
+  int vt_total;                // vocabulary tiles (of 128)
+  // pass 1 out: [5][strips][n_pad]
+  float* part;
+  // pass 2 in / out
+  const float* lse2; const float* mu;
+  __bf16* slab; int64_t Vp; int64_t slab_row0;
+};
+
+constexpr int kLogitStage = (kTileVocab + kTileTokens) * kRowBytes;   // 48 KiB
+constexpr int kLogitLds = 2 * kLogitStage;
+
+template <bool PASS2>
+__global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // virtual id -> (group of 4 token tiles, strip, tile in group)
+  const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int per_group = 4 * a.strips;
+  const int tg = vid / per_group, within = vid % per_group;
+  const int strip = within >> 2, tt_local = tg * 4 + (within & 3);
+  if (tt_local >= a.n_tiles) return;
+  const int tt = a.tile0 + tt_local;
+  const int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
+  const int vt_end = (int)((int64_t)a.vt_total * (strip + 1) / a.strips);
+
+  // token-row stagers (rows fixed for the whole vocabulary walk)
+  RowStager<kTileTokens> hs, ht;
+  RowStager<kTileVocab> ws, wt;
+  {
+    const int r = tid >> 3, c = tid & 7;
+#pragma unroll
+    for (int i = 0; i < kTileTokens / 32; ++i) {
+      const int64_t row = a.row_idx[(int64_t)tt * kTileTokens + r + 32 * i];
+      hs.p[i] = (const uint4*)(a.h_s + row * a.H_s) + c;
+      ht.p[i] = (const uint4*)(a.h_t + row * a.H_t) + c;
+    }
+  }
+  const int waveB = wave * 64 * kRowBytes;   // this wave's 64 token rows in the B tile
+
+  float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2];
+  float lse2[2], mu[2];
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    m_s[fn] = kNegBig; Z_s[fn] = 0.f; A_s[fn] = 0.f; m_t[fn] = kNegBig; Z_t[fn] = 0.f;
+    if (PASS2) {
+      const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
+      lse2[fn] = a.lse2[r];
+      mu[fn] = a.mu[r];
+    }
+  }
+
+  for (int vt = vt_begin; vt < vt_end; ++vt) {
+    const int v0 = vt * kTileVocab;
+    {
+      const int r = tid >> 3, c = tid & 7;
+#pragma unroll
+      for (int i = 0; i < kTileVocab / 32; ++i) {
+        int v = v0 + r + 32 * i;
+        v = v < a.V ? v : a.V - 1;               // tail rows: load a valid row, masked below
+        ws.p[i] = (const uint4*)(a.W_s + (int64_t)v * a.H_s) + c;
+        wt.p[i] = (const uint4*)(a.W_t + (int64_t)v * a.H_t) + c;
+      }
+    }
+    f32x16 zt[4][2], zs[4][2];
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { zt[fm][fn][e] = 0.f; zs[fm][fn][e] = 0.f; }
+    gemm_kloop<kTileVocab, kTileTokens, 4, 2>(zt, wt, ht, 0, a.H_t / kBK, lds, kLogitStage, 0, waveB, tid);
+    gemm_kloop<kTileVocab, kTileTokens, 4, 2>(zs, ws, hs, 0, a.H_s / kBK, lds, kLogitStage, 0, waveB, tid);
+
+    const bool tail = v0 + kTileVocab > a.V;
+    // element e of block fm sits at vocabulary row v0 + fm*32 + 8*(e/4) + 4*(lane/32) + e%4
+    const int vlane = v0 + 4 * (lane >> 5);
+    if (!PASS2) {
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn) {
+        float mxs = m_s[fn], mxt = m_t[fn];
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < a.V;
+            if (ok) { mxs = fmaxf(mxs, zs[fm][fn][e]); mxt = fmaxf(mxt, zt[fm][fn][e]); }
+          }
+        const float scs = fast_exp2((m_s[fn] - mxs) * kLog2e);
+        const float sct = fast_exp2((m_t[fn] - mxt) * kLog2e);
+        float Zs = Z_s[fn] * scs, As = A_s[fn] * scs, Zt = Z_t[fn] * sct;
+        const float ms2 = mxs * kLog2e, mt2 = mxt * kLog2e;
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < a.V;
+            const float s = zs[fm][fn][e], t = zt[fm][fn][e];
+            float es = fast_exp2(fmaf(s, kLog2e, -ms2));
+            float et = fast_exp2(fmaf(t, kLog2e, -mt2));
+            float d = s - t;
+            if (!ok) { es = 0.f; et = 0.f; d = 0.f; }
+            Zs += es;
+            As = fmaf(es, d, As);
+            Zt += et;
+          }
+        m_s[fn] = mxs; m_t[fn] = mxt; Z_s[fn] = Zs; A_s[fn] = As; Z_t[fn] = Zt;
+      }
+    } else {
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn) {
+        const int64_t rl = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31) - a.slab_row0;
+        __bf16* out = a.slab + rl * a.Vp + vlane;
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float d[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
+              d[e] = fast_exp2(fmaf(s, kLog2e, -lse2[fn])) * ((s - t) - mu[fn]);
+            }
+            if (tail && vlane + fm * 32 + 8 * q >= a.V) { d[0] = d[1] = d[2] = d[3] = 0.f; }
+            uint2 o;
+            o.x = pack_bf16(d[0], d[1]);
+            o.y = pack_bf16(d[2], d[3]);
+            *(uint2*)(out + fm * 32 + 8 * q) = o;
+          }
+      }
+    }
+  }
+  if (!PASS2) {
+#pragma unroll
+    for (int fn = 0; fn < 2; ++fn) {
+      // lanes l and l^32 hold the two halves of the same token column
+      merge_mza(m_s[fn], Z_s[fn], A_s[fn], __shfl_xor(m_s[fn], 32, 64), __shfl_xor(Z_s[fn], 32, 64),
+                __shfl_xor(A_s[fn], 32, 64));
+      merge_mz(m_t[fn], Z_t[fn], __shfl_xor(m_t[fn], 32, 64), __shfl_xor(Z_t[fn], 32, 64));
+      if (lane < 32) {
+        const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + lane;
+        const int64_t plane = (int64_t)a.strips * a.n_pad;
+        float* o = a.part + (int64_t)strip * a.n_pad + r;
+        o[0 * plane] = m_s[fn];
+        o[1 * plane] = Z_s[fn];
+        o[2 * plane] = A_s[fn];
+        o[3 * plane] = m_t[fn];
+        o[4 * plane] = Z_t[fn];
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Merge of the strip partials, KL_t and c_t.  One wave per computed row.
+// ---------------------------------------------------------------------------------------
+struct MergeArgs {
+  const float* part; int strips; int64_t n_pad; int64_t n_rows;
+  const int32_t* row_idx;
+  const __bf16* h_s; const __bf16* h_t; const __bf16* W_s; const __bf16* W_t;
+  int H_s, H_t, V;
+  const int32_t* ids;
+  float* lse2; float* mu; float* klr;
+  float* kl; float* c;
+  uint32_t* status;
+};
+
+__device__ __forceinline__ float dot_bf16_row(const __bf16* x, const __bf16* y, int H, int lane) {
+  float acc = 0.f;
+  const uint4* px = (const uint4*)x;
+  const uint4* py = (const uint4*)y;
+  for (int q = lane; q < (H >> 3); q += 64) {
+    const uint4 a = px[q], b = py[q];
+    acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+    acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+    acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+    acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+  }
+  return wave_sum(acc);
+}
+
+__global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.n_pad) return;
+  const int64_t plane = (int64_t)a.strips * a.n_pad;
+  float ms = kNegBig, Zs = 0.f, A = 0.f, mt = kNegBig, Zt = 0.f;
+  if (lane < a.strips) {
+    const float* p = a.part + (int64_t)lane * a.n_pad + r;
+    ms = p[0]; Zs = p[plane]; A = p[2 * plane]; mt = p[3 * plane]; Zt = p[4 * plane];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    merge_mza(ms, Zs, A, __shfl_xor(ms, o, 64), __shfl_xor(Zs, o, 64), __shfl_xor(A, o, 64));
+    merge_mz(mt, Zt, __shfl_xor(mt, o, 64), __shfl_xor(Zt, o, 64));
+  }
+  const float lse_s = ms + logf(Zs), lse_t = mt + logf(Zt);
+  const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
+  const float kl = mu - lse_s + lse_t;
+  if (lane == 0) {
+    a.lse2[r] = lse_s * kLog2e;
+    a.mu[r] = mu;
+    a.klr[r] = kl;
+  }
+  if (r >= a.n_rows) return;                // padding rows feed pass 2 only
+  const int64_t t = a.row_idx[r];
+  float c = 0.f;
+  uint32_t flag = 0;
+  if (a.ids && a.c) {
+    const int y = a.ids[t];
+    if (y >= 0 && y < a.V) {
+      const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
+      const float zy_t = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)y * a.H_t, a.H_t, lane);
+      c = (zy_s - lse_s) - (zy_t - lse_t);
+    } else {
+      flag |= ADWIN_DEV_BAD_ID;
+    }
+  }
+  if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f))
+    flag |= ADWIN_DEV_NONFINITE;
+  if (lane == 0) {
+    if (flag && a.status) atomicOr(a.status, flag);
+    if (a.kl) a.kl[t] = kl;
+    if (a.c) a.c[t] = c;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// W_s [V, H] -> W_sT [H, Vp] (zero beyond V) so that the gradient GEMM reads both operands
+// k-contiguous.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ W,
+                                                            uint16_t* __restrict__ WT, int V, int H,
+                                                            int64_t Vp) {
+  __shared__ uint16_t tile[64][66];
+  const int v0 = blockIdx.x * 64, h0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int v = v0 + i, h = h0 + tx;
+    tile[i][tx] = (v < V && h < H) ? W[(int64_t)v * H + h] : (uint16_t)0;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int h = h0 + i, v = v0 + tx;
+    if (h < H && v < Vp) WT[(int64_t)h * Vp + v] = tile[tx][i];
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Pass 3: g[r][h] = sum_v dz[r][v] W_sT[h][v].  256x256 output tile, 2x2 waves of 128x128.
+// A = dz slab rows (i = row), B = W_sT rows (j = hidden column, contiguous in g).
+// ---------------------------------------------------------------------------------------
+struct GradArgs {
+  const __bf16* slab; const __bf16* WsT; int64_t Vp;
+  float* g;                 // [ksplit][n_pad][H]
+  int64_t n_pad; int H;
+  int64_t slab_row0;        // computed-row index of slab row 0
+  int row_tiles, h_tiles, ksplit;
+};
+
+constexpr int kGradStage = 2 * kGradTile * kRowBytes;   // 64 KiB
+constexpr int kGradLds = 2 * kGradStage;
+
+__global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int tiles = a.row_tiles * a.h_tiles;
+  const int split = vid / tiles;
+  vid -= split * tiles;
+  const int rt = vid / a.h_tiles, ht = vid % a.h_tiles;
+
+  const int nk_total = (int)(a.Vp / kBK);
+  const int k_begin = (int)((int64_t)nk_total * split / a.ksplit);
+  const int k_end = (int)((int64_t)nk_total * (split + 1) / a.ksplit);
+
+  RowStager<kGradTile> sa, sb;
+  {
+    const int r = tid >> 3, c = tid & 7;
+#pragma unroll
+    for (int i = 0; i < kGradTile / 32; ++i) {
+      const int64_t row = (int64_t)rt * kGradTile + r + 32 * i;
+      sa.p[i] = (const uint4*)(a.slab + row * a.Vp) + c;
+      int h = ht * kGradTile + r + 32 * i;
+      h = h < a.H ? h : a.H - 1;
+      sb.p[i] = (const uint4*)(a.WsT + (int64_t)h * a.Vp) + c;
+    }
+  }
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+    for (int fn = 0; fn < 4; ++fn)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[fm][fn][e] = 0.f;
+  gemm_kloop<kGradTile, kGradTile, 4, 4>(acc, sa, sb, k_begin, k_end - k_begin, lds, kGradStage,
+                                         wm * 128 * kRowBytes, wn * 128 * kRowBytes, tid);
+  float* g = a.g + (int64_t)split * a.n_pad * a.H;
+#pragma unroll
+  for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+    for (int fn = 0; fn < 4; ++fn) {
+      const int h = ht * kGradTile + wn * 128 + fn * 32 + (lane & 31);
+      if (h < a.H) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int64_t r = a.slab_row0 + (int64_t)rt * kGradTile + wm * 128 + fm * 32 +
+                            8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+          g[r * a.H + h] = acc[fm][fn][e];
+        }
+      }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Finalize: one wave per packed row.  Sums the k-split partials, writes the row norm,
+// scales by grad_scale*alpha and scatters to dh_prefix / dh_full (zero outside windows).
+// ---------------------------------------------------------------------------------------
+struct FinalizeArgs {
+  DevicePlan pl; int B; int64_t T; int probe;
+  float* g; int ksplit; int64_t n_pad; int H;
+  float grad_scale; int dh_bf16;
+  void* dh_prefix; void* dh_full;
+  float* rownorm;
+};
+
+__device__ __forceinline__ void store_dh(void* base, int bf16, int64_t t, int H, int h, float4 v) {
+  if (!base) return;
+  if (bf16) {
+    uint2 o;
+    o.x = pack_bf16(v.x, v.y);
+    o.y = pack_bf16(v.z, v.w);
+    *(uint2*)((uint16_t*)base + t * H + h) = o;
+  } else {
+    *(float4*)((float*)base + t * H + h) = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= a.T) return;
+  const int i = last_le<int64_t>(a.pl.offsets, a.B + 1, t);
+  const int64_t j = t - a.pl.offsets[i];
+  const bool admitted = j < a.pl.n[i];
+  const bool computed = a.probe || admitted;
+  const float4 zero = {0.f, 0.f, 0.f, 0.f};
+  if (!computed) {
+    for (int h = lane * 4; h < a.H; h += 256) store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, zero);
+    return;
+  }
+  const int64_t r = a.pl.comp_off[i] + j;
+  const float sp = admitted ? a.grad_scale * a.pl.alpha_p[i] : 0.f;
+  const float sf = a.grad_scale * a.pl.alpha_f[i];
+  float nrm = 0.f;
+  for (int h = lane * 4; h < a.H; h += 256) {
+    float4 g = *(const float4*)(a.g + r * a.H + h);
+    for (int s = 1; s < a.ksplit; ++s) {
+      const float4 q = *(const float4*)(a.g + ((int64_t)s * a.n_pad + r) * a.H + h);
+      g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w;
+    }
+    if (a.ksplit > 1) *(float4*)(a.g + r * a.H + h) = g;
+    nrm = fmaf(g.x, g.x, fmaf(g.y, g.y, fmaf(g.z, g.z, fmaf(g.w, g.w, nrm))));
+    const float4 p = {g.x * sp, g.y * sp, g.z * sp, g.w * sp};
+    store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, p);
+    if (a.probe) {
+      const float4 f = {g.x * sf, g.y * sf, g.z * sf, g.w * sf};
+      store_dh(a.dh_full, a.dh_bf16, t, a.H, h, f);
+    }
+  }
+  nrm = wave_sum(nrm);
+  if (lane == 0) a.rownorm[r] = nrm;
+}
+
+// ---------------------------------------------------------------------------------------
+// Pooled gradients: column sums of g over the window and over the rollout, two levels.
+// ---------------------------------------------------------------------------------------
+struct PoolArgs {
+  DevicePlan pl; int B; int probe; int H;
+  const float* g; float* pp; float* pf;   // partials [n_chunks][H]
+  float* up; float* uf;                   // [B][H]
+};
+
+__global__ __launch_bounds__(256) void pool_partial_kernel(PoolArgs a) {
+  const int ch = blockIdx.x;
+  const int h = blockIdx.y * 256 + threadIdx.x;
+  const int i = last_le<int32_t>(a.pl.chunk_off, a.B + 1, ch);
+  const int64_t len = a.pl.offsets[i + 1] - a.pl.offsets[i];
+  const int64_t ni = a.pl.n[i];
+  const int64_t hi = a.probe ? len : ni;
+  const int64_t j0 = (int64_t)(ch - a.pl.chunk_off[i]) * kChunkRows;
+  const int64_t j1 = j0 + kChunkRows < hi ? j0 + kChunkRows : hi;
+  if (h >= a.H) return;
+  const float* g = a.g + (a.pl.comp_off[i] + j0) * a.H + h;
+  float sp = 0.f, sf = 0.f;
+  for (int64_t j = j0; j < j1; ++j, g += a.H) {
+    const float v = *g;
+    sf += v;
+    if (j < ni) sp += v;
+  }
+  a.pp[(int64_t)ch * a.H + h] = sp;
+  a.pf[(int64_t)ch * a.H + h] = sf;
+}
+
+__global__ __launch_bounds__(256) void pool_final_kernel(PoolArgs a) {
+  const int i = blockIdx.x;
+  const int h = blockIdx.y * 256 + threadIdx.x;
+  if (h >= a.H) return;
+  float sp = 0.f, sf = 0.f;
+  for (int ch = a.pl.chunk_off[i]; ch < a.pl.chunk_off[i + 1]; ++ch) {
+    sp += a.pp[(int64_t)ch * a.H + h];
+    sf += a.pf[(int64_t)ch * a.H + h];
+  }
+  a.up[(int64_t)i * a.H + h] = sp;
+  a.uf[(int64_t)i * a.H + h] = sf;
+}
+
+// ---------------------------------------------------------------------------------------
+// Workspace layout and the entry point
+// ---------------------------------------------------------------------------------------
+struct FusedLayout {
+  int strips, ksplit;
+  int64_t slab_rows, Vp;
+  size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, total;
+};
+
+static int env_int(const char* name, int dflt) {
+  const char* s = getenv(name);
+  if (!s || !*s) return dflt;
+  const int v = atoi(s);
+  return v > 0 ? v : dflt;
+}
+
+static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) {
+  FusedLayout L;
+  const int64_t n_pad = hp.n_pad > 0 ? hp.n_pad : kTileTokens;
+  const int vt_total = (p->V + kTileVocab - 1) / kTileVocab;
+  L.Vp = (int64_t)vt_total * kTileVocab;
+  int strips = env_int("ADWIN_STRIPS", 8);
+  if (strips > vt_total) strips = vt_total;
+  if (strips > kMaxStrips) strips = kMaxStrips;
+  L.strips = strips;
+  int64_t slab = env_int("ADWIN_SLAB_ROWS", 8192);
+  slab = (int64_t)align_up((size_t)slab, kTileTokens);
+  if (slab > n_pad) slab = n_pad;
+  L.slab_rows = slab;
+  const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
+  const int64_t tiles = (slab / kGradTile) * h_tiles;
+  int ks = (int)(256 / (tiles > 0 ? tiles : 1));
+  const int nk = (int)(L.Vp / kBK);
+  if (ks > 16) ks = 16;
+  if (ks > nk) ks = nk;
+  if (ks < 1) ks = 1;
+  L.ksplit = ks;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+  L.o_plan = take(PlanBlobLayout(p->B).bytes);
+  L.o_row_idx = take(sizeof(int32_t) * (size_t)n_pad);
+  L.o_row_seq = take(sizeof(int32_t) * (size_t)n_pad);
+  L.o_part = take(sizeof(float) * 5 * (size_t)strips * (size_t)n_pad);
+  L.o_lse2 = take(sizeof(float) * (size_t)n_pad);
+  L.o_mu = take(sizeof(float) * (size_t)n_pad);
+  L.o_klr = take(sizeof(float) * (size_t)n_pad);
+  L.o_rownorm = take(sizeof(float) * (size_t)n_pad);
+  L.o_WsT = take(2 * (size_t)p->H_s * (size_t)L.Vp);
+  L.o_slab = take(2 * (size_t)slab * (size_t)L.Vp);
+  L.o_g = take(sizeof(float) * (size_t)ks * (size_t)n_pad * (size_t)p->H_s);
+  const size_t nch = (size_t)(hp.n_chunks > 0 ? hp.n_chunks : 1);
+  L.o_pp = take(sizeof(float) * nch * (size_t)p->H_s);
+  L.o_pf = take(sizeof(float) * nch * (size_t)p->H_s);
+  L.o_up = take(sizeof(float) * (size_t)p->B * (size_t)p->H_s);
+  L.o_uf = take(sizeof(float) * (size_t)p->B * (size_t)p->H_s);
+  L.o_seg = take(sizeof(double) * 4 * (size_t)p->B);
+  L.o_racc = take(sizeof(double) * 4 * (size_t)p->B);
+  L.total = o;
+  return L;
+}
+
+static int check_problem(const adwin_opd_problem* p) {
+  if (!p) return ADWIN_E_NULL;
+  if (p->struct_bytes != sizeof(adwin_opd_problem)) return ADWIN_E_MODE;
+  int st = validate_ragged(p->T, p->B, p->offsets, p->window);
+  if (st != ADWIN_OK) return st;
+  if (p->V <= 0 || (p->V & 7) || p->H_s <= 0 || (p->H_s % kBK) || p->H_t <= 0 || (p->H_t % kBK))
+    return ADWIN_E_SHAPE;
+  if (p->mode != ADWIN_PREFIX_ONLY && p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
+  if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
+  if (p->dh_dtype != ADWIN_DT_BF16 && p->dh_dtype != ADWIN_DT_F32) return ADWIN_E_MODE;
+  return ADWIN_OK;
+}
+
+static hipError_t ensure_lds_opt_in() {
+  static bool done = false;
+  if (done) return hipSuccess;
+  hipError_t e;
+  e = hipFuncSetAttribute((const void*)logit_pass_kernel<false>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kLogitLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_kernel<true>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kLogitLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)grad_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kGradLds);
+  if (e != hipSuccess) return e;
+  done = true;
+  return hipSuccess;
+}
+
+}  // namespace adwin
+
+using namespace adwin;
+
+extern "C" int adwin_opd_workspace_bytes(const adwin_opd_problem* p, size_t* bytes) {
+  if (!bytes) return ADWIN_E_NULL;
+  int st = check_problem(p);
+  if (st != ADWIN_OK) return st;
+  HostPlan hp = make_host_plan(p->T, p->B, p->offsets, p->window,
+                               p->mode == ADWIN_PREFIX_AND_FULL, p->reduction, nullptr);
+  *bytes = fused_layout(p, hp).total;
+  return ADWIN_OK;
+}
+
+extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+  int st = check_problem(p);
+  if (st != ADWIN_OK) return st;
+  if (!p->W_s || !p->W_t) return ADWIN_E_NULL;
+  if (p->T > 0 && (!p->h_s || !p->h_t)) return ADWIN_E_NULL;
+  const uintptr_t al = (uintptr_t)p->h_s | (uintptr_t)p->h_t | (uintptr_t)p->W_s |
+                       (uintptr_t)p->W_t | (uintptr_t)p->dh_prefix | (uintptr_t)p->dh_full;
+  if (al & 15) return ADWIN_E_ALIGN;
+  const int probe = p->mode == ADWIN_PREFIX_AND_FULL;
+  std::vector<unsigned char> blob;
+  HostPlan hp = make_host_plan(p->T, p->B, p->offsets, p->window, probe, p->reduction, &blob);
+  FusedLayout L = fused_layout(p, hp);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total)
+    return ADWIN_E_WORKSPACE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  unsigned char* ws = (unsigned char*)workspace;
+  ADWIN_HIP_TRY(ensure_lds_opt_in());
+
+  ADWIN_HIP_TRY(hipMemcpyAsync(ws + L.o_plan, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
+  DevicePlan pl = device_plan_at(ws + L.o_plan, p->B, (int32_t*)(ws + L.o_row_idx),
+                                 (int32_t*)(ws + L.o_row_seq));
+  float* klr = (float*)(ws + L.o_klr);
+  float* rownorm = (float*)(ws + L.o_rownorm);
+  float* gws = (float*)(ws + L.o_g);
+  double* seg = (double*)(ws + L.o_seg);
+  const int64_t n_pad = hp.n_pad;
+
+  ADWIN_HIP_TRY(launch_fill_u32(p->status_dev, 1, 0u, stream));
+  if (!probe) {   // rows outside the windows report zero KL and cost
+    ADWIN_HIP_TRY(launch_fill_f32(p->kl, p->T, 0.f, stream));
+    ADWIN_HIP_TRY(launch_fill_f32(p->c, p->T, 0.f, stream));
+  } else if (!p->ids) {
+    ADWIN_HIP_TRY(launch_fill_f32(p->c, p->T, 0.f, stream));
+  }
+
+  if (hp.n_rows > 0) {
+    ADWIN_HIP_TRY(launch_build_rows(pl, p->B, hp.n_rows, n_pad, stream));
+    const int vt_total = (int)(L.Vp / kTileVocab);
+    const int n_tiles = (int)(n_pad / kTileTokens);
+    // W_s^T for the gradient GEMM
+    {
+      dim3 g((unsigned)((L.Vp + 63) / 64), (unsigned)((p->H_s + 63) / 64));
+      transpose_pad_kernel<<<g, 256, 0, stream>>>((const uint16_t*)p->W_s, (uint16_t*)(ws + L.o_WsT),
+                                                  p->V, p->H_s, L.Vp);
+      ADWIN_HIP_TRY(hipGetLastError());
+    }
+    LogitPassArgs la;
+    la.h_s = (const __bf16*)p->h_s; la.h_t = (const __bf16*)p->h_t;
+    la.W_s = (const __bf16*)p->W_s; la.W_t = (const __bf16*)p->W_t;
+    la.H_s = p->H_s; la.H_t = p->H_t; la.V = p->V;
+    la.row_idx = pl.row_idx; la.n_pad = n_pad;
+    la.vt_total = vt_total;
+    la.part = (float*)(ws + L.o_part);
+    la.lse2 = (const float*)(ws + L.o_lse2); la.mu = (const float*)(ws + L.o_mu);
+    la.slab = (__bf16*)(ws + L.o_slab); la.Vp = L.Vp; la.slab_row0 = 0;
+    // pass 1 over all token tiles
+    {
+      la.tile0 = 0; la.n_tiles = n_tiles; la.strips = L.strips;
+      const int groups = (n_tiles + 3) / 4;
+      logit_pass_kernel<false><<<(unsigned)(groups * 4 * L.strips), 256, kLogitLds, stream>>>(la);
+      ADWIN_HIP_TRY(hipGetLastError());
+    }
+    {
+      MergeArgs m;
+      m.part = la.part; m.strips = L.strips; m.n_pad = n_pad; m.n_rows = hp.n_rows;
+      m.row_idx = pl.row_idx;
+      m.h_s = la.h_s; m.h_t = la.h_t; m.W_s = la.W_s; m.W_t = la.W_t;
+      m.H_s = p->H_s; m.H_t = p->H_t; m.V = p->V; m.ids = p->ids;
+      m.lse2 = (float*)(ws + L.o_lse2); m.mu = (float*)(ws + L.o_mu); m.klr = klr;
+      m.kl = p->kl; m.c = p->c; m.status = p->status_dev;
+      merge_stats_kernel<<<(unsigned)((n_pad + 3) / 4), 256, 0, stream>>>(m);
+      ADWIN_HIP_TRY(hipGetLastError());
+    }
+    // pass 2 + 3, one row slab at a time
+    const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
+    const int strips2 = env_int("ADWIN_STRIPS2", 32) < vt_total ? env_int("ADWIN_STRIPS2", 32) : vt_total;
+    for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
+      const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
+      la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
+      la.strips = strips2; la.slab_row0 = r0;
+      const int groups = (la.n_tiles + 3) / 4;
+      logit_pass_kernel<true><<<(unsigned)(groups * 4 * strips2), 256, kLogitLds, stream>>>(la);
+      ADWIN_HIP_TRY(hipGetLastError());
+      GradArgs ga;
+      ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.Vp = L.Vp;
+      ga.g = gws; ga.n_pad = n_pad; ga.H = p->H_s; ga.slab_row0 = r0;
+      ga.row_tiles = (int)(rows / kGradTile); ga.h_tiles = h_tiles; ga.ksplit = L.ksplit;
+      grad_gemm_kernel<<<(unsigned)(ga.row_tiles * h_tiles * L.ksplit), 256, kGradLds, stream>>>(ga);
+      ADWIN_HIP_TRY(hipGetLastError());
+    }
+  }
+  // finalize over every packed row (also zero-fills rows outside the windows)
+  if (p->T > 0) {
+    FinalizeArgs f;
+    f.pl = pl; f.B = p->B; f.T = p->T; f.probe = probe;
+    f.g = gws; f.ksplit = L.ksplit; f.n_pad = n_pad; f.H = p->H_s;
+    f.grad_scale = p->grad_scale; f.dh_bf16 = p->dh_dtype == ADWIN_DT_BF16;
+    f.dh_prefix = p->dh_prefix; f.dh_full = p->dh_full; f.rownorm = rownorm;
+    finalize_kernel<<<(unsigned)((p->T + 3) / 4), 256, 0, stream>>>(f);
+    ADWIN_HIP_TRY(hipGetLastError());
+  }
+  ADWIN_HIP_TRY(launch_segment_sums(pl, p->B, probe, klr, rownorm, seg, p->loss_prefix,
+                                    p->loss_full, stream));
+  PoolArgs pa;
+  pa.pl = pl; pa.B = p->B; pa.probe = probe; pa.H = p->H_s; pa.g = gws;
+  pa.pp = (float*)(ws + L.o_pp); pa.pf = (float*)(ws + L.o_pf);
+  pa.up = (float*)(ws + L.o_up); pa.uf = (float*)(ws + L.o_uf);
+  if (probe) {
+    const unsigned hy = (unsigned)((p->H_s + 255) / 256);
+    if (hp.n_chunks > 0) {
+      pool_partial_kernel<<<dim3((unsigned)hp.n_chunks, hy), 256, 0, stream>>>(pa);
+      ADWIN_HIP_TRY(hipGetLastError());
+    }
+    pool_final_kernel<<<dim3((unsigned)p->B, hy), 256, 0, stream>>>(pa);
+    ADWIN_HIP_TRY(hipGetLastError());
+  }
+  BatchArgs b{};
+  b.pl = pl; b.B = p->B; b.H = p->H_s; b.probe = probe; b.zero_grad = (p->grad_scale == 0.f);
+  b.seg = seg; b.up = pa.up; b.uf = pa.uf; b.racc = (double*)(ws + L.o_racc);
+  b.rho_pooled = p->rho_pooled; b.rho_field = p->rho_field; b.batch = p->batch;
+  b.n_out = p->n_out; b.n_adm_out = p->n_adm_out; b.n_adm = hp.n_adm;
+  ADWIN_HIP_TRY(launch_alignment_and_batch(b, stream));
+  return ADWIN_OK;
+}

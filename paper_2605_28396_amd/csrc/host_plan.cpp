@@ -1,0 +1,78 @@
+// Host-side integer bookkeeping (Sec. 4.1: rollouts truncated at the window), status
+// strings and the version.  Nothing here touches the GPU.
+#include <atomic>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+
+namespace adwin {
+
+static thread_local char g_hip_error[256] = "";
+
+const char* last_hip_error_text() { return g_hip_error; }
+
+void set_last_hip_error(hipError_t e, const char* where) {
+  snprintf(g_hip_error, sizeof(g_hip_error), "HIP error %d (%s) at %s", (int)e,
+           hipGetErrorString(e), where);
+}
+
+int validate_ragged(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window) {
+  if (!offsets || !window) return ADWIN_E_NULL;
+  if (B < 1 || T < 0 || T >= (int64_t(1) << 31)) return ADWIN_E_SHAPE;
+  if (offsets[0] != 0) return ADWIN_E_OFFSETS;
+  for (int32_t i = 0; i < B; ++i)
+    if (offsets[i + 1] < offsets[i]) return ADWIN_E_OFFSETS;
+  if (offsets[B] != T) return ADWIN_E_OFFSETS;
+  for (int32_t i = 0; i < B; ++i)
+    if (window[i] < 0) return ADWIN_E_WINDOW;
+  return ADWIN_OK;
+}
+
+}  // namespace adwin
+
+extern "C" {
+
+int adwin_opd_version(void) { return 100; }  // 0.1.0
+
+const char* adwin_opd_strerror(int status) {
+  switch (status) {
+    case ADWIN_OK: return "ok";
+    case ADWIN_E_NULL: return "a required pointer is NULL";
+    case ADWIN_E_SHAPE:
+      return "bad shape: need B>=1, 0<=T<2^31, V a positive multiple of 8, H_s and H_t positive "
+             "multiples of 64";
+    case ADWIN_E_OFFSETS: return "offsets must start at 0, be non-decreasing and end at T";
+    case ADWIN_E_WINDOW: return "window lengths must be >= 0";
+    case ADWIN_E_ALIGN: return "device pointers must be 16-byte aligned";
+    case ADWIN_E_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
+    case ADWIN_E_MODE: return "unknown mode, reduction or dh_dtype, or struct_bytes mismatch";
+    case ADWIN_E_HIP: {
+      const char* t = adwin::last_hip_error_text();
+      return t[0] ? t : "a HIP call failed";
+    }
+    default: return "unknown status";
+  }
+}
+
+int adwin_opd_plan_host(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
+                        int32_t* n, int64_t* row_list, int32_t* row_seq, int64_t* n_adm) {
+  int st = adwin::validate_ragged(T, B, offsets, window);
+  if (st != ADWIN_OK) return st;
+  if (!n || !n_adm) return ADWIN_E_NULL;
+  int64_t total = 0;
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t len = offsets[i + 1] - offsets[i];
+    const int64_t ni = window[i] < len ? (int64_t)window[i] : len;
+    n[i] = (int32_t)ni;
+    for (int64_t j = 0; j < ni; ++j) {
+      if (row_list) row_list[total + j] = offsets[i] + j;
+      if (row_seq) row_seq[total + j] = i;
+    }
+    total += ni;
+  }
+  *n_adm = total;
+  return ADWIN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,216 @@
+// Logits-given path: full-vocabulary log-softmax of student and teacher, per-token
+// reverse KL (Eq. 2 at token level), sampled cost c_t (Sec. 2.3) and the logit gradient
+// p_s((z_s - z_t) - mu) (Eq. 4 in expectation, App. A.1) on the admitted rows
+// (Sec. 4.1), streamed from HBM.  One workgroup per packed row; two sweeps over the row.
+#include <vector>
+
+#include "device_utils.h"
+#include "plan_device.h"
+
+namespace adwin {
+
+constexpr int kRowThreads = 512;
+
+struct LogitsArgs {
+  DevicePlan pl;
+  int32_t B, V;
+  const uint4* z_s;
+  const uint4* z_t;
+  const int32_t* ids;
+  float grad_scale;
+  float* kl;
+  float* c;
+  uint4* dz;
+  float* klr;          // [T] workspace copy of KL_t on computed rows (compact index)
+  uint32_t* status;
+};
+
+__device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
+  f[0] = bf16_lo(q.x); f[1] = bf16_hi(q.x);
+  f[2] = bf16_lo(q.y); f[3] = bf16_hi(q.y);
+  f[4] = bf16_lo(q.z); f[5] = bf16_hi(q.z);
+  f[6] = bf16_lo(q.w); f[7] = bf16_hi(q.w);
+}
+
+__global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
+  __shared__ float sh[5][kRowThreads / 64];
+  __shared__ float bc[4];
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int nvec = a.V >> 3;
+  const int i = last_le<int64_t>(a.pl.offsets, a.B + 1, t);
+  const int64_t j = t - a.pl.offsets[i];
+  uint4* dzr = a.dz ? a.dz + t * nvec : nullptr;
+  if (j >= a.pl.n[i]) {   // outside the window: zero gradient row, zero KL
+    if (dzr) {
+      const uint4 z = {0u, 0u, 0u, 0u};
+      for (int q = tid; q < nvec; q += kRowThreads) nt_store16(dzr + q, z);
+    }
+    if (tid == 0) {
+      if (a.kl) a.kl[t] = 0.f;
+      if (a.c) a.c[t] = 0.f;
+    }
+    return;
+  }
+  const uint4* zs = a.z_s + t * nvec;
+  const uint4* zt = a.z_t + t * nvec;
+
+  // ---- sweep 1: running max / sum-exp of both rows and A = sum e^{z_s-m}(z_s-z_t) ----
+  float ms = kNegBig, Zs = 0.f, A = 0.f, mt = kNegBig, Zt = 0.f;
+  for (int q = tid; q < nvec; q += kRowThreads) {
+    const uint4 qs = zs[q], qt = zt[q];
+    float s[8], u[8];
+    unpack8(qs, s);
+    unpack8(qt, u);
+    float mx = s[0], mxt = u[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) { mx = fmaxf(mx, s[k]); mxt = fmaxf(mxt, u[k]); }
+    if (mx > ms) {
+      const float sc = fast_exp2((ms - mx) * kLog2e);
+      Zs *= sc; A *= sc; ms = mx;
+    }
+    if (mxt > mt) { Zt *= fast_exp2((mt - mxt) * kLog2e); mt = mxt; }
+    const float ms2 = ms * kLog2e, mt2 = mt * kLog2e;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float e = fast_exp2(fmaf(s[k], kLog2e, -ms2));
+      Zs += e;
+      A = fmaf(e, s[k] - u[k], A);
+      Zt += fast_exp2(fmaf(u[k], kLog2e, -mt2));
+    }
+  }
+  // wave then block merge, fixed order
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    merge_mza(ms, Zs, A, __shfl_xor(ms, o, 64), __shfl_xor(Zs, o, 64), __shfl_xor(A, o, 64));
+    merge_mz(mt, Zt, __shfl_xor(mt, o, 64), __shfl_xor(Zt, o, 64));
+  }
+  if (lane == 0) { sh[0][w] = ms; sh[1][w] = Zs; sh[2][w] = A; sh[3][w] = mt; sh[4][w] = Zt; }
+  __syncthreads();
+  if (tid == 0) {
+    float m = sh[0][0], Z = sh[1][0], Aa = sh[2][0], m2 = sh[3][0], Z2 = sh[4][0];
+    for (int k = 1; k < kRowThreads / 64; ++k) {
+      merge_mza(m, Z, Aa, sh[0][k], sh[1][k], sh[2][k]);
+      merge_mz(m2, Z2, sh[3][k], sh[4][k]);
+    }
+    const float lse_s = m + logf(Z), lse_t = m2 + logf(Z2);
+    const float mu = Aa / Z;                       // E_{p_s}[z_s - z_t]
+    const float kl = mu - lse_s + lse_t;
+    float c = 0.f;
+    uint32_t flag = 0;
+    if (a.ids) {
+      const int y = a.ids[t];
+      if (y >= 0 && y < a.V) {
+        const uint16_t* ps = (const uint16_t*)zs;
+        const uint16_t* pt = (const uint16_t*)zt;
+        const float zy_s = __uint_as_float((uint32_t)ps[y] << 16);
+        const float zy_t = __uint_as_float((uint32_t)pt[y] << 16);
+        c = (zy_s - lse_s) - (zy_t - lse_t);
+      } else {
+        flag |= ADWIN_DEV_BAD_ID;
+      }
+    }
+    if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f))
+      flag |= ADWIN_DEV_NONFINITE;
+    if (flag && a.status) atomicOr(a.status, flag);
+    if (a.kl) a.kl[t] = kl;
+    if (a.c) a.c[t] = c;
+    a.klr[a.pl.comp_off[i] + j] = kl;
+    bc[0] = lse_s * kLog2e;
+    bc[1] = mu;
+  }
+  __syncthreads();
+  if (!dzr) return;
+  // ---- sweep 2: dz = scale * p_s * ((z_s - z_t) - mu) --------------------------------
+  const float lse2 = bc[0], mu = bc[1];
+  const float scale = a.grad_scale * a.pl.alpha_p[i];
+  for (int q = tid; q < nvec; q += kRowThreads) {
+    const uint4 qs = zs[q], qt = zt[q];
+    float s[8], u[8], d[8];
+    unpack8(qs, s);
+    unpack8(qt, u);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      d[k] = scale * fast_exp2(fmaf(s[k], kLog2e, -lse2)) * ((s[k] - u[k]) - mu);
+    uint4 o;
+    o.x = pack_bf16(d[0], d[1]);
+    o.y = pack_bf16(d[2], d[3]);
+    o.z = pack_bf16(d[4], d[5]);
+    o.w = pack_bf16(d[6], d[7]);
+    nt_store16(dzr + q, o);
+  }
+}
+
+struct LogitsLayout {
+  size_t o_plan, o_klr, o_seg, o_racc, total;
+  LogitsLayout(int32_t B, int64_t T) {
+    size_t o = 0;
+    o_plan = o; o += PlanBlobLayout(B).bytes;
+    o_klr = o;  o = align_up(o + sizeof(float) * (size_t)(T > 0 ? T : 1), 256);
+    o_seg = o;  o = align_up(o + sizeof(double) * 4 * (size_t)B, 256);
+    o_racc = o; o = align_up(o + sizeof(double) * 4 * (size_t)B, 256);
+    total = o;
+  }
+};
+
+static int check_logits_problem(const adwin_opd_logits_problem* p) {
+  if (!p) return ADWIN_E_NULL;
+  if (p->struct_bytes != sizeof(adwin_opd_logits_problem)) return ADWIN_E_MODE;
+  int st = validate_ragged(p->T, p->B, p->offsets, p->window);
+  if (st != ADWIN_OK) return st;
+  if (p->V <= 0 || (p->V & 7)) return ADWIN_E_SHAPE;
+  if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
+  return ADWIN_OK;
+}
+
+}  // namespace adwin
+
+using namespace adwin;
+
+extern "C" int adwin_opd_logits_workspace_bytes(const adwin_opd_logits_problem* p, size_t* bytes) {
+  if (!bytes) return ADWIN_E_NULL;
+  int st = check_logits_problem(p);
+  if (st != ADWIN_OK) return st;
+  *bytes = LogitsLayout(p->B, p->T).total;
+  return ADWIN_OK;
+}
+
+extern "C" int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  int st = check_logits_problem(p);
+  if (st != ADWIN_OK) return st;
+  if (p->T > 0 && (!p->z_s || !p->z_t)) return ADWIN_E_NULL;
+  const uintptr_t al = (uintptr_t)p->z_s | (uintptr_t)p->z_t | (uintptr_t)p->dz;
+  if (al & 15) return ADWIN_E_ALIGN;
+  LogitsLayout L(p->B, p->T);
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total)
+    return ADWIN_E_WORKSPACE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  unsigned char* ws = (unsigned char*)workspace;
+
+  std::vector<unsigned char> blob;
+  HostPlan hp = make_host_plan(p->T, p->B, p->offsets, p->window, /*probe=*/0, p->reduction, &blob);
+  ADWIN_HIP_TRY(hipMemcpyAsync(ws + L.o_plan, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
+  DevicePlan pl = device_plan_at(ws + L.o_plan, p->B, nullptr, nullptr);
+  float* klr = (float*)(ws + L.o_klr);
+  double* seg = (double*)(ws + L.o_seg);
+
+  ADWIN_HIP_TRY(launch_fill_u32(p->status_dev, 1, 0u, stream));
+  if (p->T > 0) {
+    LogitsArgs a;
+    a.pl = pl; a.B = p->B; a.V = p->V;
+    a.z_s = (const uint4*)p->z_s; a.z_t = (const uint4*)p->z_t; a.ids = p->ids;
+    a.grad_scale = p->grad_scale;
+    a.kl = p->kl; a.c = p->c; a.dz = (uint4*)p->dz; a.klr = klr; a.status = p->status_dev;
+    logits_row_kernel<<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
+    ADWIN_HIP_TRY(hipGetLastError());
+  }
+  ADWIN_HIP_TRY(launch_segment_sums(pl, p->B, 0, klr, nullptr, seg, p->loss_prefix, nullptr, stream));
+  BatchArgs b{};
+  b.pl = pl; b.B = p->B; b.H = 0; b.probe = 0; b.zero_grad = 1; b.seg = seg;
+  b.up = nullptr; b.uf = nullptr; b.racc = (double*)(ws + L.o_racc);
+  b.rho_pooled = nullptr; b.rho_field = nullptr; b.batch = p->batch;
+  b.n_out = p->n_out; b.n_adm_out = p->n_adm_out; b.n_adm = hp.n_adm;
+  ADWIN_HIP_TRY(launch_alignment_and_batch(b, stream));
+  return ADWIN_OK;
+}

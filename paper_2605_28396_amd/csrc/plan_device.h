@@ -1,0 +1,60 @@
+// Per-call plan blob (host side) and the launchers of the small bookkeeping and
+// reduction kernels shared by the fused and the logits-given path.
+#pragma once
+#include <vector>
+
+#include "common.h"
+
+namespace adwin {
+
+// Byte offsets of the plan arrays inside one contiguous upload, a function of B only.
+struct PlanBlobLayout {
+  size_t o_offsets, o_comp_off, o_n, o_chunk_off, o_alpha_p, o_alpha_f, bytes;
+  explicit PlanBlobLayout(int32_t B) {
+    size_t o = 0;
+    o_offsets = o;   o = align_up(o + sizeof(int64_t) * (size_t)(B + 1), 16);
+    o_comp_off = o;  o = align_up(o + sizeof(int64_t) * (size_t)(B + 1), 16);
+    o_n = o;         o = align_up(o + sizeof(int32_t) * (size_t)B, 16);
+    o_chunk_off = o; o = align_up(o + sizeof(int32_t) * (size_t)(B + 1), 16);
+    o_alpha_p = o;   o = align_up(o + sizeof(float) * (size_t)B, 16);
+    o_alpha_f = o;   o = align_up(o + sizeof(float) * (size_t)B, 16);
+    bytes = align_up(o, 256);
+  }
+};
+
+// Integer bookkeeping of Sec. 4.1 (n_i, first computed row and first reduction chunk of
+// each rollout) and the per-rollout weights alpha^p_i, alpha^f_i of the chosen
+// reduction.  `blob` may be NULL when only the counts are wanted.
+HostPlan make_host_plan(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
+                        int probe, int reduction, std::vector<unsigned char>* blob);
+
+DevicePlan device_plan_at(unsigned char* ws_plan, int32_t B, int32_t* row_idx, int32_t* row_seq);
+
+// --- launchers (all asynchronous on `st`) ---------------------------------------------
+hipError_t launch_build_rows(const DevicePlan& pl, int32_t B, int64_t n_rows, int64_t n_pad,
+                             hipStream_t st);
+hipError_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
+
+// Per-rollout sums of KL (and of ||g_t||^2 when `rownorm` is given) over the window and
+// over the whole rollout; writes loss_prefix / loss_full.  seg is double [B][4].
+hipError_t launch_segment_sums(const DevicePlan& pl, int32_t B, int probe, const float* klr,
+                               const float* rownorm, double* seg, float* loss_prefix,
+                               float* loss_full, hipStream_t st);
+
+struct BatchArgs {
+  DevicePlan pl;
+  int32_t B;
+  int32_t H;            // 0: no gradient statistics (logits-given path)
+  int probe;
+  int zero_grad;        // grad_scale == 0: every alignment is defined as 0
+  const double* seg;    // [B][4]
+  const float* up;      // [B][H] pooled prefix sums (unweighted)
+  const float* uf;      // [B][H] pooled full-rollout sums
+  double* racc;         // [B][4] scratch
+  float* rho_pooled; float* rho_field; float* batch;
+  int32_t* n_out; int64_t* n_adm_out; int64_t n_adm;
+};
+hipError_t launch_alignment_and_batch(const BatchArgs& a, hipStream_t st);
+
+}  // namespace adwin

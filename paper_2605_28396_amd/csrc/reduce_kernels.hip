@@ -1,0 +1,281 @@
+// Plan expansion, fills and the deterministic segmented reductions over ragged
+// windows: per-window losses (Sec. 4.1) and prefix-vs-full alignment (Sec. 4.2).
+// No floating-point atomics: every sum has a fixed order.
+#include <cmath>
+#include <cstring>
+
+#include "device_utils.h"
+#include "plan_device.h"
+
+namespace adwin {
+
+// ---------------------------------------------------------------------------------------
+// host plan
+// ---------------------------------------------------------------------------------------
+HostPlan make_host_plan(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
+                        int probe, int reduction, std::vector<unsigned char>* blob) {
+  HostPlan hp;
+  hp.T = T;
+  hp.B = B;
+  PlanBlobLayout L(B);
+  unsigned char* base = nullptr;
+  if (blob) {
+    blob->assign(L.bytes, 0);
+    base = blob->data();
+  }
+  int64_t n_adm = 0;
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t len = offsets[i + 1] - offsets[i];
+    n_adm += window[i] < len ? (int64_t)window[i] : len;
+  }
+  int64_t comp = 0;
+  int64_t chunks = 0;
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t len = offsets[i + 1] - offsets[i];
+    const int64_t ni = window[i] < len ? (int64_t)window[i] : len;
+    const int64_t hi = probe ? len : ni;
+    if (base) {
+      ((int64_t*)(base + L.o_offsets))[i] = offsets[i];
+      ((int64_t*)(base + L.o_comp_off))[i] = comp;
+      ((int32_t*)(base + L.o_n))[i] = (int32_t)ni;
+      ((int32_t*)(base + L.o_chunk_off))[i] = (int32_t)chunks;
+      double ap = 0.0, af = 0.0;
+      if (reduction == ADWIN_RED_SEQ_MEAN) {
+        ap = ni > 0 ? 1.0 / ((double)B * (double)ni) : 0.0;
+        af = len > 0 ? 1.0 / ((double)B * (double)len) : 0.0;
+      } else if (reduction == ADWIN_RED_SUM) {
+        ap = af = 1.0;
+      } else {
+        ap = n_adm > 0 ? 1.0 / (double)n_adm : 0.0;
+        af = T > 0 ? 1.0 / (double)T : 0.0;
+      }
+      ((float*)(base + L.o_alpha_p))[i] = (float)ap;
+      ((float*)(base + L.o_alpha_f))[i] = (float)af;
+    }
+    comp += hi;
+    chunks += (hi + kChunkRows - 1) / kChunkRows;
+  }
+  if (base) {
+    ((int64_t*)(base + L.o_offsets))[B] = offsets[B];
+    ((int64_t*)(base + L.o_comp_off))[B] = comp;
+    ((int32_t*)(base + L.o_chunk_off))[B] = (int32_t)chunks;
+  }
+  hp.n_adm = n_adm;
+  hp.n_rows = comp;
+  hp.n_pad = (int64_t)align_up((size_t)comp, kTileTokens);
+  hp.n_chunks = chunks;
+  return hp;
+}
+
+DevicePlan device_plan_at(unsigned char* ws_plan, int32_t B, int32_t* row_idx, int32_t* row_seq) {
+  PlanBlobLayout L(B);
+  DevicePlan d;
+  d.offsets = (const int64_t*)(ws_plan + L.o_offsets);
+  d.comp_off = (const int64_t*)(ws_plan + L.o_comp_off);
+  d.n = (const int32_t*)(ws_plan + L.o_n);
+  d.chunk_off = (const int32_t*)(ws_plan + L.o_chunk_off);
+  d.alpha_p = (const float*)(ws_plan + L.o_alpha_p);
+  d.alpha_f = (const float*)(ws_plan + L.o_alpha_f);
+  d.row_idx = row_idx;
+  d.row_seq = row_seq;
+  return d;
+}
+
+// ---------------------------------------------------------------------------------------
+// small kernels
+// ---------------------------------------------------------------------------------------
+__global__ void build_rows_kernel(DevicePlan pl, int B, int64_t n_rows, int64_t n_pad) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_pad) return;
+  const int64_t rr = r < n_rows ? r : n_rows - 1;   // padding repeats the last computed row
+  const int i = last_le<int64_t>(pl.comp_off, B + 1, rr);
+  pl.row_idx[r] = (int32_t)(pl.offsets[i] + (rr - pl.comp_off[i]));
+  pl.row_seq[r] = i;
+}
+
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// Fixed-order block sum of up to 4 doubles per thread (256 threads).
+template <int K>
+__device__ __forceinline__ void block_sum256(double (&v)[K], double* sh /* [K][4] */) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    v[k] = wave_sum(v[k]);
+    if (lane == 0) sh[k * 4 + w] = v[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < K; ++k) v[k] = (sh[k * 4 + 0] + sh[k * 4 + 1]) + (sh[k * 4 + 2] + sh[k * 4 + 3]);
+  __syncthreads();
+}
+
+// One workgroup per rollout: sums of KL_t and ||g_t||^2 over the window and the rollout.
+__global__ __launch_bounds__(256) void segment_sums_kernel(DevicePlan pl, int probe,
+                                                           const float* __restrict__ klr,
+                                                           const float* __restrict__ rownorm,
+                                                           double* __restrict__ seg,
+                                                           float* loss_prefix, float* loss_full) {
+  __shared__ double sh[16];
+  const int i = blockIdx.x;
+  const int64_t len = pl.offsets[i + 1] - pl.offsets[i];
+  const int64_t ni = pl.n[i];
+  const int64_t hi = probe ? len : ni;
+  const int64_t r0 = pl.comp_off[i];
+  double v[4] = {0.0, 0.0, 0.0, 0.0};   // kl prefix, kl full, norm prefix, norm full
+  for (int64_t j = threadIdx.x; j < hi; j += 256) {
+    const double k = klr[r0 + j];
+    const double s = rownorm ? (double)rownorm[r0 + j] : 0.0;
+    v[1] += k;
+    v[3] += s;
+    if (j < ni) { v[0] += k; v[2] += s; }
+  }
+  block_sum256<4>(v, sh);
+  if (threadIdx.x == 0) {
+    seg[i * 4 + 0] = v[0];
+    seg[i * 4 + 1] = v[1];
+    seg[i * 4 + 2] = v[2];
+    seg[i * 4 + 3] = v[3];
+    if (loss_prefix) loss_prefix[i] = ni > 0 ? (float)(v[0] / (double)ni) : 0.f;
+    if (loss_full) loss_full[i] = (probe && len > 0) ? (float)(v[1] / (double)len) : 0.f;
+  }
+}
+
+// One workgroup per rollout: cosines from the pooled sums and the norm sums.
+__global__ __launch_bounds__(256) void rollout_alignment_kernel(BatchArgs a) {
+  __shared__ double sh[16];
+  const int i = blockIdx.x;
+  double v[3] = {0.0, 0.0, 0.0};
+  if (a.probe && !a.zero_grad) {
+    const float* up = a.up + (size_t)i * a.H;
+    const float* uf = a.uf + (size_t)i * a.H;
+    for (int h = threadIdx.x; h < a.H; h += 256) {
+      const double p = up[h], f = uf[h];
+      v[0] += p * f;
+      v[1] += p * p;
+      v[2] += f * f;
+    }
+  }
+  block_sum256<3>(v, sh);
+  if (threadIdx.x == 0) {
+    double rp = 0.0, rf = 0.0, okp = 0.0, okf = 0.0;
+    if (a.probe && !a.zero_grad) {
+      if (v[1] > 0.0 && v[2] > 0.0) { rp = v[0] / (sqrt(v[1]) * sqrt(v[2])); okp = 1.0; }
+      const double Sp = a.seg[i * 4 + 2], Sf = a.seg[i * 4 + 3];
+      if (Sp > 0.0 && Sf > 0.0) { rf = sqrt(Sp / Sf); okf = 1.0; }
+    }
+    a.racc[i * 4 + 0] = rp;
+    a.racc[i * 4 + 1] = okp;
+    a.racc[i * 4 + 2] = rf;
+    a.racc[i * 4 + 3] = okf;
+    if (a.rho_pooled) a.rho_pooled[i] = (float)rp;
+    if (a.rho_field) a.rho_field[i] = (float)rf;
+  }
+}
+
+// Single workgroup: batch objectives, micro (after aggregation) and macro (mean of
+// per-rollout) alignment, integer outputs.
+__global__ __launch_bounds__(256) void batch_kernel(BatchArgs a) {
+  __shared__ double sh[16];
+  const int B = a.B;
+  // batch objectives and field sums
+  double w[4] = {0.0, 0.0, 0.0, 0.0};   // L^p, L^f, macro pooled sum, macro pooled count
+  double f[4] = {0.0, 0.0, 0.0, 0.0};   // field: dot, |p|^2, |f|^2, unused
+  double mf[2] = {0.0, 0.0};            // macro field sum, count
+  for (int i = threadIdx.x; i < B; i += 256) {
+    const double ap = a.pl.alpha_p[i], af = a.pl.alpha_f[i];
+    w[0] += ap * a.seg[i * 4 + 0];
+    if (a.probe) {
+      w[1] += af * a.seg[i * 4 + 1];
+      w[2] += a.racc[i * 4 + 0] * a.racc[i * 4 + 1];
+      w[3] += a.racc[i * 4 + 1];
+      mf[0] += a.racc[i * 4 + 2] * a.racc[i * 4 + 3];
+      mf[1] += a.racc[i * 4 + 3];
+      const double Sp = a.seg[i * 4 + 2], Sf = a.seg[i * 4 + 3];
+      f[0] += ap * af * Sp;
+      f[1] += ap * ap * Sp;
+      f[2] += af * af * Sf;
+    }
+  }
+  block_sum256<4>(w, sh);
+  block_sum256<4>(f, sh);
+  block_sum256<2>(mf, sh);
+  // micro pooled: aggregate the weighted pooled gradients over the batch, then one cosine
+  double m[3] = {0.0, 0.0, 0.0};
+  if (a.probe && !a.zero_grad) {
+    for (int h = threadIdx.x; h < a.H; h += 256) {
+      double sp = 0.0, sf = 0.0;
+      for (int i = 0; i < B; ++i) {
+        sp += (double)a.pl.alpha_p[i] * (double)a.up[(size_t)i * a.H + h];
+        sf += (double)a.pl.alpha_f[i] * (double)a.uf[(size_t)i * a.H + h];
+      }
+      m[0] += sp * sf;
+      m[1] += sp * sp;
+      m[2] += sf * sf;
+    }
+  }
+  block_sum256<3>(m, sh);
+  if (a.n_out)
+    for (int i = threadIdx.x; i < B; i += 256) a.n_out[i] = a.pl.n[i];
+  if (threadIdx.x == 0) {
+    if (a.n_adm_out) *a.n_adm_out = a.n_adm;
+    if (a.batch) {
+      float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      o[0] = (float)w[0];
+      if (a.probe) {
+        o[1] = (float)w[1];
+        if (!a.zero_grad) {
+          if (m[1] > 0.0 && m[2] > 0.0) o[2] = (float)(m[0] / (sqrt(m[1]) * sqrt(m[2])));
+          if (f[1] > 0.0 && f[2] > 0.0) o[3] = (float)(f[0] / (sqrt(f[1]) * sqrt(f[2])));
+          if (w[3] > 0.0) o[4] = (float)(w[2] / w[3]);
+          if (mf[1] > 0.0) o[5] = (float)(mf[0] / mf[1]);
+        }
+      }
+      for (int k = 0; k < 8; ++k) a.batch[k] = o[k];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------
+hipError_t launch_build_rows(const DevicePlan& pl, int32_t B, int64_t n_rows, int64_t n_pad,
+                             hipStream_t st) {
+  if (n_rows <= 0) return hipSuccess;
+  const unsigned g = (unsigned)((n_pad + 255) / 256);
+  build_rows_kernel<<<g, 256, 0, st>>>(pl, B, n_rows, n_pad);
+  return hipGetLastError();
+}
+hipError_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t st) {
+  if (!p || n <= 0) return hipSuccess;
+  fill_f32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, n, v);
+  return hipGetLastError();
+}
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
+  if (!p || n <= 0) return hipSuccess;
+  fill_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, n, v);
+  return hipGetLastError();
+}
+hipError_t launch_segment_sums(const DevicePlan& pl, int32_t B, int probe, const float* klr,
+                               const float* rownorm, double* seg, float* loss_prefix,
+                               float* loss_full, hipStream_t st) {
+  segment_sums_kernel<<<(unsigned)B, 256, 0, st>>>(pl, probe, klr, rownorm, seg, loss_prefix,
+                                                   loss_full);
+  return hipGetLastError();
+}
+hipError_t launch_alignment_and_batch(const BatchArgs& a, hipStream_t st) {
+  rollout_alignment_kernel<<<(unsigned)a.B, 256, 0, st>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  batch_kernel<<<1, 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace adwin

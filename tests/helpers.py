@@ -1,0 +1,53 @@
+"""Shared parity helpers: tolerances (stated once, used by every GPU parity test) and
+conversion of the seeded inputs into what the oracle takes."""
+import numpy as np
+
+from paper_2605_28396_amd import synth
+
+# Tolerances: bf16 inputs, fp32 accumulation on the GPU, fp64 oracle.
+KL_REL = 1e-3          # |dKL| <= KL_REL * KL  (+ KL_ABS floor for tiny KL)
+KL_ABS = 1e-6
+C_REL = 1e-3           # |dc| <= C_REL * max(1, |c|)
+DH_ABS = 2e-3          # max |d dh| <= DH_ABS  and  <= DH_REL * max|dh_oracle|
+DH_REL = 2e-3
+RHO_ABS = 2e-3
+LOSS_REL = 1e-3
+BF16_ULP = 2.0 ** -8   # storage rounding of a bf16 output element, relative
+
+
+def oracle_inputs(p: dict) -> dict:
+    return {k: (v.cpu().numpy() if k == "ids" else synth.to_f64(v)) for k, v in p.items()}
+
+
+def assert_kl(got, want, what="kl"):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want)
+    tol = KL_REL * np.abs(want) + KL_ABS
+    bad = np.where(err > tol)[0]
+    assert len(bad) == 0, f"{what}: {len(bad)} rows off, worst {err.max():.3e} at {bad[:5]}"
+
+
+def assert_cost(got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want)
+    tol = C_REL * np.maximum(1.0, np.abs(want))
+    assert np.all(err <= tol), f"c: worst {err.max():.3e}"
+
+
+def assert_grad(got, want, what="dh", storage_ulp=0.0):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    scale = np.abs(want).max() if want.size else 0.0
+    err = np.abs(got - want)
+    tol = np.minimum(DH_ABS, DH_REL * scale) + storage_ulp * np.abs(want)
+    worst = (err - tol).max() if err.size else -1.0
+    assert worst <= 0, (f"{what}: max err {err.max():.3e} vs tol {DH_REL * scale:.3e} "
+                        f"(max|ref| {scale:.3e})")
+    # rows that must be exactly zero are exactly zero
+    zero_rows = ~np.any(want.reshape(want.shape[0], -1) != 0, axis=1)
+    assert not np.any(got.reshape(got.shape[0], -1)[zero_rows] != 0), f"{what}: non-zero outside windows"
+
+
+def assert_close_rel(got, want, rel, what):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want)
+    assert np.all(err <= rel * np.abs(want) + 1e-7), f"{what}: worst {err.max():.3e}"

@@ -1,0 +1,132 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, the
+host planner is bit-exact against the oracle, and argument errors are reported as
+status codes (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import adwin_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_28396_amd import binding
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "adwin_opd.h")).read()
+    declared = set(re.findall(r"\b(adwin_opd_[a-z_]+)\s*\(", header))
+    assert {"adwin_opd_fused", "adwin_opd_from_logits", "adwin_opd_plan_host",
+            "adwin_opd_workspace_bytes", "adwin_opd_logits_workspace_bytes",
+            "adwin_opd_strerror", "adwin_opd_version"} <= declared
+    for name in declared:
+        assert hasattr(B.lib, name), name
+        assert hasattr(B, name), f"binding lacks {name}"
+    assert B.adwin_opd_version() >= 100
+    assert "offsets" in B.adwin_opd_strerror(B.ADWIN_E_OFFSETS)
+
+
+def test_struct_layout_matches_header(B):
+    # field order and count of the ctypes mirror follow the header
+    header = open(os.path.join(ROOT, "include", "adwin_opd.h")).read()
+    for struct, cls in (("adwin_opd_problem", B.adwin_opd_problem),
+                        ("adwin_opd_logits_problem", B.adwin_opd_logits_problem)):
+        body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (struct, struct), header, re.S).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        names = []
+        for decl in body.split(";"):
+            decl = decl.strip()
+            if not decl:
+                continue
+            parts = decl.split(",")
+            names.append(re.findall(r"(\w+)\s*$", parts[0])[0])
+            names += [re.findall(r"(\w+)\s*$", x)[0] for x in parts[1:]]
+        assert names == [f[0] for f in cls._fields_], struct
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_plan_host_bit_exact_against_oracle(B, seed):
+    g = np.random.default_rng(seed)
+    nb = int(g.integers(1, 12))
+    lens = g.integers(0, 300, size=nb)
+    if seed % 4 == 0:
+        lens[g.integers(0, nb)] = 0
+    window = g.integers(0, 350, size=nb)
+    offsets = np.concatenate([[0], np.cumsum(lens)])
+    got = B.adwin_opd_plan_host(offsets, window)
+    want = O.plan(offsets, window)
+    assert got["n"].dtype == np.int32 and np.array_equal(got["n"], want["n"])
+    assert got["n_adm"] == want["n_adm"]
+    assert np.array_equal(got["rows"], want["rows"])
+    assert np.array_equal(got["row_seq"], want["row_seq"])
+
+
+def test_plan_host_error_codes(B):
+    def status(offsets, window, T=None):
+        try:
+            B.adwin_opd_plan_host(offsets, window, T=T)
+        except B.AdwinError as e:
+            return e.status
+        return 0
+    assert status([0, 5, 9], [3, 3]) == 0
+    assert status([1, 5, 9], [3, 3]) == B.ADWIN_E_OFFSETS
+    assert status([0, 5, 4], [3, 3]) == B.ADWIN_E_OFFSETS
+    assert status([0, 5, 9], [3, 3], T=10) == B.ADWIN_E_OFFSETS
+    assert status([0, 5, 9], [3, -1]) == B.ADWIN_E_WINDOW
+    assert status([0, 2 ** 31], [3]) == B.ADWIN_E_SHAPE
+
+
+def _problem(mod, **over):
+    B = mod
+    off = np.array([0, 40, 100], np.int64)
+    win = np.array([16, 100], np.int32)
+    p = B.adwin_opd_problem()
+    p.struct_bytes = C.sizeof(B.adwin_opd_problem)
+    p.T, p.B, p.V, p.H_s, p.H_t = 100, 2, 4096, 256, 384
+    p.offsets, p.window = off.ctypes.data, win.ctypes.data
+    p.mode, p.reduction, p.grad_scale, p.dh_dtype = 0, 0, 1.0, 1
+    p.h_s = p.h_t = p.W_s = p.W_t = 4096      # never dereferenced on the error paths below
+    for k, v in over.items():
+        setattr(p, k, v)
+    p._keep = (off, win)
+    return p
+
+
+def test_workspace_bytes_and_argument_errors_without_gpu(B):
+    p = _problem(B)
+    n = B.adwin_opd_workspace_bytes(p)
+    assert n > 0 and n % 256 == 0
+    bigger = B.adwin_opd_workspace_bytes(_problem(B, mode=1))
+    assert bigger >= n
+
+    def st(p, ws=0, ws_bytes=0):
+        return B.lib.adwin_opd_fused(C.byref(p), ws, ws_bytes, None)
+    assert st(_problem(B, V=4097)) == B.ADWIN_E_SHAPE
+    assert st(_problem(B, H_s=100)) == B.ADWIN_E_SHAPE
+    assert st(_problem(B, H_t=0)) == B.ADWIN_E_SHAPE
+    assert st(_problem(B, B=0)) == B.ADWIN_E_SHAPE
+    assert st(_problem(B, mode=7)) == B.ADWIN_E_MODE
+    assert st(_problem(B, reduction=5)) == B.ADWIN_E_MODE
+    assert st(_problem(B, dh_dtype=9)) == B.ADWIN_E_MODE
+    assert st(_problem(B, struct_bytes=8)) == B.ADWIN_E_MODE
+    assert st(_problem(B, W_s=None)) == B.ADWIN_E_NULL
+    assert st(_problem(B, h_s=4100)) == B.ADWIN_E_ALIGN
+    assert st(_problem(B)) == B.ADWIN_E_WORKSPACE                  # NULL workspace
+    assert st(_problem(B), 4096 + 8, n) == B.ADWIN_E_WORKSPACE     # misaligned
+    assert st(_problem(B), 4096, n - 256) == B.ADWIN_E_WORKSPACE   # too small
+    assert B.lib.adwin_opd_fused(None, 0, 0, None) == B.ADWIN_E_NULL
+
+    lp = B.adwin_opd_logits_problem()
+    lp.struct_bytes = C.sizeof(B.adwin_opd_logits_problem)
+    off = np.array([0, 40, 100], np.int64); win = np.array([16, 100], np.int32)
+    lp.T, lp.B, lp.V = 100, 2, 4096
+    lp.offsets, lp.window = off.ctypes.data, win.ctypes.data
+    assert B.adwin_opd_logits_workspace_bytes(lp) > 0
+    lp.V = 4095
+    assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_SHAPE
