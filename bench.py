@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X.
+
+A "step" is one pass of the whole path (plan upload, both logit passes, gradient
+contraction, scatter and window reductions) over one batch of seeded synthetic rollouts
+already resident in HBM.  Prints ONE JSON line: distilled tokens/s, a roofline object for
+the dominant kernel (durations from HIP events on the launch stream, via the library's
+profiling entry point) and the fp64 oracle timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def _cpu_threads() -> int:
+    try:
+        from threadpoolctl import threadpool_info
+        n = [i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"]
+        if n:
+            return int(max(n))
+    except Exception:
+        pass
+    return len(os.sched_getaffinity(0))
+
+
+def _oracle_fused_baseline(w, prob, k_rows):
+    """fp64 oracle on a seeded sample of computed rows of the same workload."""
+    import numpy as np
+    from oracle import adwin_oracle as O
+    from paper_2605_28396_amd import synth
+    rows = synth.sample_rows(w, k_rows)
+    import torch
+    idx = torch.from_numpy(rows).to(prob["h_s"].device)
+    Hs = synth.to_f64(prob["h_s"][idx])
+    Ht = synth.to_f64(prob["h_t"][idx])
+    Ws = synth.to_f64(prob["W_s"])
+    Wt = synth.to_f64(prob["W_t"])
+    ids = prob["ids"][idx].cpu().numpy()
+    t0 = time.perf_counter()
+    kl, c, g = O.rows_terms(Hs, Ht, Ws, Wt, ids)
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) / dt, "unit": "tokens/s", "cores": _cpu_threads(), "kind": "oracle",
+            "sample": f"{len(rows)} seeded computed rows of this workload (full vocabulary, fp64, "
+                      f"numpy/BLAS inner products), {dt:.1f} s"}, (rows, kl, c, g)
+
+
+def _oracle_logits_baseline(w, prob, k_rows):
+    import numpy as np
+    from oracle import adwin_oracle as O
+    from paper_2605_28396_amd import synth
+    import torch
+    rows = synth.sample_rows(w, k_rows)
+    idx = torch.from_numpy(rows).to(prob["z_s"].device)
+    zs = synth.to_f64(prob["z_s"][idx])
+    zt = synth.to_f64(prob["z_t"][idx])
+    ids = prob["ids"][idx].cpu().numpy()
+    t0 = time.perf_counter()
+    kl = np.zeros(len(rows))
+    for r in range(len(rows)):
+        kl[r] = O.token_kl(zs[r], zt[r])
+        O.token_cost(zs[r], zt[r], int(ids[r]))
+        O.token_dz(zs[r], zt[r])
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(rows)} seeded admitted rows of this workload (fp64, numpy), {dt:.1f} s"}, (rows, kl)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="strong_to_weak",
+                    choices=["tiny", "logits_given", "strong_to_weak", "same_family", "probe_alignment"])
+    ap.add_argument("--cpu-rows", type=int, default=256, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--dh-dtype", default="f32", choices=["f32", "bf16"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2605_28396_amd import binding as B, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = synth.workload(args.workload)
+    lens = np.diff(w.offsets)
+    n = np.minimum(w.window.astype(np.int64), lens)
+    n_adm = int(n.sum())
+    logits = w.name == "logits_given"
+
+    if logits:
+        prob = synth.logits_problem(w, dev)
+        call = B.LogitsCall(prob["z_s"], prob["z_t"], prob["ids"], w.offsets, w.window,
+                            reduction=B.ADWIN_RED_SEQ_MEAN)
+        profile = B.adwin_opd_from_logits_profile
+        tokens = n_adm
+    else:
+        prob = synth.hidden_problem(w, dev)
+        call = B.FusedCall(prob["h_s"], prob["h_t"], prob["W_s"], prob["W_t"], prob["ids"],
+                           w.offsets, w.window, mode=w.mode, reduction=B.ADWIN_RED_SEQ_MEAN,
+                           dh_dtype=B.ADWIN_DT_BF16 if args.dh_dtype == "bf16" else B.ADWIN_DT_F32)
+        profile = B.adwin_opd_fused_profile
+        tokens = w.T if w.mode == synth.MODE_PREFIX_AND_FULL else n_adm
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        st = call.run()
+        assert st == 0, B.adwin_opd_strerror(st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st = call.run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert st == 0, B.adwin_opd_strerror(st)
+    assert int(call.out["status_dev"][0]) == 0
+    ms_per_step = dt / args.steps * 1e3
+    value = tokens / (dt / args.steps)
+
+    # per-kernel durations from HIP events on the launch stream (same launches, profiled)
+    phases = [profile(call) for _ in range(max(1, min(3, args.steps)))]
+    ph = {k: float(np.mean([p[k] for p in phases])) for k in phases[0]}
+
+    if logits:
+        V = w.V
+        alg_bytes = 6.0 * V * n_adm + 2.0 * V * (w.T - n_adm)      # read z_s,z_t + write dz; zero rows
+        ach = alg_bytes / (ph["stats"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "logits_row_kernel", "achieved": ach, "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                    "launch_ms": ph["stats"], "alg_bytes_per_launch": alg_bytes}
+        extra = {}
+    else:
+        V, Hs, Ht = w.V, w.H_s, w.H_t
+        f_stats = 2.0 * V * (Hs + Ht) * tokens              # one full-vocabulary sweep of both heads
+        ach = f_stats / (ph["stats"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "logit_pass_kernel<stats>", "achieved": ach,
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                    "traffic": None, "launch_ms": ph["stats"], "alg_flops_per_launch": f_stats}
+        f_alg = 2.0 * V * (2 * Hs + Ht) * tokens            # student fwd + teacher fwd + dz W_s
+        f_exec = 2.0 * V * (3 * Hs + 2 * Ht) * tokens       # two-pass design recomputes the logits
+        t_s = ms_per_step * 1e-3
+        extra = {"roofline_call": {
+            "alg_tflops": f_alg / t_s / 1e12, "alg_frac": f_alg / t_s / 1e12 / PEAK_BF16_TFLOPS,
+            "exec_tflops": f_exec / t_s / 1e12, "exec_frac": f_exec / t_s / 1e12 / PEAK_BF16_TFLOPS,
+            "dz_pass_tflops": f_stats / (ph["dz"] * 1e-3) / 1e12,
+            "grad_gemm_tflops": 2.0 * V * Hs * tokens / (ph["grad"] * 1e-3) / 1e12}}
+
+    cpu = None
+    if args.cpu_rows > 0:
+        if logits:
+            cpu, _ = _oracle_logits_baseline(w, prob, args.cpu_rows)
+        else:
+            cpu, _ = _oracle_fused_baseline(w, prob, args.cpu_rows)
+
+    line = {
+        "metric": "distilled tokens/sec (fused fwd+bwd reverse-KL, V=151936) + % roofline",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "rollouts": w.B, "packed_rows": w.T, "computed_rows": tokens,
+                   "V": w.V, "H_s": w.H_s, "H_t": w.H_t,
+                   "mode": "prefix_and_full" if w.mode else "prefix_only"},
+        "roofline": roofline, "cpu_baseline": cpu, "phase_ms": ph,
+    }
+    line.update(extra)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -177,6 +177,28 @@ int adwin_opd_logits_workspace_bytes(const adwin_opd_logits_problem* p, size_t* 
 int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Profiling variants: identical work and results, but every kernel launch is bracketed
+ * with HIP events on the stream, the call waits for the stream to drain, and the summed
+ * milliseconds per phase are written to phase_ms (host float[ADWIN_N_PHASES]).  Phases
+ * follow the steps of the path: setup (plan upload, W_s transpose), full-vocabulary
+ * statistics pass (Eq. 2 terms), per-row merge (KL_t, c_t), logit-gradient pass (Eq. 4 in
+ * expectation), gradient contraction with W_s, and scatter plus window reductions
+ * (Sec. 4.1 losses, Sec. 4.2 alignment).  The logits-given variant reports its single
+ * streaming kernel under ADWIN_PHASE_STATS and the reductions under ADWIN_PHASE_REDUCE.
+ */
+#define ADWIN_PHASE_SETUP   0
+#define ADWIN_PHASE_STATS   1
+#define ADWIN_PHASE_MERGE   2
+#define ADWIN_PHASE_DZ      3
+#define ADWIN_PHASE_GRAD    4
+#define ADWIN_PHASE_REDUCE  5
+#define ADWIN_N_PHASES      6
+int adwin_opd_fused_profile(const adwin_opd_problem* p, void* workspace, size_t workspace_bytes,
+                            void* hip_stream, float* phase_ms);
+int adwin_opd_from_logits_profile(const adwin_opd_logits_problem* p, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream, float* phase_ms);
+
 #ifdef __cplusplus
 }
 #endif

@@ -76,10 +76,19 @@ def _load() -> C.CDLL:
     lib.adwin_opd_from_logits.restype = C.c_int
     lib.adwin_opd_from_logits.argtypes = [C.POINTER(adwin_opd_logits_problem), C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+    lib.adwin_opd_fused_profile.restype = C.c_int
+    lib.adwin_opd_fused_profile.argtypes = [C.POINTER(adwin_opd_problem), C.c_void_p, C.c_size_t,
+                                            C.c_void_p, C.POINTER(C.c_float)]
+    lib.adwin_opd_from_logits_profile.restype = C.c_int
+    lib.adwin_opd_from_logits_profile.argtypes = [C.POINTER(adwin_opd_logits_problem), C.c_void_p,
+                                                  C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
     return lib
 
 
 lib = _load()
+
+ADWIN_N_PHASES = 6
+PHASE_NAMES = ("setup", "stats", "merge", "dz", "grad", "reduce")
 
 
 class AdwinError(RuntimeError):
@@ -193,6 +202,21 @@ class FusedCall:
     def run(self, stream=None) -> int:
         return int(lib.adwin_opd_fused(C.byref(self.p), self._ws_ptr(), self.workspace_bytes,
                                        _stream_handle(stream)))
+
+
+def adwin_opd_fused_profile(call: "FusedCall", stream=None) -> dict:
+    """Runs the call with per-phase HIP-event timing; returns {phase name: ms}."""
+    ms = (C.c_float * ADWIN_N_PHASES)()
+    _check(lib.adwin_opd_fused_profile(C.byref(call.p), call._ws_ptr(), call.workspace_bytes,
+                                       _stream_handle(stream), ms))
+    return dict(zip(PHASE_NAMES, [float(x) for x in ms]))
+
+
+def adwin_opd_from_logits_profile(call: "LogitsCall", stream=None) -> dict:
+    ms = (C.c_float * ADWIN_N_PHASES)()
+    _check(lib.adwin_opd_from_logits_profile(C.byref(call.p), call._ws_ptr(), call.workspace_bytes,
+                                             _stream_handle(stream), ms))
+    return dict(zip(PHASE_NAMES, [float(x) for x in ms]))
 
 
 def adwin_opd_workspace_bytes(p: adwin_opd_problem) -> int:

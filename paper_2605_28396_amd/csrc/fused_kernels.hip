@@ -649,8 +649,8 @@ extern "C" int adwin_opd_workspace_bytes(const adwin_opd_problem* p, size_t* byt
   return ADWIN_OK;
 }
 
-extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size_t workspace_bytes,
-                               void* hip_stream) {
+static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t workspace_bytes,
+                      void* hip_stream, PhaseTimer* timer) {
   int st = check_problem(p);
   if (st != ADWIN_OK) return st;
   if (!p->W_s || !p->W_t) return ADWIN_E_NULL;
@@ -668,6 +668,9 @@ extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size
   unsigned char* ws = (unsigned char*)workspace;
   ADWIN_HIP_TRY(ensure_lds_opt_in());
 
+  PhaseScope* scope = new PhaseScope(timer, ADWIN_PHASE_SETUP);
+  struct ScopeGuard { PhaseScope*& s; ~ScopeGuard() { delete s; } } guard{scope};
+  auto phase = [&](int ph) { delete scope; scope = new PhaseScope(timer, ph); };
   ADWIN_HIP_TRY(hipMemcpyAsync(ws + L.o_plan, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
   DevicePlan pl = device_plan_at(ws + L.o_plan, p->B, (int32_t*)(ws + L.o_row_idx),
                                  (int32_t*)(ws + L.o_row_seq));
@@ -706,12 +709,14 @@ extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size
     la.lse2 = (const float*)(ws + L.o_lse2); la.mu = (const float*)(ws + L.o_mu);
     la.slab = (__bf16*)(ws + L.o_slab); la.Vp = L.Vp; la.slab_row0 = 0;
     // pass 1 over all token tiles
+    phase(ADWIN_PHASE_STATS);
     {
       la.tile0 = 0; la.n_tiles = n_tiles; la.strips = L.strips;
       const int groups = (n_tiles + 3) / 4;
       logit_pass_kernel<false><<<(unsigned)(groups * 4 * L.strips), 256, kLogitLds, stream>>>(la);
       ADWIN_HIP_TRY(hipGetLastError());
     }
+    phase(ADWIN_PHASE_MERGE);
     {
       MergeArgs m;
       m.part = la.part; m.strips = L.strips; m.n_pad = n_pad; m.n_rows = hp.n_rows;
@@ -731,8 +736,10 @@ extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size
       la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
       la.strips = strips2; la.slab_row0 = r0;
       const int groups = (la.n_tiles + 3) / 4;
+      phase(ADWIN_PHASE_DZ);
       logit_pass_kernel<true><<<(unsigned)(groups * 4 * strips2), 256, kLogitLds, stream>>>(la);
       ADWIN_HIP_TRY(hipGetLastError());
+      phase(ADWIN_PHASE_GRAD);
       GradArgs ga;
       ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.Vp = L.Vp;
       ga.g = gws; ga.n_pad = n_pad; ga.H = p->H_s; ga.slab_row0 = r0;
@@ -742,6 +749,7 @@ extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size
     }
   }
   // finalize over every packed row (also zero-fills rows outside the windows)
+  phase(ADWIN_PHASE_REDUCE);
   if (p->T > 0) {
     FinalizeArgs f;
     f.pl = pl; f.B = p->B; f.T = p->T; f.probe = probe;
@@ -772,5 +780,20 @@ extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size
   b.rho_pooled = p->rho_pooled; b.rho_field = p->rho_field; b.batch = p->batch;
   b.n_out = p->n_out; b.n_adm_out = p->n_adm_out; b.n_adm = hp.n_adm;
   ADWIN_HIP_TRY(launch_alignment_and_batch(b, stream));
+  return ADWIN_OK;
+}
+
+extern "C" int adwin_opd_fused(const adwin_opd_problem* p, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+  return fused_impl(p, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+extern "C" int adwin_opd_fused_profile(const adwin_opd_problem* p, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream, float* phase_ms) {
+  if (!phase_ms) return ADWIN_E_NULL;
+  PhaseTimer timer((hipStream_t)hip_stream);
+  int st = fused_impl(p, workspace, workspace_bytes, hip_stream, &timer);
+  if (st != ADWIN_OK) return st;
+  ADWIN_HIP_TRY(timer.collect(phase_ms, ADWIN_N_PHASES));
   return ADWIN_OK;
 }

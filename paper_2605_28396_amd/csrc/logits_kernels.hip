@@ -175,8 +175,8 @@ extern "C" int adwin_opd_logits_workspace_bytes(const adwin_opd_logits_problem* 
   return ADWIN_OK;
 }
 
-extern "C" int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* workspace,
-                                     size_t workspace_bytes, void* hip_stream) {
+static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_t workspace_bytes,
+                       void* hip_stream, PhaseTimer* timer) {
   int st = check_logits_problem(p);
   if (st != ADWIN_OK) return st;
   if (p->T > 0 && (!p->z_s || !p->z_t)) return ADWIN_E_NULL;
@@ -202,9 +202,11 @@ extern "C" int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* wo
     a.z_s = (const uint4*)p->z_s; a.z_t = (const uint4*)p->z_t; a.ids = p->ids;
     a.grad_scale = p->grad_scale;
     a.kl = p->kl; a.c = p->c; a.dz = (uint4*)p->dz; a.klr = klr; a.status = p->status_dev;
+    PhaseScope scope(timer, ADWIN_PHASE_STATS);
     logits_row_kernel<<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
     ADWIN_HIP_TRY(hipGetLastError());
   }
+  PhaseScope scope(timer, ADWIN_PHASE_REDUCE);
   ADWIN_HIP_TRY(launch_segment_sums(pl, p->B, 0, klr, nullptr, seg, p->loss_prefix, nullptr, stream));
   BatchArgs b{};
   b.pl = pl; b.B = p->B; b.H = 0; b.probe = 0; b.zero_grad = 1; b.seg = seg;
@@ -212,5 +214,21 @@ extern "C" int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* wo
   b.rho_pooled = nullptr; b.rho_field = nullptr; b.batch = p->batch;
   b.n_out = p->n_out; b.n_adm_out = p->n_adm_out; b.n_adm = hp.n_adm;
   ADWIN_HIP_TRY(launch_alignment_and_batch(b, stream));
+  return ADWIN_OK;
+}
+
+extern "C" int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* workspace,
+                                     size_t workspace_bytes, void* hip_stream) {
+  return logits_impl(p, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+extern "C" int adwin_opd_from_logits_profile(const adwin_opd_logits_problem* p, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream,
+                                             float* phase_ms) {
+  if (!phase_ms) return ADWIN_E_NULL;
+  PhaseTimer timer((hipStream_t)hip_stream);
+  int st = logits_impl(p, workspace, workspace_bytes, hip_stream, &timer);
+  if (st != ADWIN_OK) return st;
+  ADWIN_HIP_TRY(timer.collect(phase_ms, ADWIN_N_PHASES));
   return ADWIN_OK;
 }

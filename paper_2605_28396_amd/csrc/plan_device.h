@@ -57,4 +57,26 @@ struct BatchArgs {
 };
 hipError_t launch_alignment_and_batch(const BatchArgs& a, hipStream_t st);
 
+// Optional per-phase timing with HIP events on the caller's stream (profiling entry
+// points only).  begin()/end() bracket one launch; collect() waits and sums per phase.
+class PhaseTimer {
+ public:
+  explicit PhaseTimer(hipStream_t st) : st_(st) {}
+  ~PhaseTimer();
+  hipError_t begin(int phase);
+  hipError_t end();
+  hipError_t collect(float* phase_ms, int n_phases);
+ private:
+  struct Span { int phase; hipEvent_t a, b; };
+  hipStream_t st_;
+  std::vector<Span> spans_;
+};
+
+// RAII helper: no-op when the timer is null.
+struct PhaseScope {
+  PhaseTimer* t;
+  PhaseScope(PhaseTimer* timer, int phase) : t(timer) { if (t) t->begin(phase); }
+  ~PhaseScope() { if (t) t->end(); }
+};
+
 }  // namespace adwin

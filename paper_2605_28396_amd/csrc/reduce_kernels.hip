@@ -278,4 +278,39 @@ hipError_t launch_alignment_and_batch(const BatchArgs& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// phase timer
+// ---------------------------------------------------------------------------------------
+PhaseTimer::~PhaseTimer() {
+  for (auto& s : spans_) {
+    if (s.a) (void)hipEventDestroy(s.a);
+    if (s.b) (void)hipEventDestroy(s.b);
+  }
+}
+hipError_t PhaseTimer::begin(int phase) {
+  Span s{phase, nullptr, nullptr};
+  hipError_t e = hipEventCreate(&s.a);
+  if (e != hipSuccess) return e;
+  e = hipEventCreate(&s.b);
+  if (e != hipSuccess) { (void)hipEventDestroy(s.a); return e; }
+  spans_.push_back(s);
+  return hipEventRecord(s.a, st_);
+}
+hipError_t PhaseTimer::end() {
+  if (spans_.empty()) return hipSuccess;
+  return hipEventRecord(spans_.back().b, st_);
+}
+hipError_t PhaseTimer::collect(float* phase_ms, int n_phases) {
+  hipError_t e = hipStreamSynchronize(st_);
+  if (e != hipSuccess) return e;
+  for (int k = 0; k < n_phases; ++k) phase_ms[k] = 0.f;
+  for (auto& s : spans_) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, s.a, s.b);
+    if (e != hipSuccess) return e;
+    if (s.phase >= 0 && s.phase < n_phases) phase_ms[s.phase] += ms;
+  }
+  return hipSuccess;
+}
+
 }  // namespace adwin
