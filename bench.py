@@ -76,6 +76,25 @@ def _oracle_logits_baseline(w, prob, k_rows):
             "sample": f"{len(rows)} seeded admitted rows of this workload (fp64, numpy), {dt:.1f} s"}, (rows, kl)
 
 
+def _measured_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
+    (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter
+    reads for the 1 GiB copy kernel in the same run), or None."""
+    path = os.path.join(ROOT, "profiles", "logits_given_hbm_counters.txt")
+    try:
+        vals = {}
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[1] in ("FETCH_SIZE", "WRITE_SIZE"):
+                vals[(f[0], f[1])] = float(f[3])
+        gib = 1048576.0
+        rd = vals[(kernel, "FETCH_SIZE")] * gib / vals[("adwin::copy_kernel", "FETCH_SIZE")]
+        wr = vals[(kernel, "WRITE_SIZE")] * gib / vals[("adwin::copy_kernel", "WRITE_SIZE")]
+        return (rd + wr) * 1024.0
+    except Exception:
+        return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,7 +160,8 @@ def main() -> int:
         alg_bytes = 6.0 * V * n_adm + 2.0 * V * (w.T - n_adm)      # read z_s,z_t + write dz; zero rows
         ach = alg_bytes / (ph["stats"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "logits_row_kernel", "achieved": ach, "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                    "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                    "traffic": _measured_traffic("adwin::logits_row_kernel"),
                     "launch_ms": ph["stats"], "alg_bytes_per_launch": alg_bytes}
         extra = {}
     else:
@@ -177,6 +197,9 @@ def main() -> int:
                    "mode": "prefix_and_full" if w.mode else "prefix_only"},
         "roofline": roofline, "cpu_baseline": cpu, "phase_ms": ph,
     }
+    line["ceilings"] = {"copy_GBps": B.adwin_opd_ceiling_copy(), "mfma_bf16_TFLOPs": B.adwin_opd_ceiling_mfma(),
+                        "note": "measured on this box: streaming copy (read+write bytes) and a "
+                                "register-resident 32x32x16 bf16 MFMA loop"}
     line.update(extra)
     print(json.dumps(line))
     return 0

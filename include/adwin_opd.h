@@ -199,6 +199,18 @@ int adwin_opd_fused_profile(const adwin_opd_problem* p, void* workspace, size_t 
 int adwin_opd_from_logits_profile(const adwin_opd_logits_problem* p, void* workspace,
                                   size_t workspace_bytes, void* hip_stream, float* phase_ms);
 
+/*
+ * Measured ceilings of the machine, for quoting roofline fractions against what the box
+ * delivers as well as against the published peaks.  Both synchronise.
+ *   copy: streams `bytes` (multiple of 16; device pointers, 16-byte aligned) from src to
+ *         dst `reps` times; *ms (host) = average milliseconds per copy.
+ *   mfma: register-resident v_mfma_f32_32x32x16_bf16 loop on every CU; `scratch` is at
+ *         least 4 bytes of device memory; *tflops (host) = achieved dense bf16 TFLOP/s.
+ */
+int adwin_opd_ceiling_copy(const void* src, void* dst, size_t bytes, int reps, void* hip_stream,
+                           float* ms);
+int adwin_opd_ceiling_mfma(void* scratch, int iters, void* hip_stream, float* tflops);
+
 #ifdef __cplusplus
 }
 #endif

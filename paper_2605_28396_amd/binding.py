@@ -82,6 +82,11 @@ def _load() -> C.CDLL:
     lib.adwin_opd_from_logits_profile.restype = C.c_int
     lib.adwin_opd_from_logits_profile.argtypes = [C.POINTER(adwin_opd_logits_problem), C.c_void_p,
                                                   C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
+    lib.adwin_opd_ceiling_copy.restype = C.c_int
+    lib.adwin_opd_ceiling_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p,
+                                           C.POINTER(C.c_float)]
+    lib.adwin_opd_ceiling_mfma.restype = C.c_int
+    lib.adwin_opd_ceiling_mfma.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_float)]
     return lib
 
 
@@ -285,3 +290,21 @@ def adwin_opd_from_logits(z_s, z_t, ids, offsets, window, stream=None, **kw) -> 
     call = LogitsCall(z_s, z_t, ids, offsets, window, **kw)
     _check(call.run(stream))
     return call.out
+
+
+def adwin_opd_ceiling_copy(nbytes: int = 1 << 30, reps: int = 10, stream=None) -> float:
+    """Measured streaming-copy rate in GB/s (read + write bytes)."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").zero_()
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ms = C.c_float(0)
+    _check(lib.adwin_opd_ceiling_copy(_ptr(src), _ptr(dst), nbytes, reps, _stream_handle(stream),
+                                      C.byref(ms)))
+    return 2.0 * nbytes / (ms.value * 1e-3) / 1e9
+
+
+def adwin_opd_ceiling_mfma(iters: int = 20000, stream=None) -> float:
+    """Measured register-resident bf16 MFMA rate in TFLOP/s."""
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    tf = C.c_float(0)
+    _check(lib.adwin_opd_ceiling_mfma(_ptr(scratch), iters, _stream_handle(stream), C.byref(tf)))
+    return float(tf.value)

@@ -10,7 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadwin_opd.so")
-SOURCES = ["host_plan.cpp", "reduce_kernels.hip", "logits_kernels.hip", "fused_kernels.hip"]
+SOURCES = ["host_plan.cpp", "reduce_kernels.hip", "logits_kernels.hip", "fused_kernels.hip",
+           "ceilings.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
