@@ -2,6 +2,7 @@
 // reverse KL (Eq. 2 at token level), sampled cost c_t (Sec. 2.3) and the logit gradient
 // p_s((z_s - z_t) - mu) (Eq. 4 in expectation, App. A.1) on the admitted rows
 // (Sec. 4.1), streamed from HBM.  One workgroup per packed row; two sweeps over the row.
+#include <utility>
 #include <vector>
 
 #include "device_utils.h"
@@ -141,6 +142,199 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Row-resident variant.  One 256-thread workgroup (one wave per SIMD, up to 512 registers
+// per lane) per packed row keeps the whole row pair on chip between the two sweeps: z_s in
+// registers, z_t partly in LDS and partly in registers, so HBM sees each logit once
+// (4 B read + 2 B written per element).  Rows longer than kResVec vectors re-read the
+// excess from memory.
+// ---------------------------------------------------------------------------------------
+constexpr int kResThreads = 256;
+constexpr int kResIters = 75;                      // vectors of 8 logits per thread
+constexpr int kResTLds = 39;                       // of which z_t vectors parked in LDS
+constexpr int kResTReg = kResIters - kResTLds;     // and in registers
+constexpr int kResBatch = 5;                       // iterations whose loads are issued together
+constexpr int kResVec = kResIters * kResThreads;   // 19,200 vectors = 153,600 logits
+constexpr int kResLdsBytes = kResTLds * kResThreads * 16 + 256;
+
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+// Calls f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index
+// is a compile-time constant, so that register arrays are never indexed dynamically.
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+struct RowStats { float ms, Zs, A, mt, Zt; };
+
+__device__ __forceinline__ float max8(const float (&v)[8]) {
+  return fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+}
+
+__device__ __forceinline__ void stats_update(RowStats& r, const uint4& qs, const uint4& qt) {
+  float s[8], u[8];
+  unpack8(qs, s);
+  unpack8(qt, u);
+  const float mx = max8(s), mxt = max8(u);
+  if (mx > r.ms) {
+    const float sc = fast_exp2((r.ms - mx) * kLog2e);
+    r.Zs *= sc; r.A *= sc; r.ms = mx;
+  }
+  if (mxt > r.mt) { r.Zt *= fast_exp2((r.mt - mxt) * kLog2e); r.mt = mxt; }
+  const float ms2 = r.ms * kLog2e, mt2 = r.mt * kLog2e;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const float e = fast_exp2(fmaf(s[k], kLog2e, -ms2));
+    r.Zs += e;
+    r.A = fmaf(e, s[k] - u[k], r.A);
+    r.Zt += fast_exp2(fmaf(u[k], kLog2e, -mt2));
+  }
+}
+
+// dz = sgn * 2^(z_s*log2e - lse2s) * ((z_s - z_t) - mu), with |scale| folded into lse2s
+__device__ __forceinline__ uint4 dz_vector(const uint4& qs, const uint4& qt, float lse2s, float sgn,
+                                           float neg_sgn_mu) {
+  float s[8], u[8], d[8];
+  unpack8(qs, s);
+  unpack8(qt, u);
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    d[k] = fast_exp2(fmaf(s[k], kLog2e, -lse2s)) * fmaf(s[k] - u[k], sgn, neg_sgn_mu);
+  uint4 o;
+  o.x = pack_bf16(d[0], d[1]);
+  o.y = pack_bf16(d[2], d[3]);
+  o.z = pack_bf16(d[4], d[5]);
+  o.w = pack_bf16(d[6], d[7]);
+  return o;
+}
+
+__global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(LogitsArgs a) {
+  extern __shared__ __align__(16) char lds_raw[];
+  uint4* lds_t = (uint4*)lds_raw;
+  float* sh = (float*)(lds_raw + kResTLds * kResThreads * 16);   // [5][4] + broadcast [2]
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int nvec = a.V >> 3;
+  const int i = last_le<int64_t>(a.pl.offsets, a.B + 1, t);
+  const int64_t j = t - a.pl.offsets[i];
+  uint4* dzr = a.dz ? a.dz + t * nvec : nullptr;
+  if (j >= a.pl.n[i]) {
+    if (dzr) {
+      const uint4 z = {0u, 0u, 0u, 0u};
+      for (int q = tid; q < nvec; q += kResThreads) nt_store16(dzr + q, z);
+    }
+    if (tid == 0) {
+      if (a.kl) a.kl[t] = 0.f;
+      if (a.c) a.c[t] = 0.f;
+    }
+    return;
+  }
+  const uint4* zs = a.z_s + t * nvec;
+  const uint4* zt = a.z_t + t * nvec;
+  // bf16 -3.39e38 in every lane: neutral for max, exp and the difference
+  const uint4 neutral = {0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu, 0xff7fff7fu};
+
+  uint4 rs[kResIters];
+  uint4 rt[kResTReg];
+  RowStats st = {kNegBig, 0.f, 0.f, kNegBig, 0.f};
+  // ---- sweep 1: load the row pair once, keep it, accumulate the statistics ------------
+  // Loads are issued one batch (kResBatch iterations) ahead of the arithmetic so that the
+  // single wave per SIMD always has 2*kResBatch 16-byte loads in flight.  They are
+  // unconditional (out-of-range lanes fetch the row's last vector and use a neutral value)
+  // so that the number of loads in flight is the same on every path and the compiler can
+  // wait for exactly the ones it needs.
+  uint4 tb[2][kResBatch];
+  const int last = nvec - 1;
+  auto issue = [&](auto b_c) {
+    constexpr int b = decltype(b_c)::value;
+    if constexpr (b < kResIters / kResBatch) {
+      static_for<kResBatch>([&](auto g_c) {
+        constexpr int g = decltype(g_c)::value;
+        int q = (b * kResBatch + g) * kResThreads + tid;
+        q = q < last ? q : last;
+        rs[b * kResBatch + g] = zs[q];
+        tb[b & 1][g] = zt[q];
+      });
+    }
+  };
+  issue(std::integral_constant<int, 0>{});
+  static_for<kResIters / kResBatch>([&](auto b_c) {
+    constexpr int b = decltype(b_c)::value;
+    issue(std::integral_constant<int, b + 1>{});
+    if (b * kResBatch * kResThreads < nvec) {
+      static_for<kResBatch>([&](auto g_c) {
+        constexpr int g = decltype(g_c)::value;
+        constexpr int it = b * kResBatch + g;
+        const bool in = it * kResThreads + tid < nvec;
+        uint4 qs = rs[it], qt = tb[b & 1][g];
+        if (!in) { qs = neutral; qt = neutral; }
+        if constexpr (it < kResTLds) lds_t[it * kResThreads + tid] = qt; else rt[it - kResTLds] = qt;
+        stats_update(st, qs, qt);
+      });
+    }
+  });
+  for (int q = kResVec + tid; q < nvec; q += kResThreads) stats_update(st, zs[q], zt[q]);
+  float Zs = st.Zs, As = st.A, Zt = st.Zt;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    merge_mza(st.ms, Zs, As, __shfl_xor(st.ms, o, 64), __shfl_xor(Zs, o, 64), __shfl_xor(As, o, 64));
+    merge_mz(st.mt, Zt, __shfl_xor(st.mt, o, 64), __shfl_xor(Zt, o, 64));
+  }
+  if (lane == 0) { sh[0 + w] = st.ms; sh[4 + w] = Zs; sh[8 + w] = As; sh[12 + w] = st.mt; sh[16 + w] = Zt; }
+  __syncthreads();
+  if (tid == 0) {
+    float m = sh[0], Z = sh[4], Aa = sh[8], m2 = sh[12], Z2 = sh[16];
+    for (int k = 1; k < kResThreads / 64; ++k) {
+      merge_mza(m, Z, Aa, sh[k], sh[4 + k], sh[8 + k]);
+      merge_mz(m2, Z2, sh[12 + k], sh[16 + k]);
+    }
+    const float lse_s = m + logf(Z), lse_t = m2 + logf(Z2);
+    const float mu = Aa / Z;                       // E_{p_s}[z_s - z_t]
+    const float kl = mu - lse_s + lse_t;
+    float c = 0.f;
+    uint32_t flag = 0;
+    if (a.ids) {
+      const int y = a.ids[t];
+      if (y >= 0 && y < a.V) {
+        const float zy_s = __uint_as_float((uint32_t)((const uint16_t*)zs)[y] << 16);
+        const float zy_t = __uint_as_float((uint32_t)((const uint16_t*)zt)[y] << 16);
+        c = (zy_s - lse_s) - (zy_t - lse_t);
+      } else {
+        flag |= ADWIN_DEV_BAD_ID;
+      }
+    }
+    if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f))
+      flag |= ADWIN_DEV_NONFINITE;
+    if (flag && a.status) atomicOr(a.status, flag);
+    if (a.kl) a.kl[t] = kl;
+    if (a.c) a.c[t] = c;
+    a.klr[a.pl.comp_off[i] + j] = kl;
+    sh[20] = lse_s * kLog2e;
+    sh[21] = mu;
+  }
+  __syncthreads();
+  if (!dzr) return;
+  // ---- sweep 2: dz from the resident copy ----------------------------------------------
+  const float scale = a.grad_scale * a.pl.alpha_p[i];
+  const float sgn = scale < 0.f ? -1.f : 1.f;
+  const float lse2 = sh[20] - log2f(fabsf(scale)), nmu = -sgn * sh[21];
+  static_for<kResIters>([&](auto it_c) {
+    constexpr int it = decltype(it_c)::value;
+    if (it * kResThreads < nvec) {
+      const int q = it * kResThreads + tid;
+      uint4 qt;
+      if constexpr (it < kResTLds) qt = lds_t[it * kResThreads + tid]; else qt = rt[it - kResTLds];
+      const uint4 o = dz_vector(rs[it], qt, lse2, sgn, nmu);
+      if (q < nvec) nt_store16(dzr + q, o);
+    }
+  });
+  for (int q = kResVec + tid; q < nvec; q += kResThreads)
+    nt_store16(dzr + q, dz_vector(zs[q], zt[q], lse2, sgn, nmu));
+}
+
 struct LogitsLayout {
   size_t o_plan, o_klr, o_seg, o_racc, total;
   LogitsLayout(int32_t B, int64_t T) {
@@ -203,7 +397,18 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
     a.grad_scale = p->grad_scale;
     a.kl = p->kl; a.c = p->c; a.dz = (uint4*)p->dz; a.klr = klr; a.status = p->status_dev;
     PhaseScope scope(timer, ADWIN_PHASE_STATS);
-    logits_row_kernel<<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
+    static const bool streaming = getenv("ADWIN_LOGITS_STREAMING") != nullptr;
+    if (streaming) {
+      logits_row_kernel<<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
+    } else {
+      static bool opted = false;
+      if (!opted) {
+        ADWIN_HIP_TRY(hipFuncSetAttribute((const void*)logits_row_resident_kernel,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes));
+        opted = true;
+      }
+      logits_row_resident_kernel<<<(unsigned)p->T, kResThreads, kResLdsBytes, stream>>>(a);
+    }
     ADWIN_HIP_TRY(hipGetLastError());
   }
   PhaseScope scope(timer, ADWIN_PHASE_REDUCE);
