@@ -15,6 +15,7 @@
 // with i in registers and j = lane % 32.  In the logit passes A = W tile (i = vocabulary)
 // and B = h tile (j = token), so each lane owns one token column and the reduction over
 // the vocabulary runs down its own registers with no cross-lane traffic.
+#include <utility>
 #include <vector>
 
 #include "device_utils.h"
@@ -30,8 +31,9 @@ constexpr int kRowBytes = kBK * 2;   // 128 B of k per staged row
 // ---------------------------------------------------------------------------------------
 // Staging of [ROWS x 64] bf16 tiles: global -> registers -> LDS.  Thread t moves the
 // 16-byte chunk (t & 7) of rows (t >> 3) + 32 i.  Chunk c of row r is stored at chunk
-// position c ^ (r & 7), so that the 32 rows one MFMA fragment read touches spread over
-// all LDS banks.
+// position c ^ ((r >> 1) & 7): two 128-byte rows span all 64 LDS banks, so the 16 rows
+// that 16 consecutive lanes of an MFMA fragment read touch land on 16 distinct
+// (row parity, position) pairs, i.e. on distinct banks.
 // ---------------------------------------------------------------------------------------
 template <int ROWS>
 struct RowStager {
@@ -50,7 +52,7 @@ struct RowStager {
 
 __device__ __forceinline__ int stage_thread_off(int tid) {
   const int r = tid >> 3, c = tid & 7;
-  return r * kRowBytes + ((c ^ (r & 7)) << 4);
+  return r * kRowBytes + ((c ^ ((r >> 1) & 7)) << 4);
 }
 
 // acc[FM][FN] += A_tile(wave rows) * B_tile(wave rows)^T for one staged k-step of 64.
@@ -60,7 +62,7 @@ __device__ __forceinline__ void mma_stage(f32x16 (&acc)[FM][FN], const char* tA,
   const int row_off = (lane & 31) * kRowBytes;
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    const int sw = ((kk * 2 + (lane >> 5)) ^ (lane & 7)) << 4;
+    const int sw = ((kk * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4;
     bf16x8 a[FM], b[FN];
 #pragma unroll
     for (int fm = 0; fm < FM; ++fm)
@@ -126,6 +128,8 @@ struct LogitPassArgs {
   int tile0;                   // first token tile of this launch
   int n_tiles;                 // token tiles in this launch
   int strips;                  // vocabulary strips
+  int tg;                      // token tiles per workgroup group (share W tiles in one L2)
+  int debug_same;              // timing experiment (results invalid): every workgroup reads the same tiles
   int vt_total;                // vocabulary tiles (of 128)
   // pass 1 out: [5][strips][n_pad]
   float* part;
@@ -133,6 +137,93 @@ struct LogitPassArgs {
   const float* lse2; const float* mu;
   __bf16* slab; int64_t Vp; int64_t slab_row0;
 };
+
+// Running per-token statistics held by one lane for its two token columns.
+struct LaneStats { float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2]; };
+
+// Element e of block fm sits at vocabulary row v0 + fm*32 + 8*(e/4) + 4*(lane/32) + e%4.
+// Online update of (m_s, Z_s, A, m_t, Z_t) with one 128 x 64 logit tile per wave.
+__device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
+                                               LaneStats& st, int v0, int V, bool tail, int lane) {
+  const int vlane = v0 + 4 * (lane >> 5);
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    float mxs = st.m_s[fn], mxt = st.m_t[fn];
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < V;
+        if (ok) { mxs = fmaxf(mxs, zs[fm][fn][e]); mxt = fmaxf(mxt, zt[fm][fn][e]); }
+      }
+    const float scs = fast_exp2((st.m_s[fn] - mxs) * kLog2e);
+    const float sct = fast_exp2((st.m_t[fn] - mxt) * kLog2e);
+    float Zs = st.Z_s[fn] * scs, As = st.A_s[fn] * scs, Zt = st.Z_t[fn] * sct;
+    const float ms2 = mxs * kLog2e, mt2 = mxt * kLog2e;
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < V;
+        const float s = zs[fm][fn][e], t = zt[fm][fn][e];
+        float es = fast_exp2(fmaf(s, kLog2e, -ms2));
+        float et = fast_exp2(fmaf(t, kLog2e, -mt2));
+        float d = s - t;
+        if (!ok) { es = 0.f; et = 0.f; d = 0.f; }
+        Zs += es;
+        As = fmaf(es, d, As);
+        Zt += et;
+      }
+    st.m_s[fn] = mxs; st.m_t[fn] = mxt; st.Z_s[fn] = Zs; st.A_s[fn] = As; st.Z_t[fn] = Zt;
+  }
+}
+
+// dz = p_s ((z_s - z_t) - mu), rounded to bf16, into slab rows row0 + fn*32 + lane%32.
+__device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
+                                            const float (&lse2)[2], const float (&mu)[2], __bf16* slab,
+                                            int64_t Vp, int64_t row0, int v0, int V, bool tail, int lane) {
+  const int vlane = v0 + 4 * (lane >> 5);
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    __bf16* out = slab + (row0 + fn * 32 + (lane & 31)) * Vp + vlane;
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float d[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
+          d[e] = fast_exp2(fmaf(s, kLog2e, -lse2[fn])) * ((s - t) - mu[fn]);
+        }
+        if (tail && vlane + fm * 32 + 8 * q >= V) { d[0] = d[1] = d[2] = d[3] = 0.f; }
+        uint2 o;
+        o.x = pack_bf16(d[0], d[1]);
+        o.y = pack_bf16(d[2], d[3]);
+        *(uint2*)(out + fm * 32 + 8 * q) = o;
+      }
+  }
+}
+
+// Merge the two half-columns held by lanes l and l^32 and write one strip's partials.
+__device__ __forceinline__ void write_partials(LaneStats& st, float* part, int strips, int strip,
+                                               int64_t n_pad, int64_t row0, int lane) {
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    merge_mza(st.m_s[fn], st.Z_s[fn], st.A_s[fn], __shfl_xor(st.m_s[fn], 32, 64),
+              __shfl_xor(st.Z_s[fn], 32, 64), __shfl_xor(st.A_s[fn], 32, 64));
+    merge_mz(st.m_t[fn], st.Z_t[fn], __shfl_xor(st.m_t[fn], 32, 64), __shfl_xor(st.Z_t[fn], 32, 64));
+    if (lane < 32) {
+      const int64_t plane = (int64_t)strips * n_pad;
+      float* o = part + (int64_t)strip * n_pad + row0 + fn * 32 + lane;
+      o[0 * plane] = st.m_s[fn];
+      o[1 * plane] = st.Z_s[fn];
+      o[2 * plane] = st.A_s[fn];
+      o[3 * plane] = st.m_t[fn];
+      o[4 * plane] = st.Z_t[fn];
+    }
+  }
+}
 
 constexpr int kLogitStage = (kTileVocab + kTileTokens) * kRowBytes;   // 48 KiB
 constexpr int kLogitLds = 2 * kLogitStage;
@@ -143,9 +234,9 @@ __global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // virtual id -> (group of 4 token tiles, strip, tile in group)
   const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
-  const int per_group = 4 * a.strips;
+  const int per_group = a.tg * a.strips;
   const int tg = vid / per_group, within = vid % per_group;
-  const int strip = within >> 2, tt_local = tg * 4 + (within & 3);
+  const int strip = within / a.tg, tt_local = tg * a.tg + (within % a.tg);
   if (tt_local >= a.n_tiles) return;
   const int tt = a.tile0 + tt_local;
   const int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
@@ -165,11 +256,12 @@ __global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
   }
   const int waveB = wave * 64 * kRowBytes;   // this wave's 64 token rows in the B tile
 
-  float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2];
+  LaneStats st;
   float lse2[2], mu[2];
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
-    m_s[fn] = kNegBig; Z_s[fn] = 0.f; A_s[fn] = 0.f; m_t[fn] = kNegBig; Z_t[fn] = 0.f;
+    st.m_s[fn] = kNegBig; st.Z_s[fn] = 0.f; st.A_s[fn] = 0.f; st.m_t[fn] = kNegBig; st.Z_t[fn] = 0.f;
+    lse2[fn] = 0.f; mu[fn] = 0.f;
     if (PASS2) {
       const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
       lse2[fn] = a.lse2[r];
@@ -200,82 +292,254 @@ __global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
     gemm_kloop<kTileVocab, kTileTokens, 4, 2>(zs, ws, hs, 0, a.H_s / kBK, lds, kLogitStage, 0, waveB, tid);
 
     const bool tail = v0 + kTileVocab > a.V;
-    // element e of block fm sits at vocabulary row v0 + fm*32 + 8*(e/4) + 4*(lane/32) + e%4
-    const int vlane = v0 + 4 * (lane >> 5);
-    if (!PASS2) {
+    if (!PASS2) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
+    else dz_epilogue(zs, zt, lse2, mu, a.slab, a.Vp, (int64_t)tt * kTileTokens + wave * 64 - a.slab_row0,
+                     v0, a.V, tail, lane);
+  }
+  if (!PASS2)
+    write_partials(st, a.part, a.strips, strip, a.n_pad, (int64_t)tt * kTileTokens + wave * 64, lane);
+}
+
+// ---------------------------------------------------------------------------------------
+// Logit passes, direct global->LDS staging.
+//
+// Same tile, MFMA roles and epilogues as logit_pass_kernel, but the k-tiles are moved by
+// global_load_lds_dwordx4 (no register staging) into a three-stage LDS ring, two k-steps
+// ahead of the MFMAs.  One wave instruction moves 8 rows x 128 B: lane l lands at
+// base + 16 l, i.e. row l/8, chunk position l%8, and therefore fetches global chunk
+// (l%8) ^ swizzle(row).  The teacher and student k-loops form one pipeline of
+// H_t/64 + H_s/64 steps per vocabulary tile.
+//
+// The loads are written as inline assembly (M0 = LDS destination of the wave, scalar base
+// + 32-bit lane offset) and waited for with explicit s_waitcnt vmcnt(N): the loads return
+// in order, so "at most the 12 loads of the next stage outstanding" means this stage has
+// landed.  Compiler-issued loads in between only make the count larger, i.e. the wait
+// longer.  Requires rows * H * 2 bytes < 4 GiB per operand (32-bit lane offsets).
+// ---------------------------------------------------------------------------------------
+constexpr int kDmaStages = 3;
+constexpr int kDmaLds = kDmaStages * kLogitStage;           // 144 KiB
+constexpr int kDmaPerWave = (kTileVocab + kTileTokens) / 8 / 4;   // 12 wave-loads per stage
+
+__device__ __forceinline__ void dma16(uint32_t lds_dst, uint32_t voff, const char* sbase) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_dst), "v"(voff), "s"(sbase) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+struct DmaOffsets { uint32_t a[kTileVocab / 32]; uint32_t b[kTileTokens / 32]; };
+
+// Issues wave-loads [Q*3, Q*3+3) of the 12 this wave owns for one stage: groups wave,
+// wave+4, ... of the 48 eight-row groups ([A rows 0..127 | B rows 0..255]).
+template <int Q>
+__device__ __forceinline__ void dma_quarter(uint32_t lds_stage, int wave, const DmaOffsets& o,
+                                            const char* sA, const char* sB) {
 #pragma unroll
-      for (int fn = 0; fn < 2; ++fn) {
-        float mxs = m_s[fn], mxt = m_t[fn];
+  for (int i = Q * 3; i < Q * 3 + 3; ++i) {
+    if (i < kTileVocab / 32)
+      dma16(lds_stage + (uint32_t)(wave + 4 * i) * 1024u, o.a[i], sA);
+    else
+      dma16(lds_stage + (uint32_t)(kTileVocab / 8 + wave + 4 * (i - kTileVocab / 32)) * 1024u,
+            o.b[i - kTileVocab / 32], sB);
+  }
+}
+
+__device__ __forceinline__ void dma_stage(uint32_t lds_stage, int wave, const DmaOffsets& o,
+                                          const char* sA, const char* sB) {
+  dma_quarter<0>(lds_stage, wave, o, sA, sB);
+  dma_quarter<1>(lds_stage, wave, o, sA, sB);
+  dma_quarter<2>(lds_stage, wave, o, sA, sB);
+  dma_quarter<3>(lds_stage, wave, o, sA, sB);
+}
+
+// One staged k-step of MFMAs with the next-but-one stage's loads spread between the four
+// k16 sub-steps, so that the vector-memory issue never stalls all four waves at once.
+// Wave-load i (0..11) of this wave for one stage.
+template <int I>
+__device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, const DmaOffsets& o,
+                                        const char* sA, const char* sB) {
+  if constexpr (I < kTileVocab / 32)
+    dma16(lds_stage + (uint32_t)(wave + 4 * I) * 1024u, o.a[I], sA);
+  else
+    dma16(lds_stage + (uint32_t)(kTileVocab / 8 + wave + 4 * (I - kTileVocab / 32)) * 1024u,
+          o.b[I - kTileVocab / 32], sB);
+}
+
+// One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  The instruction
+// order is pinned: after each MFMA exactly one side operation is issued in its shadow --
+// an LDS read of a fragment of the next sub-step (fragments are double-buffered) or one
+// of the 12 global->LDS loads of the stage two k-steps ahead -- so that neither the LDS
+// latency nor the vector-memory issue ever holds up the matrix pipe.
+template <bool ISSUE>
+__device__ __forceinline__ void mma_stage_dma(f32x16 (&acc)[4][2], const char* tA, const char* tB,
+                                              int lane, uint32_t lds_stage, int wave,
+                                              const DmaOffsets& o, const char* sA, const char* sB) {
+  const int key = (lane >> 1) & 7, half = lane >> 5;
+  const char* pA[4];
+  const char* pB[4];
 #pragma unroll
-        for (int fm = 0; fm < 4; ++fm)
+  for (int kk = 0; kk < 4; ++kk) {
+    const int sw = ((kk * 2 + half) ^ key) << 4;
+    pA[kk] = tA + (lane & 31) * kRowBytes + sw;
+    pB[kk] = tB + (lane & 31) * kRowBytes + sw;
+  }
+  bf16x8 fa[2][4], fb[2][2];
+#define ADWIN_FENCE __builtin_amdgcn_sched_barrier(0);
+#define ADWIN_RA(KK, I) fa[(KK) & 1][I] = *(const bf16x8*)(pA[KK] + (I) * 32 * kRowBytes); ADWIN_FENCE
+#define ADWIN_RB(KK, I) fb[(KK) & 1][I] = *(const bf16x8*)(pB[KK] + (I) * 32 * kRowBytes); ADWIN_FENCE
+#define ADWIN_MM(KK, FMI, FNI)                                                                  \
+  acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
+                                                          acc[FMI][FNI], 0, 0, 0);              \
+  ADWIN_FENCE
+#define ADWIN_DMA(I) if constexpr (ISSUE) dma_one<I>(lds_stage, wave, o, sA, sB); ADWIN_FENCE
+  ADWIN_FENCE
+  ADWIN_RA(0, 0) ADWIN_RB(0, 0) ADWIN_RA(0, 1) ADWIN_RB(0, 1) ADWIN_RA(0, 2) ADWIN_RA(0, 3)
+#define ADWIN_STEP(KK, NK, D0, D1, D2)                          \
+  ADWIN_MM(KK, 0, 0) ADWIN_RA(NK, 0)                            \
+  ADWIN_MM(KK, 0, 1) ADWIN_RB(NK, 0)                            \
+  ADWIN_MM(KK, 1, 0) ADWIN_DMA(D0)                              \
+  ADWIN_MM(KK, 1, 1) ADWIN_RA(NK, 1)                            \
+  ADWIN_MM(KK, 2, 0) ADWIN_RB(NK, 1)                            \
+  ADWIN_MM(KK, 2, 1) ADWIN_DMA(D1)                              \
+  ADWIN_MM(KK, 3, 0) ADWIN_RA(NK, 2)                            \
+  ADWIN_MM(KK, 3, 1) ADWIN_RA(NK, 3) ADWIN_DMA(D2)
+  ADWIN_STEP(0, 1, 0, 1, 2)
+  ADWIN_STEP(1, 2, 3, 4, 5)
+  ADWIN_STEP(2, 3, 6, 7, 8)
+  // last sub-step: no further fragments of this stage
+  ADWIN_MM(3, 0, 0) ADWIN_MM(3, 0, 1) ADWIN_DMA(9)
+  ADWIN_MM(3, 1, 0) ADWIN_MM(3, 1, 1) ADWIN_DMA(10)
+  ADWIN_MM(3, 2, 0) ADWIN_MM(3, 2, 1) ADWIN_DMA(11)
+  ADWIN_MM(3, 3, 0) ADWIN_MM(3, 3, 1)
+#undef ADWIN_STEP
+#undef ADWIN_DMA
+#undef ADWIN_MM
+#undef ADWIN_RB
+#undef ADWIN_RA
+#undef ADWIN_FENCE
+}
+
+template <bool PASS2>
+__global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int per_group = a.tg * a.strips;
+  const int tg = vid / per_group, within = vid % per_group;
+  const int strip = within / a.tg, tt_local = tg * a.tg + (within % a.tg);
+  if (tt_local >= a.n_tiles) return;
+  int tt = a.tile0 + tt_local;
+  int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
+  int vt_end = (int)((int64_t)a.vt_total * (strip + 1) / a.strips);
+  if (a.debug_same & 1) { vt_end = vt_end - vt_begin; vt_begin = 0; tt = a.tile0; }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+
+  // lane -> (row within its 8-row group, chunk position); global chunk = pos ^ swizzle(row)
+  const int lrow = lane >> 3, lpos = lane & 7;
+  DmaOffsets os, ot;     // student / teacher operand offsets in bytes
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < a.V;
-            if (ok) { mxs = fmaxf(mxs, zs[fm][fn][e]); mxt = fmaxf(mxt, zt[fm][fn][e]); }
-          }
-        const float scs = fast_exp2((m_s[fn] - mxs) * kLog2e);
-        const float sct = fast_exp2((m_t[fn] - mxt) * kLog2e);
-        float Zs = Z_s[fn] * scs, As = A_s[fn] * scs, Zt = Z_t[fn] * sct;
-        const float ms2 = mxs * kLog2e, mt2 = mxt * kLog2e;
+  for (int j = 0; j < kTileTokens / 32; ++j) {
+    const int row = (wave + 4 * j) * 8 + lrow;                       // row in the 256-token tile
+    const int chunk = lpos ^ ((row >> 1) & 7);
+    const uint32_t r = (uint32_t)a.row_idx[(int64_t)tt * kTileTokens + row];
+    os.b[j] = r * (uint32_t)(a.H_s * 2) + chunk * 16;
+    ot.b[j] = r * (uint32_t)(a.H_t * 2) + chunk * 16;
+  }
+  const int waveB = wave * 64 * kRowBytes;
+  const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;
+
+  LaneStats st;
+  float lse2[2], mu[2];
 #pragma unroll
-        for (int fm = 0; fm < 4; ++fm)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < a.V;
-            const float s = zs[fm][fn][e], t = zt[fm][fn][e];
-            float es = fast_exp2(fmaf(s, kLog2e, -ms2));
-            float et = fast_exp2(fmaf(t, kLog2e, -mt2));
-            float d = s - t;
-            if (!ok) { es = 0.f; et = 0.f; d = 0.f; }
-            Zs += es;
-            As = fmaf(es, d, As);
-            Zt += et;
-          }
-        m_s[fn] = mxs; m_t[fn] = mxt; Z_s[fn] = Zs; A_s[fn] = As; Z_t[fn] = Zt;
-      }
-    } else {
-#pragma unroll
-      for (int fn = 0; fn < 2; ++fn) {
-        const int64_t rl = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31) - a.slab_row0;
-        __bf16* out = a.slab + rl * a.Vp + vlane;
-#pragma unroll
-        for (int fm = 0; fm < 4; ++fm)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            float d[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
-              d[e] = fast_exp2(fmaf(s, kLog2e, -lse2[fn])) * ((s - t) - mu[fn]);
-            }
-            if (tail && vlane + fm * 32 + 8 * q >= a.V) { d[0] = d[1] = d[2] = d[3] = 0.f; }
-            uint2 o;
-            o.x = pack_bf16(d[0], d[1]);
-            o.y = pack_bf16(d[2], d[3]);
-            *(uint2*)(out + fm * 32 + 8 * q) = o;
-          }
-      }
+  for (int fn = 0; fn < 2; ++fn) {
+    st.m_s[fn] = kNegBig; st.Z_s[fn] = 0.f; st.A_s[fn] = 0.f; st.m_t[fn] = kNegBig; st.Z_t[fn] = 0.f;
+    lse2[fn] = 0.f; mu[fn] = 0.f;
+    if (PASS2) {
+      const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
+      lse2[fn] = a.lse2[r];
+      mu[fn] = a.mu[r];
     }
   }
-  if (!PASS2) {
+
+  uint32_t ring = 0;   // stage the next issued k-step goes to (runs on across tiles)
+  for (int vt = vt_begin; vt < vt_end; ++vt) {
+    const int v0 = vt * kTileVocab;
 #pragma unroll
-    for (int fn = 0; fn < 2; ++fn) {
-      // lanes l and l^32 hold the two halves of the same token column
-      merge_mza(m_s[fn], Z_s[fn], A_s[fn], __shfl_xor(m_s[fn], 32, 64), __shfl_xor(Z_s[fn], 32, 64),
-                __shfl_xor(A_s[fn], 32, 64));
-      merge_mz(m_t[fn], Z_t[fn], __shfl_xor(m_t[fn], 32, 64), __shfl_xor(Z_t[fn], 32, 64));
-      if (lane < 32) {
-        const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + lane;
-        const int64_t plane = (int64_t)a.strips * a.n_pad;
-        float* o = a.part + (int64_t)strip * a.n_pad + r;
-        o[0 * plane] = m_s[fn];
-        o[1 * plane] = Z_s[fn];
-        o[2 * plane] = A_s[fn];
-        o[3 * plane] = m_t[fn];
-        o[4 * plane] = Z_t[fn];
-      }
+    for (int j = 0; j < kTileVocab / 32; ++j) {
+      const int row = (wave + 4 * j) * 8 + lrow;                     // row in the 128-row W tile
+      const int chunk = lpos ^ ((row >> 1) & 7);
+      int v = v0 + row;
+      v = v < a.V ? v : a.V - 1;                                     // tail: valid row, masked later
+      os.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_s * 2) + chunk * 16;
+      ot.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_t * 2) + chunk * 16;
     }
+    const char* sWt = (const char*)(a.W_t + (int64_t)v0 * a.H_t);
+    const char* sWs = (const char*)(a.W_s + (int64_t)v0 * a.H_s);
+    const char* sHt = (const char*)a.h_t;
+    const char* sHs = (const char*)a.h_s;
+    auto issue = [&](int s) {      // k-step s of this tile: teacher steps first, then student
+      const uint32_t dst = lds0 + ring * kLogitStage;
+      if (s < nk_t) dma_stage(dst, wave, ot, sWt + s * kRowBytes, sHt + s * kRowBytes);
+      else dma_stage(dst, wave, os, sWs + (s - nk_t) * kRowBytes, sHs + (s - nk_t) * kRowBytes);
+      ring = ring + 1 == kDmaStages ? 0 : ring + 1;
+    };
+    f32x16 zt[4][2], zs[4][2];
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { zt[fm][fn][e] = 0.f; zs[fm][fn][e] = 0.f; }
+
+    uint32_t rd = ring;            // stage of the next k-step to consume
+    issue(0);
+    issue(1);                      // nk >= 2 always (H_s, H_t >= 64)
+    // k-step s consumes stage rd while the loads of k-step s+2 are issued into `ring`.
+    // The loops are peeled so that the steady-state bodies carry no conditionals.
+    auto step = [&](auto issue_c, f32x16 (&acc)[4][2], const DmaOffsets& o, const char* sA, const char* sB) {
+      constexpr bool kIssue = decltype(issue_c)::value;
+      const char* cur = lds + rd * kLogitStage;
+      mma_stage_dma<kIssue>(acc, cur, cur + kTileVocab * kRowBytes + waveB, lane,
+                            lds0 + ring * kLogitStage, wave, o, sA, sB);
+      if (kIssue) ring = ring + 1 == kDmaStages ? 0 : ring + 1;
+      rd = rd + 1 == kDmaStages ? 0 : rd + 1;
+    };
+    const std::true_type yes{};
+    const std::false_type no{};
+    int s = 0;
+    for (; s + 2 < nk_t; ++s) {                // teacher k-steps prefetching teacher k-steps
+      wait_vm<kDmaPerWave>();
+      __syncthreads();
+      step(yes, zt, ot, sWt + (s + 2) * kRowBytes, sHt + (s + 2) * kRowBytes);
+    }
+    for (; s < nk_t; ++s) {                    // last teacher k-steps prefetch student k-steps
+      wait_vm<kDmaPerWave>();
+      __syncthreads();
+      const int n = s + 2 - nk_t;              // 0 or 1: nk_s >= 2 on this path
+      step(yes, zt, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
+    }
+    for (; s + 2 < nk; ++s) {                  // student k-steps
+      wait_vm<kDmaPerWave>();
+      __syncthreads();
+      const int n = s + 2 - nk_t;
+      step(yes, zs, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
+    }
+    for (; s < nk; ++s) {                      // drain: nothing left to prefetch in this tile
+      if (s + 1 < nk) wait_vm<kDmaPerWave>(); else wait_vm<0>();
+      __syncthreads();
+      step(no, zs, os, sWs, sHs);
+    }
+    const bool tail = v0 + kTileVocab > a.V;
+    if (!PASS2) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
+    else dz_epilogue(zs, zt, lse2, mu, a.slab, a.Vp, (int64_t)tt * kTileTokens + wave * 64 - a.slab_row0,
+                     v0, a.V, tail, lane);
   }
+  if (!PASS2)
+    write_partials(st, a.part, a.strips, strip, a.n_pad, (int64_t)tt * kTileTokens + wave * 64, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -628,6 +892,12 @@ static hipError_t ensure_lds_opt_in() {
   e = hipFuncSetAttribute((const void*)logit_pass_kernel<true>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kLogitLds);
   if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<false>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<true>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)grad_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                           kGradLds);
   if (e != hipSuccess) return e;
@@ -699,6 +969,10 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
                                                   p->V, p->H_s, L.Vp);
       ADWIN_HIP_TRY(hipGetLastError());
     }
+    // direct-to-LDS staging uses 32-bit byte offsets from each operand's base
+    const int64_t maxH = p->H_s > p->H_t ? p->H_s : p->H_t;
+    const bool use_dma = !getenv("ADWIN_NO_DMA") && p->T * maxH * 2 < (int64_t(1) << 32) &&
+                         p->H_s >= 2 * kBK && p->H_t >= 2 * kBK;
     LogitPassArgs la;
     la.h_s = (const __bf16*)p->h_s; la.h_t = (const __bf16*)p->h_t;
     la.W_s = (const __bf16*)p->W_s; la.W_t = (const __bf16*)p->W_t;
@@ -712,8 +986,13 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     phase(ADWIN_PHASE_STATS);
     {
       la.tile0 = 0; la.n_tiles = n_tiles; la.strips = L.strips;
-      const int groups = (n_tiles + 3) / 4;
-      logit_pass_kernel<false><<<(unsigned)(groups * 4 * L.strips), 256, kLogitLds, stream>>>(la);
+      la.tg = env_int("ADWIN_TG", 4);
+      la.debug_same = getenv("ADWIN_DEBUG_SAME") ? atoi(getenv("ADWIN_DEBUG_SAME")) : 0;
+      const int groups = (n_tiles + la.tg - 1) / la.tg;
+      if (use_dma)
+        logit_pass_dma_kernel<false><<<(unsigned)(groups * la.tg * L.strips), 256, kDmaLds, stream>>>(la);
+      else
+        logit_pass_kernel<false><<<(unsigned)(groups * la.tg * L.strips), 256, kLogitLds, stream>>>(la);
       ADWIN_HIP_TRY(hipGetLastError());
     }
     phase(ADWIN_PHASE_MERGE);
@@ -735,9 +1014,12 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
       const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
       la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
       la.strips = strips2; la.slab_row0 = r0;
-      const int groups = (la.n_tiles + 3) / 4;
+      const int groups = (la.n_tiles + la.tg - 1) / la.tg;
       phase(ADWIN_PHASE_DZ);
-      logit_pass_kernel<true><<<(unsigned)(groups * 4 * strips2), 256, kLogitLds, stream>>>(la);
+      if (use_dma)
+        logit_pass_dma_kernel<true><<<(unsigned)(groups * la.tg * strips2), 256, kDmaLds, stream>>>(la);
+      else
+        logit_pass_kernel<true><<<(unsigned)(groups * la.tg * strips2), 256, kLogitLds, stream>>>(la);
       ADWIN_HIP_TRY(hipGetLastError());
       phase(ADWIN_PHASE_GRAD);
       GradArgs ga;
