@@ -168,17 +168,22 @@ def main() -> int:
         V, Hs, Ht = w.V, w.H_s, w.H_t
         f_stats = 2.0 * V * (Hs + Ht) * tokens              # one full-vocabulary sweep of both heads
         ach = f_stats / (ph["stats"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "logit_pass_kernel<stats>", "achieved": ach,
+        roofline = {"bound": "mfma", "kernel": "logit_pass_dma_kernel", "achieved": ach,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
                     "traffic": None, "launch_ms": ph["stats"], "alg_flops_per_launch": f_stats}
         f_alg = 2.0 * V * (2 * Hs + Ht) * tokens            # student fwd + teacher fwd + dz W_s
-        f_exec = 2.0 * V * (3 * Hs + 2 * Ht) * tokens       # two-pass design recomputes the logits
+        single = ph["dz"] == 0.0                            # single-sweep scheme: no second logit sweep
+        # executed: single sweep = logits once + two gradient factors through W_s;
+        # two sweeps = logits twice + one gradient contraction
+        f_exec = 2.0 * V * ((3 * Hs + Ht) if single else (3 * Hs + 2 * Ht)) * tokens
+        f_grad = 2.0 * V * Hs * tokens * (2 if single else 1)
         t_s = ms_per_step * 1e-3
         extra = {"roofline_call": {
+            "scheme": "single_sweep" if single else "two_sweeps",
             "alg_tflops": f_alg / t_s / 1e12, "alg_frac": f_alg / t_s / 1e12 / PEAK_BF16_TFLOPS,
             "exec_tflops": f_exec / t_s / 1e12, "exec_frac": f_exec / t_s / 1e12 / PEAK_BF16_TFLOPS,
-            "dz_pass_tflops": f_stats / (ph["dz"] * 1e-3) / 1e12,
-            "grad_gemm_tflops": 2.0 * V * Hs * tokens / (ph["grad"] * 1e-3) / 1e12}}
+            "dz_pass_tflops": None if single else f_stats / (ph["dz"] * 1e-3) / 1e12,
+            "grad_gemm_tflops": f_grad / (ph["grad"] * 1e-3) / 1e12}}
 
     cpu = None
     if args.cpu_rows > 0:

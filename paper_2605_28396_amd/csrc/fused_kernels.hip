@@ -136,7 +136,15 @@ struct LogitPassArgs {
   // pass 2 in / out
   const float* lse2; const float* mu;
   __bf16* slab; int64_t Vp; int64_t slab_row0;
+  // single-sweep mode: fixed per-row references and the offset of the second slab half
+  const float* ref_s2; const float* ref_t2; const float* mu0;
+  int64_t e2_off;
 };
+
+// Modes of the direct-to-LDS logit kernel.
+constexpr int kModeStats = 0;   // online (running-max) statistics only
+constexpr int kModeDz = 1;      // second sweep of the two-sweep scheme: dz tiles
+constexpr int kModeSingle = 2;  // single sweep: fixed-reference statistics + E1/E2 tiles
 
 // Running per-token statistics held by one lane for its two token columns.
 struct LaneStats { float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2]; };
@@ -202,6 +210,71 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
         o.y = pack_bf16(d[2], d[3]);
         *(uint2*)(out + fm * 32 + 8 * q) = o;
       }
+  }
+}
+
+// Single-sweep epilogue.  With per-row references fixed in advance (rs2 = m_ref_s*log2e,
+// rt2 = m_ref_t*log2e, mu0 ~ E_{p_s}[z_s - z_t]) every exponential is taken relative to the
+// same reference in every tile, so the statistics are plain sums,
+//   Z_s = sum e_s,  A = sum e_s d,  Z_t = sum e_t,   e_s = exp(z_s - m_ref_s), d = z_s - z_t,
+// and the unnormalised gradient factors E1 = e_s (d - mu0) and E2 = e_s can be emitted at
+// once: dz = (E1 - (mu - mu0) E2) / Z_s, hence g = (E1 W_s - (mu - mu0) E2 W_s) / Z_s.
+// E1 goes to slab rows row0.., E2 to the same rows e2_off elements further on.
+struct LaneSums { float Z_s[2], A_s[2], Z_t[2]; };
+
+__device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
+                                                LaneSums& sm, const float (&rs2)[2],
+                                                const float (&rt2)[2], const float (&mu0)[2],
+                                                __bf16* slab, int64_t Vp, int64_t e2_off, int64_t row0,
+                                                int v0, int V, bool tail, int lane) {
+  const int vlane = v0 + 4 * (lane >> 5);
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    __bf16* out = slab + (row0 + fn * 32 + (lane & 31)) * Vp + vlane;
+    float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn];
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float e1[4], e2[4];
+        const bool ok = !tail || (vlane + fm * 32 + 8 * q) < V;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
+          float es = fast_exp2(fmaf(s, kLog2e, -rs2[fn]));
+          float et = fast_exp2(fmaf(t, kLog2e, -rt2[fn]));
+          float d = s - t;
+          if (!ok) { es = 0.f; et = 0.f; d = 0.f; }
+          Zs += es;
+          As = fmaf(es, d, As);
+          Zt += et;
+          e1[e] = es * (d - mu0[fn]);
+          e2[e] = es;
+        }
+        uint2 o1, o2;
+        o1.x = pack_bf16(e1[0], e1[1]); o1.y = pack_bf16(e1[2], e1[3]);
+        o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
+        *(uint2*)(out + fm * 32 + 8 * q) = o1;
+        *(uint2*)(out + e2_off + fm * 32 + 8 * q) = o2;
+      }
+    sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
+  }
+}
+
+__device__ __forceinline__ void write_sums(LaneSums& sm, float* part, int strips, int strip,
+                                           int64_t n_pad, int64_t row0, int lane) {
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    const float Zs = sm.Z_s[fn] + __shfl_xor(sm.Z_s[fn], 32, 64);
+    const float As = sm.A_s[fn] + __shfl_xor(sm.A_s[fn], 32, 64);
+    const float Zt = sm.Z_t[fn] + __shfl_xor(sm.Z_t[fn], 32, 64);
+    if (lane < 32) {
+      const int64_t plane = (int64_t)strips * n_pad;
+      float* o = part + (int64_t)strip * n_pad + row0 + fn * 32 + lane;
+      o[0 * plane] = Zs;
+      o[1 * plane] = As;
+      o[2 * plane] = Zt;
+    }
   }
 }
 
@@ -422,7 +495,7 @@ __device__ __forceinline__ void mma_stage_dma(f32x16 (&acc)[4][2], const char* t
 #undef ADWIN_FENCE
 }
 
-template <bool PASS2>
+template <int MODE>
 __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   extern __shared__ __align__(16) char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -453,15 +526,21 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;
 
   LaneStats st;
-  float lse2[2], mu[2];
+  LaneSums sm;
+  float lse2[2], mu[2], rs2[2], rt2[2];   // per-row inputs of the dz / single-sweep epilogues
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
     st.m_s[fn] = kNegBig; st.Z_s[fn] = 0.f; st.A_s[fn] = 0.f; st.m_t[fn] = kNegBig; st.Z_t[fn] = 0.f;
-    lse2[fn] = 0.f; mu[fn] = 0.f;
-    if (PASS2) {
-      const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
+    sm.Z_s[fn] = 0.f; sm.A_s[fn] = 0.f; sm.Z_t[fn] = 0.f;
+    lse2[fn] = 0.f; mu[fn] = 0.f; rs2[fn] = 0.f; rt2[fn] = 0.f;
+    const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
+    if (MODE == kModeDz) {
       lse2[fn] = a.lse2[r];
       mu[fn] = a.mu[r];
+    } else if (MODE == kModeSingle) {
+      rs2[fn] = a.ref_s2[r];
+      rt2[fn] = a.ref_t2[r];
+      mu[fn] = a.mu0[r];
     }
   }
 
@@ -534,12 +613,15 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       step(no, zs, os, sWs, sHs);
     }
     const bool tail = v0 + kTileVocab > a.V;
-    if (!PASS2) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
-    else dz_epilogue(zs, zt, lse2, mu, a.slab, a.Vp, (int64_t)tt * kTileTokens + wave * 64 - a.slab_row0,
-                     v0, a.V, tail, lane);
+    const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
+    if (MODE == kModeStats) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
+    else if (MODE == kModeDz) dz_epilogue(zs, zt, lse2, mu, a.slab, a.Vp, row0 - a.slab_row0, v0, a.V, tail, lane);
+    else single_epilogue(zs, zt, sm, rs2, rt2, mu, a.slab, a.Vp, a.e2_off, row0 - a.slab_row0, v0, a.V,
+                         tail, lane);
   }
-  if (!PASS2)
-    write_partials(st, a.part, a.strips, strip, a.n_pad, (int64_t)tt * kTileTokens + wave * 64, lane);
+  const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
+  if (MODE == kModeStats) write_partials(st, a.part, a.strips, strip, a.n_pad, row0, lane);
+  else if (MODE == kModeSingle) write_sums(sm, a.part, a.strips, strip, a.n_pad, row0, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -617,6 +699,70 @@ __global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Single-sweep mode: per-row references from the online statistics of vocabulary tile 0,
+// and the merge of the fixed-reference strip sums.
+// ---------------------------------------------------------------------------------------
+__global__ void make_refs_kernel(const float* __restrict__ part /* [5][1][n_pad] */, int64_t n_pad,
+                                 float* ref_s2, float* ref_t2, float* mu0) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_pad) return;
+  const float ms = part[r], Zs = part[n_pad + r], A = part[2 * n_pad + r], mt = part[3 * n_pad + r];
+  ref_s2[r] = ms * kLog2e;
+  ref_t2[r] = mt * kLog2e;
+  mu0[r] = A / Zs;
+}
+
+struct MergeSingleArgs {
+  MergeArgs m;                 // part: [3][strips][n_pad] sums Z_s, A, Z_t
+  const float* ref_s2; const float* ref_t2; const float* mu0;
+  float* delta; float* inv_z;
+};
+
+__global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
+  const MergeArgs& a = b.m;
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.n_pad) return;
+  const int64_t plane = (int64_t)a.strips * a.n_pad;
+  float Zs = 0.f, A = 0.f, Zt = 0.f;
+  if (lane < a.strips) {
+    const float* p = a.part + (int64_t)lane * a.n_pad + r;
+    Zs = p[0]; A = p[plane]; Zt = p[2 * plane];
+  }
+  Zs = wave_sum(Zs); A = wave_sum(A); Zt = wave_sum(Zt);
+  const float lse_s = b.ref_s2[r] * kLn2 + logf(Zs), lse_t = b.ref_t2[r] * kLn2 + logf(Zt);
+  const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
+  const float kl = mu - lse_s + lse_t;
+  if (lane == 0) {
+    b.delta[r] = mu - b.mu0[r];
+    b.inv_z[r] = 1.f / Zs;
+    a.klr[r] = kl;
+  }
+  if (r >= a.n_rows) return;
+  const int64_t t = a.row_idx[r];
+  float c = 0.f;
+  uint32_t flag = 0;
+  if (a.ids && a.c) {
+    const int y = a.ids[t];
+    if (y >= 0 && y < a.V) {
+      const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
+      const float zy_t = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)y * a.H_t, a.H_t, lane);
+      c = (zy_s - lse_s) - (zy_t - lse_t);
+    } else {
+      flag |= ADWIN_DEV_BAD_ID;
+    }
+  }
+  if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f) ||
+      !(fabsf(A) < 3.0e38f))
+    flag |= ADWIN_DEV_NONFINITE;
+  if (lane == 0) {
+    if (flag && a.status) atomicOr(a.status, flag);
+    if (a.kl) a.kl[t] = kl;
+    if (a.c) a.c[t] = c;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // W_s [V, H] -> W_sT [H, Vp] (zero beyond V) so that the gradient GEMM reads both operands
 // k-contiguous.
 // ---------------------------------------------------------------------------------------
@@ -643,10 +789,12 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __re
 // ---------------------------------------------------------------------------------------
 struct GradArgs {
   const __bf16* slab; const __bf16* WsT; int64_t Vp;
-  float* g;                 // [ksplit][n_pad][H]
-  int64_t n_pad; int H;
+  float* g;                 // [ksplit][g_rows][H]
+  int64_t g_rows; int H;
   int64_t slab_row0;        // computed-row index of slab row 0
   int row_tiles, h_tiles, ksplit;
+  int half_tiles;           // slab row tiles >= half_tiles hold the E2 factor: output rows
+  int64_t half_off;         // half_off + slab_row0 + ... (single-sweep mode; else half_tiles = row_tiles)
 };
 
 constexpr int kGradStage = 2 * kGradTile * kRowBytes;   // 64 KiB
@@ -687,7 +835,9 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       for (int e = 0; e < 16; ++e) acc[fm][fn][e] = 0.f;
   gemm_kloop<kGradTile, kGradTile, 4, 4>(acc, sa, sb, k_begin, k_end - k_begin, lds, kGradStage,
                                          wm * 128 * kRowBytes, wn * 128 * kRowBytes, tid);
-  float* g = a.g + (int64_t)split * a.n_pad * a.H;
+  float* g = a.g + (int64_t)split * a.g_rows * a.H;
+  const int64_t out_row0 = rt < a.half_tiles ? a.slab_row0 + (int64_t)rt * kGradTile
+                                             : a.half_off + a.slab_row0 + (int64_t)(rt - a.half_tiles) * kGradTile;
 #pragma unroll
   for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
@@ -696,7 +846,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       if (h < a.H) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int64_t r = a.slab_row0 + (int64_t)rt * kGradTile + wm * 128 + fm * 32 +
+          const int64_t r = out_row0 + wm * 128 + fm * 32 +
                             8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
           g[r * a.H + h] = acc[fm][fn][e];
         }
@@ -711,6 +861,8 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 struct FinalizeArgs {
   DevicePlan pl; int B; int64_t T; int probe;
   float* g; int ksplit; int64_t n_pad; int H;
+  int64_t g_rows;                          // rows per k-split plane of g
+  const float* delta; const float* inv_z;  // single-sweep mode: g = (G1 - delta G2) inv_z, else NULL
   float grad_scale; int dh_bf16;
   void* dh_prefix; void* dh_full;
   float* rownorm;
@@ -745,13 +897,23 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a) {
   const float sp = admitted ? a.grad_scale * a.pl.alpha_p[i] : 0.f;
   const float sf = a.grad_scale * a.pl.alpha_f[i];
   float nrm = 0.f;
+  const float dl = a.delta ? a.delta[r] : 0.f, iz = a.inv_z ? a.inv_z[r] : 1.f;
   for (int h = lane * 4; h < a.H; h += 256) {
     float4 g = *(const float4*)(a.g + r * a.H + h);
     for (int s = 1; s < a.ksplit; ++s) {
-      const float4 q = *(const float4*)(a.g + ((int64_t)s * a.n_pad + r) * a.H + h);
+      const float4 q = *(const float4*)(a.g + ((int64_t)s * a.g_rows + r) * a.H + h);
       g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w;
     }
-    if (a.ksplit > 1) *(float4*)(a.g + r * a.H + h) = g;
+    if (a.delta) {
+      float4 g2 = *(const float4*)(a.g + (a.n_pad + r) * a.H + h);
+      for (int s = 1; s < a.ksplit; ++s) {
+        const float4 q = *(const float4*)(a.g + ((int64_t)s * a.g_rows + a.n_pad + r) * a.H + h);
+        g2.x += q.x; g2.y += q.y; g2.z += q.z; g2.w += q.w;
+      }
+      g.x = (g.x - dl * g2.x) * iz; g.y = (g.y - dl * g2.y) * iz;
+      g.z = (g.z - dl * g2.z) * iz; g.w = (g.w - dl * g2.w) * iz;
+    }
+    if (a.ksplit > 1 || a.delta) *(float4*)(a.g + r * a.H + h) = g;
     nrm = fmaf(g.x, g.x, fmaf(g.y, g.y, fmaf(g.z, g.z, fmaf(g.w, g.w, nrm))));
     const float4 p = {g.x * sp, g.y * sp, g.z * sp, g.w * sp};
     store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, p);
@@ -811,6 +973,10 @@ __global__ __launch_bounds__(256) void pool_final_kernel(PoolArgs a) {
 // Workspace layout and the entry point
 // ---------------------------------------------------------------------------------------
 struct FusedLayout {
+  bool use_dma;      // logit passes staged by direct global->LDS loads
+  bool single;       // single-sweep scheme (needs use_dma)
+  int strips1;       // vocabulary strips of the single sweep
+  size_t o_ref_t2, o_delta, o_invz;
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
@@ -833,12 +999,23 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   if (strips > vt_total) strips = vt_total;
   if (strips > kMaxStrips) strips = kMaxStrips;
   L.strips = strips;
+  // direct-to-LDS staging uses 32-bit byte offsets from each operand's base and a
+  // pipeline of at least two k-steps per head
+  const int64_t maxH = p->H_s > p->H_t ? p->H_s : p->H_t;
+  L.use_dma = !getenv("ADWIN_NO_DMA") && p->T * maxH * 2 < (int64_t(1) << 32) &&
+              (int64_t)p->V * maxH * 2 < (int64_t(1) << 32) && p->H_s >= 2 * kBK && p->H_t >= 2 * kBK;
+  L.single = L.use_dma && !getenv("ADWIN_TWO_SWEEP");
+  int strips1 = env_int("ADWIN_STRIPS2", 32);
+  if (strips1 > vt_total) strips1 = vt_total;
+  if (strips1 > kMaxStrips) strips1 = kMaxStrips;
+  L.strips1 = strips1;
+  const int halves = L.single ? 2 : 1;     // the single sweep stores two factors per logit
   int64_t slab = env_int("ADWIN_SLAB_ROWS", 8192);
   slab = (int64_t)align_up((size_t)slab, kTileTokens);
   if (slab > n_pad) slab = n_pad;
   L.slab_rows = slab;
   const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
-  const int64_t tiles = (slab / kGradTile) * h_tiles;
+  const int64_t tiles = halves * (slab / kGradTile) * h_tiles;
   int ks = (int)(256 / (tiles > 0 ? tiles : 1));
   const int nk = (int)(L.Vp / kBK);
   if (ks > 16) ks = 16;
@@ -850,14 +1027,17 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_plan = take(PlanBlobLayout(p->B).bytes);
   L.o_row_idx = take(sizeof(int32_t) * (size_t)n_pad);
   L.o_row_seq = take(sizeof(int32_t) * (size_t)n_pad);
-  L.o_part = take(sizeof(float) * 5 * (size_t)strips * (size_t)n_pad);
+  L.o_part = take(sizeof(float) * 5 * (size_t)(strips > strips1 ? strips : strips1) * (size_t)n_pad);
+  L.o_ref_t2 = take(sizeof(float) * (size_t)n_pad);
+  L.o_delta = take(sizeof(float) * (size_t)n_pad);
+  L.o_invz = take(sizeof(float) * (size_t)n_pad);
   L.o_lse2 = take(sizeof(float) * (size_t)n_pad);
   L.o_mu = take(sizeof(float) * (size_t)n_pad);
   L.o_klr = take(sizeof(float) * (size_t)n_pad);
   L.o_rownorm = take(sizeof(float) * (size_t)n_pad);
   L.o_WsT = take(2 * (size_t)p->H_s * (size_t)L.Vp);
-  L.o_slab = take(2 * (size_t)slab * (size_t)L.Vp);
-  L.o_g = take(sizeof(float) * (size_t)ks * (size_t)n_pad * (size_t)p->H_s);
+  L.o_slab = take(2 * (size_t)halves * (size_t)slab * (size_t)L.Vp);
+  L.o_g = take(sizeof(float) * (size_t)ks * (size_t)halves * (size_t)n_pad * (size_t)p->H_s);
   const size_t nch = (size_t)(hp.n_chunks > 0 ? hp.n_chunks : 1);
   L.o_pp = take(sizeof(float) * nch * (size_t)p->H_s);
   L.o_pf = take(sizeof(float) * nch * (size_t)p->H_s);
@@ -892,10 +1072,13 @@ static hipError_t ensure_lds_opt_in() {
   e = hipFuncSetAttribute((const void*)logit_pass_kernel<true>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kLogitLds);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<false>,
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeStats>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<true>,
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeDz>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingle>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)grad_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -969,10 +1152,8 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
                                                   p->V, p->H_s, L.Vp);
       ADWIN_HIP_TRY(hipGetLastError());
     }
-    // direct-to-LDS staging uses 32-bit byte offsets from each operand's base
-    const int64_t maxH = p->H_s > p->H_t ? p->H_s : p->H_t;
-    const bool use_dma = !getenv("ADWIN_NO_DMA") && p->T * maxH * 2 < (int64_t(1) << 32) &&
-                         p->H_s >= 2 * kBK && p->H_t >= 2 * kBK;
+    const bool use_dma = L.use_dma;
+    const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
     LogitPassArgs la;
     la.h_s = (const __bf16*)p->h_s; la.h_t = (const __bf16*)p->h_t;
     la.W_s = (const __bf16*)p->W_s; la.W_t = (const __bf16*)p->W_t;
@@ -982,52 +1163,91 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     la.part = (float*)(ws + L.o_part);
     la.lse2 = (const float*)(ws + L.o_lse2); la.mu = (const float*)(ws + L.o_mu);
     la.slab = (__bf16*)(ws + L.o_slab); la.Vp = L.Vp; la.slab_row0 = 0;
-    // pass 1 over all token tiles
-    phase(ADWIN_PHASE_STATS);
-    {
-      la.tile0 = 0; la.n_tiles = n_tiles; la.strips = L.strips;
-      la.tg = env_int("ADWIN_TG", 4);
-      la.debug_same = getenv("ADWIN_DEBUG_SAME") ? atoi(getenv("ADWIN_DEBUG_SAME")) : 0;
-      const int groups = (n_tiles + la.tg - 1) / la.tg;
-      if (use_dma)
-        logit_pass_dma_kernel<false><<<(unsigned)(groups * la.tg * L.strips), 256, kDmaLds, stream>>>(la);
-      else
-        logit_pass_kernel<false><<<(unsigned)(groups * la.tg * L.strips), 256, kLogitLds, stream>>>(la);
+    la.ref_s2 = (const float*)(ws + L.o_lse2); la.ref_t2 = (const float*)(ws + L.o_ref_t2);
+    la.mu0 = (const float*)(ws + L.o_mu); la.e2_off = 0;
+    la.tg = env_int("ADWIN_TG", 4);
+    la.debug_same = getenv("ADWIN_DEBUG_SAME") ? atoi(getenv("ADWIN_DEBUG_SAME")) : 0;
+    MergeArgs m;
+    m.part = la.part; m.strips = L.strips; m.n_pad = n_pad; m.n_rows = hp.n_rows;
+    m.row_idx = pl.row_idx;
+    m.h_s = la.h_s; m.h_t = la.h_t; m.W_s = la.W_s; m.W_t = la.W_t;
+    m.H_s = p->H_s; m.H_t = p->H_t; m.V = p->V; m.ids = p->ids;
+    m.lse2 = (float*)(ws + L.o_lse2); m.mu = (float*)(ws + L.o_mu); m.klr = klr;
+    m.kl = p->kl; m.c = p->c; m.status = p->status_dev;
+    GradArgs ga;
+    ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.Vp = L.Vp;
+    ga.g = gws; ga.H = p->H_s; ga.h_tiles = h_tiles; ga.ksplit = L.ksplit;
+    if (L.single) {
+      // Single sweep.  (1) online statistics of vocabulary tile 0 give each row its fixed
+      // references; (2) per row slab: one sweep over the vocabulary producing the strip sums
+      // and the two gradient factors, then one GEMM of both factors with W_s; (3) merge.
+      la.tile0 = 0; la.n_tiles = n_tiles; la.strips = 1; la.vt_total = 1;
+      {
+        const int groups = (n_tiles + la.tg - 1) / la.tg;
+        logit_pass_dma_kernel<kModeStats><<<(unsigned)(groups * la.tg), 256, kDmaLds, stream>>>(la);
+        ADWIN_HIP_TRY(hipGetLastError());
+        make_refs_kernel<<<(unsigned)((n_pad + 255) / 256), 256, 0, stream>>>(
+            la.part, n_pad, (float*)(ws + L.o_lse2), (float*)(ws + L.o_ref_t2), (float*)(ws + L.o_mu));
+        ADWIN_HIP_TRY(hipGetLastError());
+      }
+      la.vt_total = vt_total; la.strips = L.strips1;
+      ga.g_rows = 2 * n_pad; ga.half_off = n_pad;
+      for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
+        const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
+        la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
+        la.slab_row0 = r0; la.e2_off = rows * L.Vp;
+        const int groups = (la.n_tiles + la.tg - 1) / la.tg;
+        phase(ADWIN_PHASE_STATS);
+        logit_pass_dma_kernel<kModeSingle><<<(unsigned)(groups * la.tg * L.strips1), 256, kDmaLds, stream>>>(la);
+        ADWIN_HIP_TRY(hipGetLastError());
+        phase(ADWIN_PHASE_GRAD);
+        ga.slab_row0 = r0;
+        ga.half_tiles = (int)(rows / kGradTile); ga.row_tiles = 2 * ga.half_tiles;
+        grad_gemm_kernel<<<(unsigned)(ga.row_tiles * h_tiles * L.ksplit), 256, kGradLds, stream>>>(ga);
+        ADWIN_HIP_TRY(hipGetLastError());
+      }
+      phase(ADWIN_PHASE_MERGE);
+      MergeSingleArgs ms;
+      ms.m = m; ms.m.strips = L.strips1;
+      ms.ref_s2 = la.ref_s2; ms.ref_t2 = la.ref_t2; ms.mu0 = la.mu0;
+      ms.delta = (float*)(ws + L.o_delta); ms.inv_z = (float*)(ws + L.o_invz);
+      merge_single_kernel<<<(unsigned)((n_pad + 3) / 4), 256, 0, stream>>>(ms);
       ADWIN_HIP_TRY(hipGetLastError());
-    }
-    phase(ADWIN_PHASE_MERGE);
-    {
-      MergeArgs m;
-      m.part = la.part; m.strips = L.strips; m.n_pad = n_pad; m.n_rows = hp.n_rows;
-      m.row_idx = pl.row_idx;
-      m.h_s = la.h_s; m.h_t = la.h_t; m.W_s = la.W_s; m.W_t = la.W_t;
-      m.H_s = p->H_s; m.H_t = p->H_t; m.V = p->V; m.ids = p->ids;
-      m.lse2 = (float*)(ws + L.o_lse2); m.mu = (float*)(ws + L.o_mu); m.klr = klr;
-      m.kl = p->kl; m.c = p->c; m.status = p->status_dev;
+    } else {
+      // Two sweeps: statistics over all token tiles, merge, then per row slab the dz sweep
+      // and its GEMM with W_s.
+      phase(ADWIN_PHASE_STATS);
+      {
+        la.tile0 = 0; la.n_tiles = n_tiles; la.strips = L.strips;
+        const int groups = (n_tiles + la.tg - 1) / la.tg;
+        if (use_dma)
+          logit_pass_dma_kernel<kModeStats><<<(unsigned)(groups * la.tg * L.strips), 256, kDmaLds, stream>>>(la);
+        else
+          logit_pass_kernel<false><<<(unsigned)(groups * la.tg * L.strips), 256, kLogitLds, stream>>>(la);
+        ADWIN_HIP_TRY(hipGetLastError());
+      }
+      phase(ADWIN_PHASE_MERGE);
       merge_stats_kernel<<<(unsigned)((n_pad + 3) / 4), 256, 0, stream>>>(m);
       ADWIN_HIP_TRY(hipGetLastError());
-    }
-    // pass 2 + 3, one row slab at a time
-    const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
-    const int strips2 = env_int("ADWIN_STRIPS2", 32) < vt_total ? env_int("ADWIN_STRIPS2", 32) : vt_total;
-    for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
-      const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
-      la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
-      la.strips = strips2; la.slab_row0 = r0;
-      const int groups = (la.n_tiles + la.tg - 1) / la.tg;
-      phase(ADWIN_PHASE_DZ);
-      if (use_dma)
-        logit_pass_dma_kernel<true><<<(unsigned)(groups * la.tg * strips2), 256, kDmaLds, stream>>>(la);
-      else
-        logit_pass_kernel<true><<<(unsigned)(groups * la.tg * strips2), 256, kLogitLds, stream>>>(la);
-      ADWIN_HIP_TRY(hipGetLastError());
-      phase(ADWIN_PHASE_GRAD);
-      GradArgs ga;
-      ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.Vp = L.Vp;
-      ga.g = gws; ga.n_pad = n_pad; ga.H = p->H_s; ga.slab_row0 = r0;
-      ga.row_tiles = (int)(rows / kGradTile); ga.h_tiles = h_tiles; ga.ksplit = L.ksplit;
-      grad_gemm_kernel<<<(unsigned)(ga.row_tiles * h_tiles * L.ksplit), 256, kGradLds, stream>>>(ga);
-      ADWIN_HIP_TRY(hipGetLastError());
+      const int strips2 = L.strips1;
+      ga.g_rows = n_pad; ga.half_off = 0;
+      for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
+        const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
+        la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
+        la.strips = strips2; la.slab_row0 = r0;
+        const int groups = (la.n_tiles + la.tg - 1) / la.tg;
+        phase(ADWIN_PHASE_DZ);
+        if (use_dma)
+          logit_pass_dma_kernel<kModeDz><<<(unsigned)(groups * la.tg * strips2), 256, kDmaLds, stream>>>(la);
+        else
+          logit_pass_kernel<true><<<(unsigned)(groups * la.tg * strips2), 256, kLogitLds, stream>>>(la);
+        ADWIN_HIP_TRY(hipGetLastError());
+        phase(ADWIN_PHASE_GRAD);
+        ga.slab_row0 = r0;
+        ga.row_tiles = (int)(rows / kGradTile); ga.half_tiles = ga.row_tiles;
+        grad_gemm_kernel<<<(unsigned)(ga.row_tiles * h_tiles * L.ksplit), 256, kGradLds, stream>>>(ga);
+        ADWIN_HIP_TRY(hipGetLastError());
+      }
     }
   }
   // finalize over every packed row (also zero-fills rows outside the windows)
@@ -1036,6 +1256,9 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     FinalizeArgs f;
     f.pl = pl; f.B = p->B; f.T = p->T; f.probe = probe;
     f.g = gws; f.ksplit = L.ksplit; f.n_pad = n_pad; f.H = p->H_s;
+    f.g_rows = L.single ? 2 * n_pad : n_pad;
+    f.delta = L.single ? (const float*)(ws + L.o_delta) : nullptr;
+    f.inv_z = L.single ? (const float*)(ws + L.o_invz) : nullptr;
     f.grad_scale = p->grad_scale; f.dh_bf16 = p->dh_dtype == ADWIN_DT_BF16;
     f.dh_prefix = p->dh_prefix; f.dh_full = p->dh_full; f.rownorm = rownorm;
     finalize_kernel<<<(unsigned)((p->T + 3) / 4), 256, 0, stream>>>(f);

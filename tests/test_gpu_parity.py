@@ -138,3 +138,18 @@ def test_logits_given_matches_oracle_every_element(B, name, reduction):
     # synthetic per-row shift does; KL must not see it (up to bf16 re-rounding of inputs)
     assert np.all(np.abs(got["dz"].astype(np.float64).sum(axis=1)) <=
                   1e-2 * np.abs(got["dz"]).sum(axis=1) + 1e-30)
+
+
+@pytest.mark.parametrize("env", [{"ADWIN_TWO_SWEEP": "1"}, {"ADWIN_NO_DMA": "1"}])
+def test_fallback_schemes_match_oracle(B, env, monkeypatch):
+    """The two-sweep scheme and the register-staged logit kernel stay available (selected
+    by environment variables read at call time) and meet the same bar."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    w = synth.workload("ragged_small")
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SUM, grad_scale=1.0, mode=w.mode)
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, grad_scale=1.0, dh_dtype=B.ADWIN_DT_F32)
+    _check_fused(w, got, ref, O.RED_SUM)
