@@ -129,13 +129,12 @@ struct LogitPassArgs {
   int n_tiles;                 // token tiles in this launch
   int strips;                  // vocabulary strips
   int tg;                      // token tiles per workgroup group (share W tiles in one L2)
-  int debug_same;              // timing experiment (results invalid): every workgroup reads the same tiles
   int vt_total;                // vocabulary tiles (of 128)
   // pass 1 out: [5][strips][n_pad]
   float* part;
   // pass 2 in / out
   const float* lse2; const float* mu;
-  __bf16* slab; int64_t Vp; int64_t slab_row0;
+  __bf16* slab; int64_t Vp;    // slab blocks of the launch's token tiles, tile0 first
   // single-sweep mode: fixed per-row references and the offset of the second slab half
   const float* ref_s2; const float* ref_t2; const float* mu0;
   int64_t e2_off;
@@ -186,14 +185,20 @@ __device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f
   }
 }
 
-// dz = p_s ((z_s - z_t) - mu), rounded to bf16, into slab rows row0 + fn*32 + lane%32.
+// Slab layout (the A operand of the gradient GEMM, see "Tile images" below): block
+// (row tile, k-step) of 256 rows x 64 vocabulary entries, row r at r * 64 elements, its
+// 8-entry chunk c at chunk position c ^ ((r >> 1) & 7).  A 256 x 128 logit tile covers the
+// two consecutive blocks 2 vt and 2 vt + 1 of its row tile; `blk` points at the first.
+constexpr int kSlabBlock = kTileTokens * kBK;   // elements per block
+
+// dz = p_s ((z_s - z_t) - mu), rounded to bf16, into rows wrow + fn*32 + lane%32 of the tile.
 __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
-                                            const float (&lse2)[2], const float (&mu)[2], __bf16* slab,
-                                            int64_t Vp, int64_t row0, int v0, int V, bool tail, int lane) {
-  const int vlane = v0 + 4 * (lane >> 5);
+                                            const float (&lse2)[2], const float (&mu)[2], __bf16* blk,
+                                            int wrow, int v0, int V, bool tail, int lane) {
+  const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
-    __bf16* out = slab + (row0 + fn * 32 + (lane & 31)) * Vp + vlane;
+    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK + 4 * half;
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
@@ -208,7 +213,7 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
         uint2 o;
         o.x = pack_bf16(d[0], d[1]);
         o.y = pack_bf16(d[2], d[3]);
-        *(uint2*)(out + fm * 32 + 8 * q) = o;
+        *(uint2*)(out + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3)) = o;
       }
   }
 }
@@ -225,12 +230,12 @@ struct LaneSums { float Z_s[2], A_s[2], Z_t[2]; };
 __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                 LaneSums& sm, const float (&rs2)[2],
                                                 const float (&rt2)[2], const float (&mu0)[2],
-                                                __bf16* slab, int64_t Vp, int64_t e2_off, int64_t row0,
+                                                __bf16* blk, int64_t e2_off, int wrow,
                                                 int v0, int V, bool tail, int lane) {
-  const int vlane = v0 + 4 * (lane >> 5);
+  const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
-    __bf16* out = slab + (row0 + fn * 32 + (lane & 31)) * Vp + vlane;
+    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK + 4 * half;
     float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn];
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
@@ -254,8 +259,9 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
         uint2 o1, o2;
         o1.x = pack_bf16(e1[0], e1[1]); o1.y = pack_bf16(e1[2], e1[3]);
         o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
-        *(uint2*)(out + fm * 32 + 8 * q) = o1;
-        *(uint2*)(out + e2_off + fm * 32 + 8 * q) = o2;
+        const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
+        *(uint2*)(out + at) = o1;
+        *(uint2*)(out + e2_off + at) = o2;
       }
     sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
   }
@@ -366,8 +372,8 @@ __global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
 
     const bool tail = v0 + kTileVocab > a.V;
     if (!PASS2) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
-    else dz_epilogue(zs, zt, lse2, mu, a.slab, a.Vp, (int64_t)tt * kTileTokens + wave * 64 - a.slab_row0,
-                     v0, a.V, tail, lane);
+    else dz_epilogue(zs, zt, lse2, mu, a.slab + ((int64_t)tt_local * (a.Vp / kBK) + 2 * vt) * kSlabBlock,
+                     wave * 64, v0, a.V, tail, lane);
   }
   if (!PASS2)
     write_partials(st, a.part, a.strips, strip, a.n_pad, (int64_t)tt * kTileTokens + wave * 64, lane);
@@ -508,7 +514,6 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   int tt = a.tile0 + tt_local;
   int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
   int vt_end = (int)((int64_t)a.vt_total * (strip + 1) / a.strips);
-  if (a.debug_same & 1) { vt_end = vt_end - vt_begin; vt_begin = 0; tt = a.tile0; }
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
   // lane -> (row within its 8-row group, chunk position); global chunk = pos ^ swizzle(row)
@@ -615,9 +620,11 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     const bool tail = v0 + kTileVocab > a.V;
     const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
     if (MODE == kModeStats) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
-    else if (MODE == kModeDz) dz_epilogue(zs, zt, lse2, mu, a.slab, a.Vp, row0 - a.slab_row0, v0, a.V, tail, lane);
-    else single_epilogue(zs, zt, sm, rs2, rt2, mu, a.slab, a.Vp, a.e2_off, row0 - a.slab_row0, v0, a.V,
-                         tail, lane);
+    else {
+      __bf16* blk = a.slab + ((int64_t)tt_local * (a.Vp / kBK) + 2 * vt) * kSlabBlock;
+      if (MODE == kModeDz) dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
+      else single_epilogue(zs, zt, sm, rs2, rt2, mu, blk, a.e2_off, wave * 64, v0, a.V, tail, lane);
+    }
   }
   const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
   if (MODE == kModeStats) write_partials(st, a.part, a.strips, strip, a.n_pad, row0, lane);
@@ -763,32 +770,61 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
 }
 
 // ---------------------------------------------------------------------------------------
-// W_s [V, H] -> W_sT [H, Vp] (zero beyond V) so that the gradient GEMM reads both operands
-// k-contiguous.
+// Tile images.  Both operands of the gradient GEMM live in memory as the exact LDS images
+// of its k-steps: block (tile, kt) is 256 rows x 64 k-entries = 32 KiB, row r at r * 128 B,
+// its 16-byte chunk c (k-entries 8 c .. 8 c + 7) at chunk position c ^ ((r >> 1) & 7).
+// Blocks of one tile are consecutive in kt, so a workgroup streams each operand as one
+// sequential run and every wave-load moves 1 KiB of consecutive bytes.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ W,
-                                                            uint16_t* __restrict__ WT, int V, int H,
-                                                            int64_t Vp) {
-  __shared__ uint16_t tile[64][66];
-  const int v0 = blockIdx.x * 64, h0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int i = ty; i < 64; i += 4) {
-    const int v = v0 + i, h = h0 + tx;
-    tile[i][tx] = (v < V && h < H) ? W[(int64_t)v * H + h] : (uint16_t)0;
+constexpr int kImgElems = kGradTile * kBK;            // bf16 elements per block
+constexpr int kImgBytes = kImgElems * 2;              // 32 KiB
+
+// element offset of (row r of the tile, k-entry k of the k-step) inside a block
+__device__ __forceinline__ int img_elem(int r, int k) {
+  return r * kBK + ((((k >> 3) ^ (r >> 1)) & 7) << 3) + (k & 7);
+}
+
+// W_s [V, H] -> images of W_s^T: tile = 256 hidden columns, k = vocabulary (zero beyond V).
+// One workgroup per (k-step, hidden tile): reads 64 rows of W_s, writes one block.
+__global__ __launch_bounds__(256) void wst_image_kernel(const uint16_t* __restrict__ W,
+                                                        uint16_t* __restrict__ img, int V, int H,
+                                                        int nk) {
+  __shared__ uint16_t tile[kBK][kGradTile + 2];
+  const int kt = blockIdx.x, ht = blockIdx.y;
+  const int tid = threadIdx.x;
+  for (int i = 0; i < kBK; ++i) {
+    const int v = kt * kBK + i, h = ht * kGradTile + tid;
+    tile[i][tid] = (v < V && h < H) ? W[(int64_t)v * H + h] : (uint16_t)0;
   }
   __syncthreads();
-  for (int i = ty; i < 64; i += 4) {
-    const int h = h0 + i, v = v0 + tx;
-    if (h < H && v < Vp) WT[(int64_t)h * Vp + v] = tile[tx][i];
+  uint16_t* blk = img + ((int64_t)ht * nk + kt) * kImgElems;
+  // thread -> (row r, chunk position): 2048 chunks of 8 entries, 8 per thread
+  for (int q = tid; q < kGradTile * 8; q += 256) {
+    const int r = q >> 3, pos = q & 7, c = pos ^ ((r >> 1) & 7);
+    uint16_t w[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[e] = tile[c * 8 + e][r];
+    uint4 o;
+    o.x = w[0] | ((uint32_t)w[1] << 16); o.y = w[2] | ((uint32_t)w[3] << 16);
+    o.z = w[4] | ((uint32_t)w[5] << 16); o.w = w[6] | ((uint32_t)w[7] << 16);
+    *(uint4*)(blk + q * 8) = o;
   }
 }
 
 // ---------------------------------------------------------------------------------------
-// Pass 3: g[r][h] = sum_v dz[r][v] W_sT[h][v].  256x256 output tile, 2x2 waves of 128x128.
-// A = dz slab rows (i = row), B = W_sT rows (j = hidden column, contiguous in g).
+// Pass 3: g[r][h] = sum_v dz[r][v] W_s[v][h].  256 x 256 output tile, 2 x 2 waves of
+// 128 x 128.  A = slab rows (i = row), B = rows of W_s^T (j = hidden column, contiguous in
+// g).  The k-steps (one block of each operand, 64 KiB together) go through two LDS stages
+// by direct global->LDS loads.  Per k-step a wave issues its 16 wave-loads of the next
+// k-step in the shadow of the first MFMAs, so that they have the rest of the step (about
+// 1500 matrix-pipe cycles) to land.  The one barrier per k-step sits before the last of
+// the four k16 sub-steps: by then every fragment of the current stage is in registers, so
+// the last sub-step's MFMAs cover the LDS reads of the next stage's first fragments and the
+// matrix pipe never waits for LDS after a barrier.
 // ---------------------------------------------------------------------------------------
 struct GradArgs {
-  const __bf16* slab; const __bf16* WsT; int64_t Vp;
+  const __bf16* slab; const __bf16* WsT;   // tile images
+  int nk_total;             // k-steps (blocks) per tile
   float* g;                 // [ksplit][g_rows][H]
   int64_t g_rows; int H;
   int64_t slab_row0;        // computed-row index of slab row 0
@@ -797,35 +833,96 @@ struct GradArgs {
   int64_t half_off;         // half_off + slab_row0 + ... (single-sweep mode; else half_tiles = row_tiles)
 };
 
-constexpr int kGradStage = 2 * kGradTile * kRowBytes;   // 64 KiB
-constexpr int kGradLds = 2 * kGradStage;
+constexpr int kGradStage = 2 * kImgBytes;     // 64 KiB
+constexpr int kGradLds = 2 * kGradStage;      // 128 KiB
+
+// HEAD: the B block of the next k-step is loaded in sub-step 0 (into the other stage);
+// TAIL: the A block of the k-step after next in sub-step 3 (into this stage, which no wave
+// reads any more once it has passed this step's barrier).  Every block thus has a whole
+// k-step between its first wave-load and the barrier that publishes it.
+template <bool HEAD, bool TAIL, bool LAST>
+__device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][4],
+                                           const char* curA, const char* curB, const char* nxtA,
+                                           const char* nxtB, int lane, uint32_t lds_cur, uint32_t lds_nxt,
+                                           uint32_t voff, const char* sB1, const char* sA2) {
+  const int key = (lane >> 1) & 7, half = lane >> 5;
+  const int rowoff = (lane & 31) * kRowBytes;
+  int sw[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) sw[kk] = rowoff + (((kk * 2 + half) ^ key) << 4);
+#define ADWIN_FENCE __builtin_amdgcn_sched_barrier(0);
+#define ADWIN_MM(KK, I, J)                                                                    \
+  acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][I], fb[(KK) & 1][J],       \
+                                                      acc[I][J], 0, 0, 0);                    \
+  ADWIN_FENCE
+  // side operation M (0..15) in the shadow of MFMA M of sub-step KK: fragment reads of the
+  // next sub-step, then (sub-steps 0 and 1) the 16 wave-loads of the next k-step: 8 KiB
+  // groups d = 0..7 of the A block, then of the B block, each offset by this wave's 1 KiB
+#define ADWIN_SIDE(KK, M)                                                                           \
+  if constexpr ((KK) < 3 && (M) < 8) {                                                              \
+    if constexpr (((M) & 1) == 0)                                                                   \
+      fa[((KK) + 1) & 1][(M) >> 1] = *(const bf16x8*)(curA + ((M) >> 1) * 32 * kRowBytes + sw[(KK) + 1]); \
+    else                                                                                            \
+      fb[((KK) + 1) & 1][(M) >> 1] = *(const bf16x8*)(curB + ((M) >> 1) * 32 * kRowBytes + sw[(KK) + 1]); \
+    ADWIN_FENCE                                                                                     \
+  } else if constexpr ((KK) == 0 && (M) >= 8 && HEAD) {                                             \
+    dma16(lds_nxt + (uint32_t)kImgBytes + (uint32_t)((M) - 8) * 4096u, voff, sB1 + ((M) - 8) * 4096); \
+    ADWIN_FENCE                                                                                     \
+  } else if constexpr ((KK) == 3 && (M) < 8 && !LAST) {                                             \
+    if constexpr (((M) & 1) == 0)                                                                   \
+      fa[0][(M) >> 1] = *(const bf16x8*)(nxtA + ((M) >> 1) * 32 * kRowBytes + sw[0]);               \
+    else                                                                                            \
+      fb[0][(M) >> 1] = *(const bf16x8*)(nxtB + ((M) >> 1) * 32 * kRowBytes + sw[0]);               \
+    ADWIN_FENCE                                                                                     \
+  } else if constexpr ((KK) == 3 && (M) >= 8 && TAIL) {                                             \
+    dma16(lds_cur + (uint32_t)((M) - 8) * 4096u, voff, sA2 + ((M) - 8) * 4096);                     \
+    ADWIN_FENCE                                                                                     \
+  }
+#define ADWIN_ROW(KK, I, M0)                                                    \
+  ADWIN_MM(KK, I, 0) ADWIN_SIDE(KK, (M0) + 0) ADWIN_MM(KK, I, 1) ADWIN_SIDE(KK, (M0) + 1) \
+  ADWIN_MM(KK, I, 2) ADWIN_SIDE(KK, (M0) + 2) ADWIN_MM(KK, I, 3) ADWIN_SIDE(KK, (M0) + 3)
+#define ADWIN_SUB(KK) ADWIN_ROW(KK, 0, 0) ADWIN_ROW(KK, 1, 4) ADWIN_ROW(KK, 2, 8) ADWIN_ROW(KK, 3, 12)
+  ADWIN_FENCE
+  ADWIN_SUB(0)
+  ADWIN_SUB(1)
+  ADWIN_SUB(2)
+  // every fragment of this stage is in registers; the next stage's loads must have landed
+  // before its first fragments are read in the shadow of the last sub-step
+  if constexpr (!LAST) {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  ADWIN_FENCE
+  ADWIN_SUB(3)
+#undef ADWIN_SUB
+#undef ADWIN_ROW
+#undef ADWIN_SIDE
+#undef ADWIN_MM
+#undef ADWIN_FENCE
+}
 
 __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   extern __shared__ __align__(16) char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int tiles = a.row_tiles * a.h_tiles;
   const int split = vid / tiles;
   vid -= split * tiles;
   const int rt = vid / a.h_tiles, ht = vid % a.h_tiles;
+  const int k_begin = (int)((int64_t)a.nk_total * split / a.ksplit);
+  const int k_end = (int)((int64_t)a.nk_total * (split + 1) / a.ksplit);
+  const int nk = k_end - k_begin;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
-  const int nk_total = (int)(a.Vp / kBK);
-  const int k_begin = (int)((int64_t)nk_total * split / a.ksplit);
-  const int k_end = (int)((int64_t)nk_total * (split + 1) / a.ksplit);
+  // wave-load d of a block covers its bytes [4096 d + 1024 wave, + 1024): lane l moves the
+  // 16 bytes at offset 16 l of that KiB to the same place of the LDS stage
+  const uint32_t voff = (uint32_t)lane * 16u;
+  const char* sA = (const char*)a.slab + ((int64_t)rt * a.nk_total + k_begin) * kImgBytes + wave * 1024;
+  const char* sB = (const char*)a.WsT + ((int64_t)ht * a.nk_total + k_begin) * kImgBytes + wave * 1024;
+  const uint32_t ldsw = lds0 + (uint32_t)wave * 1024u;
 
-  RowStager<kGradTile> sa, sb;
-  {
-    const int r = tid >> 3, c = tid & 7;
-#pragma unroll
-    for (int i = 0; i < kGradTile / 32; ++i) {
-      const int64_t row = (int64_t)rt * kGradTile + r + 32 * i;
-      sa.p[i] = (const uint4*)(a.slab + row * a.Vp) + c;
-      int h = ht * kGradTile + r + 32 * i;
-      h = h < a.H ? h : a.H - 1;
-      sb.p[i] = (const uint4*)(a.WsT + (int64_t)h * a.Vp) + c;
-    }
-  }
   f32x16 acc[4][4];
 #pragma unroll
   for (int fm = 0; fm < 4; ++fm)
@@ -833,8 +930,54 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     for (int fn = 0; fn < 4; ++fn)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[fm][fn][e] = 0.f;
-  gemm_kloop<kGradTile, kGradTile, 4, 4>(acc, sa, sb, k_begin, k_end - k_begin, lds, kGradStage,
-                                         wm * 128 * kRowBytes, wn * 128 * kRowBytes, tid);
+
+  if (nk > 0) {
+    // stage 0 of the first k-step, then its first fragments
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+      dma16(ldsw + (uint32_t)d * 4096u, voff, sA + d * 4096);
+      dma16(ldsw + (uint32_t)kImgBytes + (uint32_t)d * 4096u, voff, sB + d * 4096);
+    }
+    wait_vm<0>();
+    __syncthreads();
+    bf16x8 fa[2][4], fb[2][4];
+    const int waveA = wm * 128 * kRowBytes, waveB = kImgBytes + wn * 128 * kRowBytes;
+    {
+      const int key = (lane >> 1) & 7, half = lane >> 5;
+      const int sw0 = (lane & 31) * kRowBytes + ((half ^ key) << 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        fa[0][i] = *(const bf16x8*)(lds + waveA + i * 32 * kRowBytes + sw0);
+        fb[0][i] = *(const bf16x8*)(lds + waveB + i * 32 * kRowBytes + sw0);
+      }
+    }
+    // A block of k-step 1 (the loop loads B of s + 1 and A of s + 2 in k-step s)
+    if (nk > 1) {
+#pragma unroll
+      for (int d = 0; d < 8; ++d) dma16(ldsw + kGradStage + (uint32_t)d * 4096u, voff, sA + kImgBytes + d * 4096);
+    }
+    int s = 0;
+    for (; s + 2 < nk; ++s) {
+      const char* cur = lds + (s & 1) * kGradStage;
+      const char* nxt = lds + ((s + 1) & 1) * kGradStage;
+      grad_kstep<true, true, false>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
+                                    ldsw + (s & 1) * kGradStage, ldsw + ((s + 1) & 1) * kGradStage, voff,
+                                    sB + (int64_t)(s + 1) * kImgBytes, sA + (int64_t)(s + 2) * kImgBytes);
+    }
+    if (s + 1 < nk) {
+      const char* cur = lds + (s & 1) * kGradStage;
+      const char* nxt = lds + ((s + 1) & 1) * kGradStage;
+      grad_kstep<true, false, false>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
+                                     ldsw + (s & 1) * kGradStage, ldsw + ((s + 1) & 1) * kGradStage, voff,
+                                     sB + (int64_t)(s + 1) * kImgBytes, sA);
+      ++s;
+    }
+    {
+      const char* cur = lds + (s & 1) * kGradStage;
+      grad_kstep<false, false, true>(acc, fa, fb, cur + waveA, cur + waveB, cur, cur, lane, ldsw, ldsw, voff,
+                                     sB, sA);
+    }
+  }
   float* g = a.g + (int64_t)split * a.g_rows * a.H;
   const int64_t out_row0 = rt < a.half_tiles ? a.slab_row0 + (int64_t)rt * kGradTile
                                              : a.half_off + a.slab_row0 + (int64_t)(rt - a.half_tiles) * kGradTile;
@@ -846,8 +989,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       if (h < a.H) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int64_t r = out_row0 + wm * 128 + fm * 32 +
-                            8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+          const int64_t r = out_row0 + wm * 128 + fm * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
           g[r * a.H + h] = acc[fm][fn][e];
         }
       }
@@ -1035,7 +1177,7 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_mu = take(sizeof(float) * (size_t)n_pad);
   L.o_klr = take(sizeof(float) * (size_t)n_pad);
   L.o_rownorm = take(sizeof(float) * (size_t)n_pad);
-  L.o_WsT = take(2 * (size_t)p->H_s * (size_t)L.Vp);
+  L.o_WsT = take(2 * (size_t)h_tiles * kGradTile * (size_t)L.Vp);
   L.o_slab = take(2 * (size_t)halves * (size_t)slab * (size_t)L.Vp);
   L.o_g = take(sizeof(float) * (size_t)ks * (size_t)halves * (size_t)n_pad * (size_t)p->H_s);
   const size_t nch = (size_t)(hp.n_chunks > 0 ? hp.n_chunks : 1);
@@ -1047,6 +1189,10 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_racc = take(sizeof(double) * 4 * (size_t)p->B);
   L.total = o;
   return L;
+}
+
+static void launch_grad(const GradArgs& ga, const FusedLayout& L, hipStream_t stream) {
+  grad_gemm_kernel<<<(unsigned)(ga.row_tiles * ga.h_tiles * L.ksplit), 256, kGradLds, stream>>>(ga);
 }
 
 static int check_problem(const adwin_opd_problem* p) {
@@ -1145,15 +1291,15 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     ADWIN_HIP_TRY(launch_build_rows(pl, p->B, hp.n_rows, n_pad, stream));
     const int vt_total = (int)(L.Vp / kTileVocab);
     const int n_tiles = (int)(n_pad / kTileTokens);
-    // W_s^T for the gradient GEMM
+    // tile images of W_s^T for the gradient GEMM
+    const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
     {
-      dim3 g((unsigned)((L.Vp + 63) / 64), (unsigned)((p->H_s + 63) / 64));
-      transpose_pad_kernel<<<g, 256, 0, stream>>>((const uint16_t*)p->W_s, (uint16_t*)(ws + L.o_WsT),
-                                                  p->V, p->H_s, L.Vp);
+      dim3 g((unsigned)(L.Vp / kBK), (unsigned)h_tiles);
+      wst_image_kernel<<<g, 256, 0, stream>>>((const uint16_t*)p->W_s, (uint16_t*)(ws + L.o_WsT), p->V,
+                                              p->H_s, (int)(L.Vp / kBK));
       ADWIN_HIP_TRY(hipGetLastError());
     }
     const bool use_dma = L.use_dma;
-    const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
     LogitPassArgs la;
     la.h_s = (const __bf16*)p->h_s; la.h_t = (const __bf16*)p->h_t;
     la.W_s = (const __bf16*)p->W_s; la.W_t = (const __bf16*)p->W_t;
@@ -1162,11 +1308,10 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     la.vt_total = vt_total;
     la.part = (float*)(ws + L.o_part);
     la.lse2 = (const float*)(ws + L.o_lse2); la.mu = (const float*)(ws + L.o_mu);
-    la.slab = (__bf16*)(ws + L.o_slab); la.Vp = L.Vp; la.slab_row0 = 0;
+    la.slab = (__bf16*)(ws + L.o_slab); la.Vp = L.Vp;
     la.ref_s2 = (const float*)(ws + L.o_lse2); la.ref_t2 = (const float*)(ws + L.o_ref_t2);
     la.mu0 = (const float*)(ws + L.o_mu); la.e2_off = 0;
     la.tg = env_int("ADWIN_TG", 4);
-    la.debug_same = getenv("ADWIN_DEBUG_SAME") ? atoi(getenv("ADWIN_DEBUG_SAME")) : 0;
     MergeArgs m;
     m.part = la.part; m.strips = L.strips; m.n_pad = n_pad; m.n_rows = hp.n_rows;
     m.row_idx = pl.row_idx;
@@ -1175,7 +1320,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     m.lse2 = (float*)(ws + L.o_lse2); m.mu = (float*)(ws + L.o_mu); m.klr = klr;
     m.kl = p->kl; m.c = p->c; m.status = p->status_dev;
     GradArgs ga;
-    ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.Vp = L.Vp;
+    ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.nk_total = (int)(L.Vp / kBK);
     ga.g = gws; ga.H = p->H_s; ga.h_tiles = h_tiles; ga.ksplit = L.ksplit;
     if (L.single) {
       // Single sweep.  (1) online statistics of vocabulary tile 0 give each row its fixed
@@ -1195,7 +1340,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
       for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
         const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
         la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
-        la.slab_row0 = r0; la.e2_off = rows * L.Vp;
+        la.e2_off = rows * L.Vp;
         const int groups = (la.n_tiles + la.tg - 1) / la.tg;
         phase(ADWIN_PHASE_STATS);
         logit_pass_dma_kernel<kModeSingle><<<(unsigned)(groups * la.tg * L.strips1), 256, kDmaLds, stream>>>(la);
@@ -1203,7 +1348,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         phase(ADWIN_PHASE_GRAD);
         ga.slab_row0 = r0;
         ga.half_tiles = (int)(rows / kGradTile); ga.row_tiles = 2 * ga.half_tiles;
-        grad_gemm_kernel<<<(unsigned)(ga.row_tiles * h_tiles * L.ksplit), 256, kGradLds, stream>>>(ga);
+        launch_grad(ga, L, stream);
         ADWIN_HIP_TRY(hipGetLastError());
       }
       phase(ADWIN_PHASE_MERGE);
@@ -1234,7 +1379,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
       for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
         const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
         la.tile0 = (int)(r0 / kTileTokens); la.n_tiles = (int)(rows / kTileTokens);
-        la.strips = strips2; la.slab_row0 = r0;
+        la.strips = strips2;
         const int groups = (la.n_tiles + la.tg - 1) / la.tg;
         phase(ADWIN_PHASE_DZ);
         if (use_dma)
@@ -1245,7 +1390,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         phase(ADWIN_PHASE_GRAD);
         ga.slab_row0 = r0;
         ga.row_tiles = (int)(rows / kGradTile); ga.half_tiles = ga.row_tiles;
-        grad_gemm_kernel<<<(unsigned)(ga.row_tiles * h_tiles * L.ksplit), 256, kGradLds, stream>>>(ga);
+        launch_grad(ga, L, stream);
         ADWIN_HIP_TRY(hipGetLastError());
       }
     }
