@@ -227,11 +227,12 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
 // E1 goes to slab rows row0.., E2 to the same rows e2_off elements further on.
 struct LaneSums { float Z_s[2], A_s[2], Z_t[2]; };
 
+template <bool TAIL>
 __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                 LaneSums& sm, const float (&rs2)[2],
                                                 const float (&rt2)[2], const float (&mu0)[2],
                                                 __bf16* blk, int64_t e2_off, int wrow,
-                                                int v0, int V, bool tail, int lane) {
+                                                int v0, int V, int lane) {
   const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
@@ -242,14 +243,14 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float e1[4], e2[4];
-        const bool ok = !tail || (vlane + fm * 32 + 8 * q) < V;
+        const bool ok = !TAIL || (vlane + fm * 32 + 8 * q) < V;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
           float es = fast_exp2(fmaf(s, kLog2e, -rs2[fn]));
           float et = fast_exp2(fmaf(t, kLog2e, -rt2[fn]));
           float d = s - t;
-          if (!ok) { es = 0.f; et = 0.f; d = 0.f; }
+          if (TAIL && !ok) { es = 0.f; et = 0.f; d = 0.f; }
           Zs += es;
           As = fmaf(es, d, As);
           Zt += et;
@@ -411,32 +412,7 @@ __device__ __forceinline__ void wait_vm() {
 
 struct DmaOffsets { uint32_t a[kTileVocab / 32]; uint32_t b[kTileTokens / 32]; };
 
-// Issues wave-loads [Q*3, Q*3+3) of the 12 this wave owns for one stage: groups wave,
-// wave+4, ... of the 48 eight-row groups ([A rows 0..127 | B rows 0..255]).
-template <int Q>
-__device__ __forceinline__ void dma_quarter(uint32_t lds_stage, int wave, const DmaOffsets& o,
-                                            const char* sA, const char* sB) {
-#pragma unroll
-  for (int i = Q * 3; i < Q * 3 + 3; ++i) {
-    if (i < kTileVocab / 32)
-      dma16(lds_stage + (uint32_t)(wave + 4 * i) * 1024u, o.a[i], sA);
-    else
-      dma16(lds_stage + (uint32_t)(kTileVocab / 8 + wave + 4 * (i - kTileVocab / 32)) * 1024u,
-            o.b[i - kTileVocab / 32], sB);
-  }
-}
-
-__device__ __forceinline__ void dma_stage(uint32_t lds_stage, int wave, const DmaOffsets& o,
-                                          const char* sA, const char* sB) {
-  dma_quarter<0>(lds_stage, wave, o, sA, sB);
-  dma_quarter<1>(lds_stage, wave, o, sA, sB);
-  dma_quarter<2>(lds_stage, wave, o, sA, sB);
-  dma_quarter<3>(lds_stage, wave, o, sA, sB);
-}
-
-// One staged k-step of MFMAs with the next-but-one stage's loads spread between the four
-// k16 sub-steps, so that the vector-memory issue never stalls all four waves at once.
-// Wave-load i (0..11) of this wave for one stage.
+// Wave-load I (0..11) of this wave for one stage.
 template <int I>
 __device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, const DmaOffsets& o,
                                         const char* sA, const char* sB) {
@@ -447,53 +423,57 @@ __device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, const DmaO
           o.b[I - kTileVocab / 32], sB);
 }
 
-// One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  The instruction
-// order is pinned: after each MFMA exactly one side operation is issued in its shadow --
-// an LDS read of a fragment of the next sub-step (fragments are double-buffered) or one
-// of the 12 global->LDS loads of the stage two k-steps ahead -- so that neither the LDS
-// latency nor the vector-memory issue ever holds up the matrix pipe.
-template <bool ISSUE>
-__device__ __forceinline__ void mma_stage_dma(f32x16 (&acc)[4][2], const char* tA, const char* tB,
-                                              int lane, uint32_t lds_stage, int wave,
-                                              const DmaOffsets& o, const char* sA, const char* sB) {
+// One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  On entry fa[0],
+// fb[0] hold the fragments of sub-step 0.  The instruction order is pinned: after each MFMA
+// one or two side operations are issued in its shadow -- an LDS read of a fragment of the
+// next sub-step (fragments are double-buffered) and, when ISSUE, one of the 12 global->LDS
+// loads of the stage two k-steps ahead -- so that neither the LDS latency nor the
+// vector-memory issue holds up the matrix pipe.  The one barrier of the k-step sits before
+// the last sub-step: by then every fragment of this stage is in registers, and the last
+// sub-step's MFMAs cover the reads of the next stage's first fragments (stage `nxt`, whose
+// loads were issued one k-step earlier and are waited for here).  LAST: no next stage in
+// this vocabulary tile; no barrier and no fragment reads.
+template <bool ISSUE, bool LAST>
+__device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
+                                            const char* curA, const char* curB, const char* nxtA,
+                                            const char* nxtB, int lane, uint32_t lds_stage, int wave,
+                                            const DmaOffsets& o, const char* sA, const char* sB) {
   const int key = (lane >> 1) & 7, half = lane >> 5;
-  const char* pA[4];
-  const char* pB[4];
+  const int rowoff = (lane & 31) * kRowBytes;
+  int sw[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const int sw = ((kk * 2 + half) ^ key) << 4;
-    pA[kk] = tA + (lane & 31) * kRowBytes + sw;
-    pB[kk] = tB + (lane & 31) * kRowBytes + sw;
-  }
-  bf16x8 fa[2][4], fb[2][2];
+  for (int kk = 0; kk < 4; ++kk) sw[kk] = rowoff + (((kk * 2 + half) ^ key) << 4);
 #define ADWIN_FENCE __builtin_amdgcn_sched_barrier(0);
-#define ADWIN_RA(KK, I) fa[(KK) & 1][I] = *(const bf16x8*)(pA[KK] + (I) * 32 * kRowBytes); ADWIN_FENCE
-#define ADWIN_RB(KK, I) fb[(KK) & 1][I] = *(const bf16x8*)(pB[KK] + (I) * 32 * kRowBytes); ADWIN_FENCE
+#define ADWIN_RA(TA, KK, I) fa[((KK) + 1) & 1][I] = *(const bf16x8*)((TA) + (I) * 32 * kRowBytes + sw[((KK) + 1) & 3]); ADWIN_FENCE
+#define ADWIN_RB(TB, KK, I) fb[((KK) + 1) & 1][I] = *(const bf16x8*)((TB) + (I) * 32 * kRowBytes + sw[((KK) + 1) & 3]); ADWIN_FENCE
 #define ADWIN_MM(KK, FMI, FNI)                                                                  \
   acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
                                                           acc[FMI][FNI], 0, 0, 0);              \
   ADWIN_FENCE
-#define ADWIN_DMA(I) if constexpr (ISSUE) dma_one<I>(lds_stage, wave, o, sA, sB); ADWIN_FENCE
+#define ADWIN_DMA(I) if constexpr (ISSUE) { dma_one<I>(lds_stage, wave, o, sA, sB); ADWIN_FENCE }
+  // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from (TA, TB) when READ
+#define ADWIN_SUB(KK, READ, TA, TB, D0, D1, D2)                         \
+  ADWIN_MM(KK, 0, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 0) }        \
+  ADWIN_MM(KK, 0, 1) if constexpr (READ) { ADWIN_RB(TB, KK, 0) }        \
+  ADWIN_MM(KK, 1, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 1) }        \
+  ADWIN_MM(KK, 1, 1) if constexpr (READ) { ADWIN_RB(TB, KK, 1) }        \
+  ADWIN_MM(KK, 2, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 2) }        \
+  ADWIN_MM(KK, 2, 1) if constexpr (READ) { ADWIN_RA(TA, KK, 3) } ADWIN_DMA(D0) \
+  ADWIN_MM(KK, 3, 0) ADWIN_DMA(D1)                                      \
+  ADWIN_MM(KK, 3, 1) ADWIN_DMA(D2)
   ADWIN_FENCE
-  ADWIN_RA(0, 0) ADWIN_RB(0, 0) ADWIN_RA(0, 1) ADWIN_RB(0, 1) ADWIN_RA(0, 2) ADWIN_RA(0, 3)
-#define ADWIN_STEP(KK, NK, D0, D1, D2)                          \
-  ADWIN_MM(KK, 0, 0) ADWIN_RA(NK, 0)                            \
-  ADWIN_MM(KK, 0, 1) ADWIN_RB(NK, 0)                            \
-  ADWIN_MM(KK, 1, 0) ADWIN_DMA(D0)                              \
-  ADWIN_MM(KK, 1, 1) ADWIN_RA(NK, 1)                            \
-  ADWIN_MM(KK, 2, 0) ADWIN_RB(NK, 1)                            \
-  ADWIN_MM(KK, 2, 1) ADWIN_DMA(D1)                              \
-  ADWIN_MM(KK, 3, 0) ADWIN_RA(NK, 2)                            \
-  ADWIN_MM(KK, 3, 1) ADWIN_RA(NK, 3) ADWIN_DMA(D2)
-  ADWIN_STEP(0, 1, 0, 1, 2)
-  ADWIN_STEP(1, 2, 3, 4, 5)
-  ADWIN_STEP(2, 3, 6, 7, 8)
-  // last sub-step: no further fragments of this stage
-  ADWIN_MM(3, 0, 0) ADWIN_MM(3, 0, 1) ADWIN_DMA(9)
-  ADWIN_MM(3, 1, 0) ADWIN_MM(3, 1, 1) ADWIN_DMA(10)
-  ADWIN_MM(3, 2, 0) ADWIN_MM(3, 2, 1) ADWIN_DMA(11)
-  ADWIN_MM(3, 3, 0) ADWIN_MM(3, 3, 1)
-#undef ADWIN_STEP
+  ADWIN_SUB(0, true, curA, curB, 0, 1, 2)
+  ADWIN_SUB(1, true, curA, curB, 3, 4, 5)
+  ADWIN_SUB(2, true, curA, curB, 6, 7, 8)
+  if constexpr (!LAST) {
+    // loads issued after those of the next stage: the 9 above (none when !ISSUE)
+    if constexpr (ISSUE) asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  ADWIN_FENCE
+  ADWIN_SUB(3, !LAST, nxtA, nxtB, 9, 10, 11)
+#undef ADWIN_SUB
 #undef ADWIN_DMA
 #undef ADWIN_MM
 #undef ADWIN_RB
@@ -511,9 +491,10 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   const int tg = vid / per_group, within = vid % per_group;
   const int strip = within / a.tg, tt_local = tg * a.tg + (within % a.tg);
   if (tt_local >= a.n_tiles) return;
-  int tt = a.tile0 + tt_local;
-  int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
-  int vt_end = (int)((int64_t)a.vt_total * (strip + 1) / a.strips);
+  const int tt = a.tile0 + tt_local;
+  const int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
+  const int vt_end = (int)((int64_t)a.vt_total * (strip + 1) / a.strips);
+  if (vt_begin >= vt_end) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
   // lane -> (row within its 8-row group, chunk position); global chunk = pos ^ swizzle(row)
@@ -527,8 +508,23 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     os.b[j] = r * (uint32_t)(a.H_s * 2) + chunk * 16;
     ot.b[j] = r * (uint32_t)(a.H_t * 2) + chunk * 16;
   }
-  const int waveB = wave * 64 * kRowBytes;
-  const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;
+  // W rows of the vocabulary tile starting at v0, relative to row v0 (tail rows: a valid
+  // row, masked in the epilogue)
+  auto set_w_offsets = [&](int v0) {
+#pragma unroll
+    for (int j = 0; j < kTileVocab / 32; ++j) {
+      const int row = (wave + 4 * j) * 8 + lrow;                     // row in the 128-row W tile
+      const int chunk = lpos ^ ((row >> 1) & 7);
+      int v = v0 + row;
+      v = v < a.V ? v : a.V - 1;
+      os.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_s * 2) + chunk * 16;
+      ot.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_t * 2) + chunk * 16;
+    }
+  };
+  const int waveA = 0, waveB = kTileVocab * kRowBytes + wave * 64 * kRowBytes;
+  const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;   // each >= 2 on this path
+  const char* sHt = (const char*)a.h_t;
+  const char* sHs = (const char*)a.h_s;
 
   LaneStats st;
   LaneSums sm;
@@ -549,28 +545,38 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     }
   }
 
-  uint32_t ring = 0;   // stage the next issued k-step goes to (runs on across tiles)
+  // The k-steps of all vocabulary tiles of the strip form one pipeline: per tile nk_t
+  // teacher steps, then nk_s student steps; step g is staged into ring slot g % 3 two steps
+  // before it is consumed, also across the tile boundary (the next tile's first two steps
+  // are loaded during this tile's last two, i.e. before and under the epilogue).
+  uint32_t wr = 0, rd = 0;     // ring slots of the next step to load / to consume
+  auto slot_inc = [](uint32_t x) { return x + 1 == kDmaStages ? 0u : x + 1; };
+  {
+    const int v0 = vt_begin * kTileVocab;
+    set_w_offsets(v0);
+    const char* sWt = (const char*)(a.W_t + (int64_t)v0 * a.H_t);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t dst = lds0 + wr * kLogitStage;
+      dma_one<0>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<1>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<2>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<3>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<4>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<5>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<6>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<7>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<8>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<9>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<10>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      dma_one<11>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      wr = slot_inc(wr);
+    }
+  }
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int v0 = vt * kTileVocab;
-#pragma unroll
-    for (int j = 0; j < kTileVocab / 32; ++j) {
-      const int row = (wave + 4 * j) * 8 + lrow;                     // row in the 128-row W tile
-      const int chunk = lpos ^ ((row >> 1) & 7);
-      int v = v0 + row;
-      v = v < a.V ? v : a.V - 1;                                     // tail: valid row, masked later
-      os.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_s * 2) + chunk * 16;
-      ot.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_t * 2) + chunk * 16;
-    }
     const char* sWt = (const char*)(a.W_t + (int64_t)v0 * a.H_t);
     const char* sWs = (const char*)(a.W_s + (int64_t)v0 * a.H_s);
-    const char* sHt = (const char*)a.h_t;
-    const char* sHs = (const char*)a.h_s;
-    auto issue = [&](int s) {      // k-step s of this tile: teacher steps first, then student
-      const uint32_t dst = lds0 + ring * kLogitStage;
-      if (s < nk_t) dma_stage(dst, wave, ot, sWt + s * kRowBytes, sHt + s * kRowBytes);
-      else dma_stage(dst, wave, os, sWs + (s - nk_t) * kRowBytes, sHs + (s - nk_t) * kRowBytes);
-      ring = ring + 1 == kDmaStages ? 0 : ring + 1;
-    };
     f32x16 zt[4][2], zs[4][2];
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
@@ -579,51 +585,65 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) { zt[fm][fn][e] = 0.f; zs[fm][fn][e] = 0.f; }
 
-    uint32_t rd = ring;            // stage of the next k-step to consume
-    issue(0);
-    issue(1);                      // nk >= 2 always (H_s, H_t >= 64)
-    // k-step s consumes stage rd while the loads of k-step s+2 are issued into `ring`.
-    // The loops are peeled so that the steady-state bodies carry no conditionals.
-    auto step = [&](auto issue_c, f32x16 (&acc)[4][2], const DmaOffsets& o, const char* sA, const char* sB) {
-      constexpr bool kIssue = decltype(issue_c)::value;
+    // step 0 of this tile has landed once at most the 12 loads of step 1 are outstanding
+    wait_vm<kDmaPerWave>();
+    __syncthreads();
+    bf16x8 fa[2][4], fb[2][2];
+    {
       const char* cur = lds + rd * kLogitStage;
-      mma_stage_dma<kIssue>(acc, cur, cur + kTileVocab * kRowBytes + waveB, lane,
-                            lds0 + ring * kLogitStage, wave, o, sA, sB);
-      if (kIssue) ring = ring + 1 == kDmaStages ? 0 : ring + 1;
-      rd = rd + 1 == kDmaStages ? 0 : rd + 1;
+      const int key = (lane >> 1) & 7, half = lane >> 5;
+      const int sw0 = (lane & 31) * kRowBytes + ((half ^ key) << 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[0][i] = *(const bf16x8*)(cur + waveA + i * 32 * kRowBytes + sw0);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fb[0][i] = *(const bf16x8*)(cur + waveB + i * 32 * kRowBytes + sw0);
+    }
+    // one k-step: consume slot rd, prefetch fragments from the following slot, load into wr
+    auto step = [&](auto issue_c, auto last_c, f32x16 (&acc)[4][2], const DmaOffsets& o, const char* sA,
+                    const char* sB) {
+      constexpr bool kIssue = decltype(issue_c)::value, kLast = decltype(last_c)::value;
+      const char* cur = lds + rd * kLogitStage;
+      const uint32_t rn = slot_inc(rd);
+      const char* nxt = lds + rn * kLogitStage;
+      sweep_kstep<kIssue, kLast>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
+                                 lds0 + wr * kLogitStage, wave, o, sA, sB);
+      if (kIssue) wr = slot_inc(wr);
+      rd = rn;
     };
     const std::true_type yes{};
     const std::false_type no{};
     int s = 0;
-    for (; s + 2 < nk_t; ++s) {                // teacher k-steps prefetching teacher k-steps
-      wait_vm<kDmaPerWave>();
-      __syncthreads();
-      step(yes, zt, ot, sWt + (s + 2) * kRowBytes, sHt + (s + 2) * kRowBytes);
-    }
-    for (; s < nk_t; ++s) {                    // last teacher k-steps prefetch student k-steps
-      wait_vm<kDmaPerWave>();
-      __syncthreads();
-      const int n = s + 2 - nk_t;              // 0 or 1: nk_s >= 2 on this path
-      step(yes, zt, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
-    }
-    for (; s + 2 < nk; ++s) {                  // student k-steps
-      wait_vm<kDmaPerWave>();
-      __syncthreads();
+    for (; s + 2 < nk_t; ++s)                  // teacher k-steps loading teacher k-steps
+      step(yes, no, zt, ot, sWt + (s + 2) * kRowBytes, sHt + (s + 2) * kRowBytes);
+    for (; s < nk_t; ++s) {                    // last two teacher k-steps load student k-steps 0, 1
       const int n = s + 2 - nk_t;
-      step(yes, zs, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
+      step(yes, no, zt, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
     }
-    for (; s < nk; ++s) {                      // drain: nothing left to prefetch in this tile
-      if (s + 1 < nk) wait_vm<kDmaPerWave>(); else wait_vm<0>();
-      __syncthreads();
-      step(no, zs, os, sWs, sHs);
+    for (; s + 2 < nk; ++s) {                  // student k-steps loading student k-steps
+      const int n = s + 2 - nk_t;
+      step(yes, no, zs, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
+    }
+    if (vt + 1 < vt_end) {                     // last two: load the next tile's teacher k-steps 0, 1
+      set_w_offsets(v0 + kTileVocab);
+      const char* sWn = (const char*)(a.W_t + (int64_t)(v0 + kTileVocab) * a.H_t);
+      step(yes, no, zs, ot, sWn, sHt);
+      step(yes, yes, zs, ot, sWn + kRowBytes, sHt + kRowBytes);
+    } else {
+      step(no, no, zs, os, sWs, sHs);
+      step(no, yes, zs, os, sWs, sHs);
     }
     const bool tail = v0 + kTileVocab > a.V;
-    const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
-    if (MODE == kModeStats) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
-    else {
+    if (MODE == kModeStats) {
+      stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
+    } else {
       __bf16* blk = a.slab + ((int64_t)tt_local * (a.Vp / kBK) + 2 * vt) * kSlabBlock;
-      if (MODE == kModeDz) dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
-      else single_epilogue(zs, zt, sm, rs2, rt2, mu, blk, a.e2_off, wave * 64, v0, a.V, tail, lane);
+      if (MODE == kModeDz) {
+        dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
+      } else if (tail) {
+        single_epilogue<true>(zs, zt, sm, rs2, rt2, mu, blk, a.e2_off, wave * 64, v0, a.V, lane);
+      } else {
+        single_epilogue<false>(zs, zt, sm, rs2, rt2, mu, blk, a.e2_off, wave * 64, v0, a.V, lane);
+      }
     }
   }
   const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
