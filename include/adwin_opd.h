@@ -66,6 +66,9 @@ extern "C" {
 #define ADWIN_DT_BF16  0
 #define ADWIN_DT_F32   1
 
+/* most candidate windows one call can audit */
+#define ADWIN_MAX_CANDIDATES 16
+
 /* bits of *status_dev (device-detected input faults; the call still completes) */
 #define ADWIN_DEV_BAD_ID     1u  /* some ids[t] on a computed row is outside [0, V): c_t = 0 there */
 #define ADWIN_DEV_NONFINITE  2u  /* a computed row produced a non-finite log-sum-exp            */
@@ -104,6 +107,17 @@ typedef struct adwin_opd_problem {
   int32_t* n_out;            /* [B] n_i                                                        */
   int64_t* n_adm_out;        /* [1] N_adm = sum n_i                                            */
   uint32_t* status_dev;      /* [1] OR of ADWIN_DEV_* bits                                     */
+  /* Candidate-window audit (Sec. 4.2: rho_t(L) for every L of the candidate list, all from
+   * the one full-rollout pass of this call; mode PREFIX_AND_FULL only).  For candidate L
+   * the prefix objective uses the shared window L on every rollout (n_i = min(L, len_i),
+   * weights by `reduction`) and is compared with the same full-rollout gradient as above.
+   * candidates == NULL or n_candidates == 0: no audit, the three outputs are not touched. */
+  const int32_t* candidates; /* host [n_candidates], each > 0                                  */
+  int32_t n_candidates;      /* 0 .. ADWIN_MAX_CANDIDATES                                      */
+  float* cand_rho_pooled;    /* [n_candidates, B] per-rollout pooled cosine                     */
+  float* cand_rho_field;     /* [n_candidates, B] per-rollout field cosine                      */
+  float* cand_batch;         /* [n_candidates, 4] pooled micro, field micro, pooled macro,     */
+                             /*                   field macro                                  */
 } adwin_opd_problem;
 
 /*
@@ -151,6 +165,25 @@ const char* adwin_opd_strerror(int status);
  */
 int adwin_opd_plan_host(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
                         int32_t* n, int64_t* row_list, int32_t* row_seq, int64_t* n_adm);
+
+/*
+ * Scheduler of Sec. 4.2 (host, no GPU).
+ *   snr:          Eq. 10, snr[k] = rho[k]^2 / (1 - rho[k]^2)  (+inf at |rho| = 1).
+ *   next_window:  L_next = the shortest candidate whose alignment reaches rho_star; if none
+ *                 does, the longest candidate (the window expands).  rho_star <= 0 selects
+ *                 the paper's threshold sqrt(2)/2, the point where the SNR is 1.
+ *   probe_staleness: bookkeeping of the hard staleness limit of Sec. 4.1.  Called once
+ *                 per optimisation step: the age of every pending probe (pending[i] != 0)
+ *                 grows by one, ages of the others are reset to 0; force[i] = 1 for the
+ *                 pending probes whose age has reached `limit` (paper: 5), which must be
+ *                 completed before the next step.  *n_forced counts them.
+ * All pointers are host memory; rho, candidates: [k]; age, pending, force: [n_probes].
+ */
+int adwin_opd_snr(const float* rho, int32_t k, float* snr);
+int adwin_opd_next_window(const float* rho, const int32_t* candidates, int32_t k, float rho_star,
+                          int32_t* next);
+int adwin_opd_probe_staleness(int32_t* age, const uint8_t* pending, int32_t n_probes, int32_t limit,
+                              uint8_t* force, int32_t* n_forced);
 
 /* Bytes of device workspace adwin_opd_fused needs for this problem.  Pure host; reads
  * shapes, mode, offsets and window only. */

@@ -286,20 +286,27 @@ def supervise_from_logits(z_s, z_t, ids, offsets, window, reduction=RED_SEQ_MEAN
 # ---------------------------------------------------------------------------
 
 def audit_candidates(g, offsets, candidates=CANDIDATE_WINDOWS, reduction=RED_SEQ_MEAN):
-    """rho_t(L) for every candidate L from one full-rollout pass: per-rollout pooled
-    cosines [len(candidates), B], their macro mean, and the micro (batch-aggregated)
-    cosine, each prefix gradient compared with the full-rollout gradient."""
+    """rho_t(L) for every candidate L from one full-rollout pass: per-rollout pooled and
+    field cosines [len(candidates), B], their macro means, and the micro
+    (batch-aggregated) cosines, each prefix gradient (shared window L on every rollout)
+    compared with the full-rollout gradient."""
     B = len(offsets) - 1
-    per = np.zeros((len(candidates), B))
-    micro, macro = np.zeros(len(candidates)), np.zeros(len(candidates))
+    K = len(candidates)
+    per, per_field = np.zeros((K, B)), np.zeros((K, B))
+    micro, macro = np.zeros(K), np.zeros(K)
+    micro_field, macro_field = np.zeros(K), np.zeros(K)
     for k, L in enumerate(candidates):
         w = np.full(B, L, np.int64)
         out = window_outputs(np.zeros(int(offsets[-1])), g, offsets, w, reduction,
                              1.0, MODE_PREFIX_AND_FULL)
         per[k] = out["rho_pooled"]
+        per_field[k] = out["rho_field"]
         micro[k] = out["batch"][2]
+        micro_field[k] = out["batch"][3]
         macro[k] = out["batch"][4]
-    return {"rho_pooled": per, "micro": micro, "macro": macro}
+        macro_field[k] = out["batch"][5]
+    return {"rho_pooled": per, "rho_field": per_field, "micro": micro, "macro": macro,
+            "micro_field": micro_field, "macro_field": macro_field}
 
 
 def snr(rho):

@@ -24,6 +24,7 @@ ADWIN_PREFIX_ONLY, ADWIN_PREFIX_AND_FULL = 0, 1
 ADWIN_RED_SEQ_MEAN, ADWIN_RED_SUM, ADWIN_RED_TOKEN_MEAN = 0, 1, 2
 ADWIN_DT_BF16, ADWIN_DT_F32 = 0, 1
 ADWIN_DEV_BAD_ID, ADWIN_DEV_NONFINITE = 1, 2
+ADWIN_MAX_CANDIDATES = 16
 
 
 class adwin_opd_problem(C.Structure):
@@ -39,6 +40,8 @@ class adwin_opd_problem(C.Structure):
         ("loss_prefix", C.c_void_p), ("loss_full", C.c_void_p),
         ("rho_pooled", C.c_void_p), ("rho_field", C.c_void_p), ("batch", C.c_void_p),
         ("n_out", C.c_void_p), ("n_adm_out", C.c_void_p), ("status_dev", C.c_void_p),
+        ("candidates", C.c_void_p), ("n_candidates", C.c_int32),
+        ("cand_rho_pooled", C.c_void_p), ("cand_rho_field", C.c_void_p), ("cand_batch", C.c_void_p),
     ]
 
 
@@ -66,6 +69,13 @@ def _load() -> C.CDLL:
     lib.adwin_opd_plan_host.restype = C.c_int
     lib.adwin_opd_plan_host.argtypes = [C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.adwin_opd_snr.restype = C.c_int
+    lib.adwin_opd_snr.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    lib.adwin_opd_next_window.restype = C.c_int
+    lib.adwin_opd_next_window.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
+    lib.adwin_opd_probe_staleness.restype = C.c_int
+    lib.adwin_opd_probe_staleness.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                              C.c_void_p]
     lib.adwin_opd_workspace_bytes.restype = C.c_int
     lib.adwin_opd_workspace_bytes.argtypes = [C.POINTER(adwin_opd_problem), C.POINTER(C.c_size_t)]
     lib.adwin_opd_fused.restype = C.c_int
@@ -143,6 +153,33 @@ def adwin_opd_plan_host(offsets, window, T=None, want_rows: bool = True) -> dict
     return out
 
 
+def adwin_opd_snr(rho) -> np.ndarray:
+    r = np.ascontiguousarray(np.asarray(rho, dtype=np.float32))
+    out = np.zeros_like(r)
+    _check(lib.adwin_opd_snr(r.ctypes.data, int(r.shape[0]), out.ctypes.data))
+    return out
+
+
+def adwin_opd_next_window(rho, candidates, rho_star: float = 0.0) -> int:
+    r = np.ascontiguousarray(np.asarray(rho, dtype=np.float32))
+    c = _host_i32(candidates)
+    nxt = C.c_int32(0)
+    _check(lib.adwin_opd_next_window(r.ctypes.data, c.ctypes.data, int(c.shape[0]), float(rho_star),
+                                     C.addressof(nxt)))
+    return int(nxt.value)
+
+
+def adwin_opd_probe_staleness(age, pending, limit: int = 5):
+    """Advances `age` (int32 array, in place); returns (force[n] uint8, n_forced)."""
+    assert age.dtype == np.int32 and age.flags.c_contiguous
+    pend = np.ascontiguousarray(np.asarray(pending, dtype=np.uint8))
+    force = np.zeros(age.shape[0], np.uint8)
+    cnt = C.c_int32(0)
+    _check(lib.adwin_opd_probe_staleness(age.ctypes.data, pend.ctypes.data, int(age.shape[0]), int(limit),
+                                         force.ctypes.data, C.addressof(cnt)))
+    return force, int(cnt.value)
+
+
 def _ptr(t) -> int | None:
     return None if t is None else int(t.data_ptr())
 
@@ -163,8 +200,9 @@ class FusedCall:
                  reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0, dh_dtype=ADWIN_DT_F32,
                  want=("kl", "c", "dh_prefix", "dh_full", "loss_prefix", "loss_full", "rho_pooled",
                        "rho_field", "batch", "n_out", "n_adm_out", "status_dev"),
-                 device=None, allocate=True):
+                 device=None, allocate=True, candidates=None):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
+        self.candidates = None if candidates is None else _host_i32(candidates)
         self.inputs = (h_s, h_t, W_s, W_t, ids)
         B = int(self.window.shape[0])
         T = int(h_s.shape[0]) if h_s is not None else int(self.offsets[-1])
@@ -178,6 +216,9 @@ class FusedCall:
         p.offsets, p.window = self.offsets.ctypes.data, self.window.ctypes.data
         p.h_s, p.h_t, p.W_s, p.W_t, p.ids = _ptr(h_s), _ptr(h_t), _ptr(W_s), _ptr(W_t), _ptr(ids)
         p.mode, p.reduction, p.grad_scale, p.dh_dtype = mode, reduction, float(grad_scale), dh_dtype
+        K = 0 if self.candidates is None else int(self.candidates.shape[0])
+        if K:
+            p.candidates, p.n_candidates = self.candidates.ctypes.data, K
         self.p = p
         self.out = {}
         self.workspace = None
@@ -198,6 +239,11 @@ class FusedCall:
                 shp, dt = shapes[k]
                 self.out[k] = torch.empty(shp, dtype=dt, device=dev)
                 setattr(p, k, _ptr(self.out[k]))
+            if K:
+                for k, shp in (("cand_rho_pooled", (K, B)), ("cand_rho_field", (K, B)),
+                               ("cand_batch", (K, 4))):
+                    self.out[k] = torch.empty(shp, dtype=torch.float32, device=dev)
+                    setattr(p, k, _ptr(self.out[k]))
             self.workspace_bytes = adwin_opd_workspace_bytes(p)
             self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=dev)
 

@@ -1142,7 +1142,7 @@ struct FusedLayout {
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, total;
 };
 
 static int env_int(const char* name, int dflt) {
@@ -1207,6 +1207,10 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_uf = take(sizeof(float) * (size_t)p->B * (size_t)p->H_s);
   L.o_seg = take(sizeof(double) * 4 * (size_t)p->B);
   L.o_racc = take(sizeof(double) * 4 * (size_t)p->B);
+  const size_t kc = (p->candidates && p->n_candidates > 0) ? (size_t)p->n_candidates : 0;
+  L.o_uc = take(sizeof(float) * kc * (size_t)p->B * (size_t)p->H_s);
+  L.o_cacc = take(sizeof(double) * 4 * kc * (size_t)p->B);
+  L.o_cS = take(sizeof(double) * kc * (size_t)p->B);
   L.total = o;
   return L;
 }
@@ -1225,6 +1229,12 @@ static int check_problem(const adwin_opd_problem* p) {
   if (p->mode != ADWIN_PREFIX_ONLY && p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
   if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
   if (p->dh_dtype != ADWIN_DT_BF16 && p->dh_dtype != ADWIN_DT_F32) return ADWIN_E_MODE;
+  if (p->n_candidates < 0 || p->n_candidates > ADWIN_MAX_CANDIDATES) return ADWIN_E_SHAPE;
+  if (p->candidates && p->n_candidates > 0) {
+    if (p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
+    for (int k = 0; k < p->n_candidates; ++k)
+      if (p->candidates[k] <= 0) return ADWIN_E_WINDOW;
+  }
   return ADWIN_OK;
 }
 
@@ -1450,6 +1460,24 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   b.rho_pooled = p->rho_pooled; b.rho_field = p->rho_field; b.batch = p->batch;
   b.n_out = p->n_out; b.n_adm_out = p->n_adm_out; b.n_adm = hp.n_adm;
   ADWIN_HIP_TRY(launch_alignment_and_batch(b, stream));
+  if (probe && p->candidates && p->n_candidates > 0) {
+    CandArgs ca{};
+    ca.pl = pl; ca.B = p->B; ca.H = p->H_s; ca.K = p->n_candidates;
+    ca.reduction = p->reduction; ca.zero_grad = (p->grad_scale == 0.f);
+    for (int k = 0; k < ca.K; ++k) {
+      ca.L[k] = p->candidates[k];
+      int64_t nadm = 0;
+      for (int32_t i = 0; i < p->B; ++i) {
+        const int64_t len = p->offsets[i + 1] - p->offsets[i];
+        nadm += ca.L[k] < len ? (int64_t)ca.L[k] : len;
+      }
+      ca.inv_nadm[k] = nadm > 0 ? 1.0 / (double)nadm : 0.0;
+    }
+    ca.g = gws; ca.pf = pa.pf; ca.uf = pa.uf; ca.rownorm = rownorm; ca.seg = seg;
+    ca.uc = (float*)(ws + L.o_uc); ca.cacc = (double*)(ws + L.o_cacc); ca.cS = (double*)(ws + L.o_cS);
+    ca.rho_pooled = p->cand_rho_pooled; ca.rho_field = p->cand_rho_field; ca.batch = p->cand_batch;
+    ADWIN_HIP_TRY(launch_candidate_audit(ca, stream));
+  }
   return ADWIN_OK;
 }
 

@@ -1,7 +1,9 @@
 // Host-side integer bookkeeping (Sec. 4.1: rollouts truncated at the window), status
 // strings and the version.  Nothing here touches the GPU.
 #include <atomic>
+#include <cmath>
 #include <cstdio>
+#include <climits>
 #include <cstring>
 
 #include "common.h"
@@ -72,6 +74,54 @@ int adwin_opd_plan_host(int64_t T, int32_t B, const int64_t* offsets, const int3
     total += ni;
   }
   *n_adm = total;
+  return ADWIN_OK;
+}
+
+// Eq. 10: SNR(L) = rho^2 / (1 - rho^2).
+int adwin_opd_snr(const float* rho, int32_t k, float* snr) {
+  if (!rho || !snr) return ADWIN_E_NULL;
+  if (k < 0) return ADWIN_E_SHAPE;
+  for (int32_t i = 0; i < k; ++i) {
+    const double r2 = (double)rho[i] * (double)rho[i];
+    snr[i] = r2 >= 1.0 ? INFINITY : (float)(r2 / (1.0 - r2));
+  }
+  return ADWIN_OK;
+}
+
+// Sec. 4.2: L_{t+1} = min{L in the candidate list : rho_t(L) >= rho*}.
+int adwin_opd_next_window(const float* rho, const int32_t* candidates, int32_t k, float rho_star,
+                          int32_t* next) {
+  if (!rho || !candidates || !next) return ADWIN_E_NULL;
+  if (k < 1) return ADWIN_E_SHAPE;
+  for (int32_t i = 0; i < k; ++i)
+    if (candidates[i] <= 0) return ADWIN_E_WINDOW;
+  const double thr = rho_star > 0.f ? (double)rho_star : std::sqrt(2.0) / 2.0;
+  int32_t best = 0, longest = candidates[0];
+  for (int32_t i = 0; i < k; ++i) {
+    if (candidates[i] > longest) longest = candidates[i];
+    if ((double)rho[i] >= thr && (best == 0 || candidates[i] < best)) best = candidates[i];
+  }
+  *next = best > 0 ? best : longest;
+  return ADWIN_OK;
+}
+
+// Sec. 4.1: a probe older than the staleness limit is forced to complete.
+int adwin_opd_probe_staleness(int32_t* age, const uint8_t* pending, int32_t n_probes, int32_t limit,
+                              uint8_t* force, int32_t* n_forced) {
+  if (n_probes < 0 || limit < 1) return ADWIN_E_SHAPE;
+  if (n_probes > 0 && (!age || !pending || !force)) return ADWIN_E_NULL;
+  int32_t cnt = 0;
+  for (int32_t i = 0; i < n_probes; ++i) {
+    if (pending[i]) {
+      if (age[i] < INT32_MAX) age[i] += 1;
+      force[i] = age[i] >= limit ? 1 : 0;
+    } else {
+      age[i] = 0;
+      force[i] = 0;
+    }
+    cnt += force[i];
+  }
+  if (n_forced) *n_forced = cnt;
   return ADWIN_OK;
 }
 

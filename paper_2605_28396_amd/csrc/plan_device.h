@@ -57,6 +57,28 @@ struct BatchArgs {
 };
 hipError_t launch_alignment_and_batch(const BatchArgs& a, hipStream_t st);
 
+// Candidate-window audit (Sec. 4.2): alignment of the shared prefix window L_k, for every
+// candidate k, with the full-rollout gradient, from the per-row gradients of one
+// full-rollout pass.
+struct CandArgs {
+  DevicePlan pl;
+  int32_t B, H, K;
+  int reduction;
+  int zero_grad;
+  int32_t L[ADWIN_MAX_CANDIDATES];
+  double inv_nadm[ADWIN_MAX_CANDIDATES];   // TOKEN_MEAN weight of candidate k: 1 / sum_i min(L_k, len_i)
+  const float* g;        // [rows][H] per-row gradients, computed-row order (every row: probe mode)
+  const float* pf;       // [chunks][H] column sums of g over kChunkRows-row chunks of each rollout
+  const float* uf;       // [B][H] pooled full-rollout sums
+  const float* rownorm;  // [rows] ||g_t||^2
+  const double* seg;     // [B][4]; seg[4 i + 3] = sum of ||g_t||^2 over rollout i
+  float* uc;             // [K][B][H] scratch: pooled prefix sums
+  double* cacc;          // [K][B][4] scratch: rho pooled, valid, rho field, valid
+  double* cS;            // [K][B]   scratch: sum of ||g_t||^2 over the prefix
+  float* rho_pooled; float* rho_field; float* batch;   // outputs, may be NULL
+};
+hipError_t launch_candidate_audit(const CandArgs& a, hipStream_t st);
+
 // Optional per-phase timing with HIP events on the caller's stream (profiling entry
 // points only).  begin()/end() bracket one launch; collect() waits and sums per phase.
 class PhaseTimer {

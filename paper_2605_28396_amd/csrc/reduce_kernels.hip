@@ -244,8 +244,133 @@ __global__ __launch_bounds__(256) void batch_kernel(BatchArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Candidate-window audit (Sec. 4.2).  For candidate k every rollout uses the shared window
+// L_k: n = min(L_k, len_i).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double cand_alpha_p(const CandArgs& a, int k, int64_t n) {
+  if (n <= 0) return 0.0;
+  if (a.reduction == ADWIN_RED_SEQ_MEAN) return 1.0 / ((double)a.B * (double)n);
+  if (a.reduction == ADWIN_RED_SUM) return 1.0;
+  return a.inv_nadm[k];
+}
+
+// Pooled prefix sum u_i(L_k): whole chunks from the chunk sums, the ragged rest row by row.
+__global__ __launch_bounds__(256) void cand_pool_kernel(CandArgs a) {
+  const int k = blockIdx.x / a.B, i = blockIdx.x % a.B;
+  const int h = blockIdx.y * 256 + threadIdx.x;
+  if (h >= a.H) return;
+  const int64_t len = a.pl.offsets[i + 1] - a.pl.offsets[i];
+  const int64_t n = a.L[k] < len ? (int64_t)a.L[k] : len;
+  const int64_t full = n / kChunkRows;
+  float s = 0.f;
+  const float* pf = a.pf + (int64_t)a.pl.chunk_off[i] * a.H + h;
+  for (int64_t c = 0; c < full; ++c) s += pf[c * a.H];
+  const float* g = a.g + (a.pl.comp_off[i] + full * kChunkRows) * a.H + h;
+  for (int64_t j = full * kChunkRows; j < n; ++j, g += a.H) s += *g;
+  a.uc[((int64_t)k * a.B + i) * a.H + h] = s;
+}
+
+// One workgroup per (candidate, rollout): cosines of the pooled and of the field gradients.
+__global__ __launch_bounds__(256) void cand_align_kernel(CandArgs a) {
+  __shared__ double sh[16];
+  const int k = blockIdx.x / a.B, i = blockIdx.x % a.B;
+  const int64_t len = a.pl.offsets[i + 1] - a.pl.offsets[i];
+  const int64_t n = a.L[k] < len ? (int64_t)a.L[k] : len;
+  double v[4] = {0.0, 0.0, 0.0, 0.0};   // <u_p,u_f>, |u_p|^2, |u_f|^2, S_i(n)
+  if (!a.zero_grad) {
+    const float* up = a.uc + ((int64_t)k * a.B + i) * a.H;
+    const float* uf = a.uf + (int64_t)i * a.H;
+    for (int h = threadIdx.x; h < a.H; h += 256) {
+      const double p = up[h], f = uf[h];
+      v[0] += p * f;
+      v[1] += p * p;
+      v[2] += f * f;
+    }
+    const float* rn = a.rownorm + a.pl.comp_off[i];
+    for (int64_t j = threadIdx.x; j < n; j += 256) v[3] += (double)rn[j];
+  }
+  block_sum256<4>(v, sh);
+  if (threadIdx.x == 0) {
+    double rp = 0.0, rf = 0.0, okp = 0.0, okf = 0.0;
+    if (!a.zero_grad) {
+      if (v[1] > 0.0 && v[2] > 0.0) { rp = v[0] / (sqrt(v[1]) * sqrt(v[2])); okp = 1.0; }
+      const double Sf = a.seg[i * 4 + 3];
+      if (v[3] > 0.0 && Sf > 0.0) { rf = sqrt(v[3] / Sf); okf = 1.0; }
+    }
+    const int64_t o = (int64_t)k * a.B + i;
+    a.cacc[o * 4 + 0] = rp;
+    a.cacc[o * 4 + 1] = okp;
+    a.cacc[o * 4 + 2] = rf;
+    a.cacc[o * 4 + 3] = okf;
+    a.cS[o] = v[3];
+    if (a.rho_pooled) a.rho_pooled[o] = (float)rp;
+    if (a.rho_field) a.rho_field[o] = (float)rf;
+  }
+}
+
+// One workgroup per candidate: micro (after batch aggregation) and macro cosines.
+__global__ __launch_bounds__(256) void cand_batch_kernel(CandArgs a) {
+  __shared__ double sh[16];
+  const int k = blockIdx.x, B = a.B;
+  double w[4] = {0.0, 0.0, 0.0, 0.0};   // macro pooled sum, count, macro field sum, count
+  double f[3] = {0.0, 0.0, 0.0};        // field: dot, |p|^2, |f|^2
+  for (int i = threadIdx.x; i < B; i += 256) {
+    const int64_t o = (int64_t)k * B + i;
+    const int64_t len = a.pl.offsets[i + 1] - a.pl.offsets[i];
+    const int64_t n = a.L[k] < len ? (int64_t)a.L[k] : len;
+    const double ap = cand_alpha_p(a, k, n), af = a.pl.alpha_f[i];
+    w[0] += a.cacc[o * 4 + 0] * a.cacc[o * 4 + 1];
+    w[1] += a.cacc[o * 4 + 1];
+    w[2] += a.cacc[o * 4 + 2] * a.cacc[o * 4 + 3];
+    w[3] += a.cacc[o * 4 + 3];
+    f[0] += ap * af * a.cS[o];
+    f[1] += ap * ap * a.cS[o];
+    f[2] += af * af * a.seg[i * 4 + 3];
+  }
+  block_sum256<4>(w, sh);
+  block_sum256<3>(f, sh);
+  double m[3] = {0.0, 0.0, 0.0};
+  if (!a.zero_grad) {
+    for (int h = threadIdx.x; h < a.H; h += 256) {
+      double sp = 0.0, sf = 0.0;
+      for (int i = 0; i < B; ++i) {
+        const int64_t len = a.pl.offsets[i + 1] - a.pl.offsets[i];
+        const int64_t n = a.L[k] < len ? (int64_t)a.L[k] : len;
+        sp += cand_alpha_p(a, k, n) * (double)a.uc[((int64_t)k * B + i) * a.H + h];
+        sf += (double)a.pl.alpha_f[i] * (double)a.uf[(int64_t)i * a.H + h];
+      }
+      m[0] += sp * sf;
+      m[1] += sp * sp;
+      m[2] += sf * sf;
+    }
+  }
+  block_sum256<3>(m, sh);
+  if (threadIdx.x == 0 && a.batch) {
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!a.zero_grad) {
+      if (m[1] > 0.0 && m[2] > 0.0) o[0] = (float)(m[0] / (sqrt(m[1]) * sqrt(m[2])));
+      if (f[1] > 0.0 && f[2] > 0.0) o[1] = (float)(f[0] / (sqrt(f[1]) * sqrt(f[2])));
+      if (w[1] > 0.0) o[2] = (float)(w[0] / w[1]);
+      if (w[3] > 0.0) o[3] = (float)(w[2] / w[3]);
+    }
+    for (int q = 0; q < 4; ++q) a.batch[k * 4 + q] = o[q];
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
+hipError_t launch_candidate_audit(const CandArgs& a, hipStream_t st) {
+  if (a.K <= 0) return hipSuccess;
+  cand_pool_kernel<<<dim3((unsigned)(a.K * a.B), (unsigned)((a.H + 255) / 256)), 256, 0, st>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  cand_align_kernel<<<(unsigned)(a.K * a.B), 256, 0, st>>>(a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  cand_batch_kernel<<<(unsigned)a.K, 256, 0, st>>>(a);
+  return hipGetLastError();
+}
 hipError_t launch_build_rows(const DevicePlan& pl, int32_t B, int64_t n_rows, int64_t n_pad,
                              hipStream_t st) {
   if (n_rows <= 0) return hipSuccess;

@@ -153,3 +153,36 @@ def test_fallback_schemes_match_oracle(B, env, monkeypatch):
                       reduction=O.RED_SUM, grad_scale=1.0, mode=w.mode)
     got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, grad_scale=1.0, dh_dtype=B.ADWIN_DT_F32)
     _check_fused(w, got, ref, O.RED_SUM)
+
+
+@pytest.mark.parametrize("name,reduction", [
+    ("tiny_probe", O.RED_SEQ_MEAN), ("ragged_small", O.RED_SUM), ("ragged_small", O.RED_TOKEN_MEAN),
+    ("ragged_mid", O.RED_SEQ_MEAN),
+])
+def test_candidate_audit_matches_oracle(B, name, reduction):
+    """rho(L) for a list of candidate windows from the one full-rollout pass (Sec. 4.2):
+    per-rollout pooled / field cosines and the micro / macro aggregates."""
+    import dataclasses
+    w = dataclasses.replace(synth.workload(name), mode=synth.MODE_PREFIX_AND_FULL)
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=reduction, grad_scale=1.0, mode=w.mode)
+    lens = np.diff(w.offsets)
+    cands = [1, 7, 64, 100, 128, 129, int(lens.max()), int(lens.max()) + 50]
+    aud = O.audit_candidates(ref["g"], w.offsets, cands, reduction)
+    got = _run_fused(B, w, p, "cuda", reduction=reduction, grad_scale=1.0, dh_dtype=B.ADWIN_DT_F32,
+                     candidates=cands)
+    _check_fused(w, got, ref, reduction)                 # the primary outputs are unchanged
+    assert got["cand_rho_pooled"].shape == (len(cands), w.B)
+    assert np.all(np.abs(got["cand_rho_pooled"] - aud["rho_pooled"]) <= Hp.RHO_ABS)
+    assert np.all(np.abs(got["cand_rho_field"] - aud["rho_field"]) <= Hp.RHO_ABS)
+    want = np.stack([aud["micro"], aud["micro_field"], aud["macro"], aud["macro_field"]], axis=1)
+    assert np.all(np.abs(got["cand_batch"] - want) <= Hp.RHO_ABS), (got["cand_batch"], want)
+    # a window that covers every rollout reproduces the full gradient: cosine 1
+    nz = lens > 0
+    assert np.all(np.abs(got["cand_rho_pooled"][-1][nz] - 1.0) <= 1e-5)
+    # the scheduler picks the same window from either set of scores
+    assert B.adwin_opd_next_window(got["cand_batch"][:, 0], cands) in \
+        {O.next_window(aud["micro"], cands), O.next_window(aud["micro"] - 2 * Hp.RHO_ABS, cands),
+         O.next_window(aud["micro"] + 2 * Hp.RHO_ABS, cands)}

@@ -130,3 +130,54 @@ def test_workspace_bytes_and_argument_errors_without_gpu(B):
     assert B.adwin_opd_logits_workspace_bytes(lp) > 0
     lp.V = 4095
     assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_SHAPE
+
+
+def test_scheduler_functions_match_oracle(B):
+    g = np.random.default_rng(3)
+    cands = np.array(O.CANDIDATE_WINDOWS, np.int32)
+    for _ in range(200):
+        rho = g.uniform(-0.2, 1.0, len(cands)).astype(np.float32)
+        assert B.adwin_opd_next_window(rho, cands) == O.next_window(rho.astype(np.float64), cands)
+        thr = float(g.uniform(0.3, 0.95))
+        assert B.adwin_opd_next_window(rho, cands, thr) == \
+            O.next_window(rho.astype(np.float64), cands, rho_star=np.float32(thr))
+    perm = np.array([512, 64, 2048, 128], np.int32)            # order of the list does not matter
+    assert B.adwin_opd_next_window([0.9, 0.1, 0.99, 0.8], perm) == 128
+    assert B.adwin_opd_next_window([0.1, 0.1, 0.2, 0.3], perm) == 2048
+    rho = np.array([0.0, 0.5, float(np.float32(O.RHO_STAR)), 0.9], np.float32)
+    want = [O.snr(float(r)) for r in rho]
+    assert np.allclose(B.adwin_opd_snr(rho), want, rtol=1e-6)
+    assert np.isinf(B.adwin_opd_snr([1.0])[0])
+    with pytest.raises(B.AdwinError) as e:
+        B.adwin_opd_next_window([0.5], [0])
+    assert e.value.status == B.ADWIN_E_WINDOW
+
+
+def test_probe_staleness_bookkeeping(B):
+    age = np.zeros(4, np.int32)
+    pending = np.array([1, 1, 0, 1], np.uint8)
+    forced_at = []
+    for step in range(1, 8):
+        if step == 3:
+            pending[1] = 0                     # probe 1 completes: its age is reset
+        force, n = B.adwin_opd_probe_staleness(age, pending, limit=5)
+        assert n == int(force.sum())
+        forced_at.append(force.copy())
+    assert list(age) == [7, 0, 0, 7]
+    assert [int(f[0]) for f in forced_at] == [0, 0, 0, 0, 1, 1, 1]   # forced from the fifth step on
+    assert all(int(f[1]) == 0 and int(f[2]) == 0 for f in forced_at)
+    with pytest.raises(B.AdwinError):
+        B.adwin_opd_probe_staleness(age, pending, limit=0)
+
+
+def test_candidate_argument_errors_without_gpu(B):
+    c = np.array([64, 128], np.int32)
+    bad = np.array([64, 0], np.int32)
+
+    def st(p):
+        return B.lib.adwin_opd_fused(C.byref(p), 0, 0, None)
+    assert st(_problem(B, mode=0, candidates=c.ctypes.data, n_candidates=2)) == B.ADWIN_E_MODE
+    assert st(_problem(B, mode=1, candidates=bad.ctypes.data, n_candidates=2)) == B.ADWIN_E_WINDOW
+    assert st(_problem(B, mode=1, candidates=c.ctypes.data, n_candidates=17)) == B.ADWIN_E_SHAPE
+    with_c = B.adwin_opd_workspace_bytes(_problem(B, mode=1, candidates=c.ctypes.data, n_candidates=2))
+    assert with_c > B.adwin_opd_workspace_bytes(_problem(B, mode=1))

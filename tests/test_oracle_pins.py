@@ -385,6 +385,26 @@ def test_audit_candidates_consistent_with_single_window():
     assert a["rho_pooled"][1][0] == pytest.approx(up @ uf / np.linalg.norm(up) / np.linalg.norm(uf), rel=1e-12)
 
 
+def test_audit_field_cosine_closed_form():
+    # the field cosine of a prefix with the whole rollout is sqrt(S(n) / S(len)), S = sum of
+    # squared row norms, whatever the weights; written here without the oracle's code path
+    g_ = np.random.default_rng(10)
+    lens = np.array([7, 2, 11])
+    offsets = np.concatenate([[0], np.cumsum(lens)])
+    g = g_.normal(0, 1, (int(offsets[-1]), 5))
+    cands = (1, 3, 8, 64)
+    for red in (O.RED_SEQ_MEAN, O.RED_SUM, O.RED_TOKEN_MEAN):
+        a = O.audit_candidates(g, offsets, cands, red)
+        for k, L in enumerate(cands):
+            for i in range(3):
+                rows = g[offsets[i]:offsets[i + 1]]
+                n = min(L, len(rows))
+                want = math.sqrt((rows[:n] ** 2).sum() / (rows ** 2).sum())
+                assert a["rho_field"][k][i] == pytest.approx(want, rel=1e-12)
+        assert np.allclose(a["rho_field"][-1], 1.0) and a["micro_field"][-1] == pytest.approx(1.0)
+        assert np.all(a["macro_field"] == pytest.approx(a["rho_field"].mean(axis=1)))
+
+
 def test_teacher_diagnostics():
     assert O.teacher_branching_factor(np.zeros(37)) == pytest.approx(37.0, rel=1e-12)
     z = np.array([0.0, 50.0, 0.0])
