@@ -61,26 +61,29 @@ def _oracle_logits_baseline(w, prob, k_rows):
     from paper_2605_28396_amd import synth
     import torch
     rows = synth.sample_rows(w, k_rows)
-    idx = torch.from_numpy(rows).to(prob["z_s"].device)
-    zs = synth.to_f64(prob["z_s"][idx])
-    zt = synth.to_f64(prob["z_t"][idx])
-    ids = prob["ids"][idx].cpu().numpy()
-    t0 = time.perf_counter()
+    ids = prob["ids"].cpu().numpy()
+    dt = 0.0
     kl = np.zeros(len(rows))
-    for r in range(len(rows)):
-        kl[r] = O.token_kl(zs[r], zt[r])
-        O.token_cost(zs[r], zt[r], int(ids[r]))
-        O.token_dz(zs[r], zt[r])
-    dt = time.perf_counter() - t0
+    for lo in range(0, len(rows), 256):                   # fp64 copies of 256 rows at a time
+        part = rows[lo:lo + 256]
+        idx = torch.from_numpy(part).to(prob["z_s"].device)
+        zs = synth.to_f64(prob["z_s"][idx])
+        zt = synth.to_f64(prob["z_t"][idx])
+        t0 = time.perf_counter()
+        for r in range(len(part)):
+            kl[lo + r] = O.token_kl(zs[r], zt[r])
+            O.token_cost(zs[r], zt[r], int(ids[part[r]]))
+            O.token_dz(zs[r], zt[r])
+        dt += time.perf_counter() - t0
     return {"value": len(rows) / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
             "sample": f"{len(rows)} seeded admitted rows of this workload (fp64, numpy), {dt:.1f} s"}, (rows, kl)
 
 
-def _measured_traffic(kernel: str):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary
-    (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter
-    reads for the 1 GiB copy kernel in the same run), or None."""
-    path = os.path.join(ROOT, "profiles", "logits_given_hbm_counters.txt")
+def _measured_traffic(summary: str, kernel: str):
+    """HBM bytes per launch of `kernel` from a committed rocprofv3 counter summary under
+    profiles/ (FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same
+    counter reads for the 1 GiB copy kernel in the same run), or None."""
+    path = os.path.join(ROOT, "profiles", summary)
     try:
         vals = {}
         for line in open(path):
@@ -102,7 +105,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="strong_to_weak",
                     choices=["tiny", "logits_given", "strong_to_weak", "same_family", "probe_alignment"])
-    ap.add_argument("--cpu-rows", type=int, default=256, help="rows of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=-1,
+                    help="rows of the oracle sample (0 = skip; default: about 15 s of host work)")
     ap.add_argument("--dh-dtype", default="f32", choices=["f32", "bf16"])
     args = ap.parse_args()
     if args.gpus != 1:
@@ -159,18 +163,25 @@ def main() -> int:
         V = w.V
         alg_bytes = 6.0 * V * n_adm + 2.0 * V * (w.T - n_adm)      # read z_s,z_t + write dz; zero rows
         ach = alg_bytes / (ph["stats"] * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "logits_row_kernel", "achieved": ach, "peak": PEAK_HBM_GBS,
+        roofline = {"bound": "hbm", "kernel": "logits_row_resident_kernel", "achieved": ach, "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                    "traffic": _measured_traffic("adwin::logits_row_kernel"),
+                    "traffic": _measured_traffic("logits_given_hbm_counters.txt", "adwin::logits_row_resident_kernel"),
                     "launch_ms": ph["stats"], "alg_bytes_per_launch": alg_bytes}
         extra = {}
     else:
         V, Hs, Ht = w.V, w.H_s, w.H_t
-        f_stats = 2.0 * V * (Hs + Ht) * tokens              # one full-vocabulary sweep of both heads
-        ach = f_stats / (ph["stats"] * 1e-3) / 1e12
+        # the sweep kernel is launched once per slab of 8,192 computed rows; figures are per launch
+        launches = max(1, -(-tokens // 8192))
+        f_stats = 2.0 * V * (Hs + Ht) * tokens / launches   # one full-vocabulary sweep of both heads
+        launch_ms = ph["stats"] / launches
+        ach = f_stats / (launch_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "logit_pass_dma_kernel", "achieved": ach,
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                    "traffic": None, "launch_ms": ph["stats"], "alg_flops_per_launch": f_stats}
+                    "traffic": _measured_traffic(f"fused_{w.name}_hbm_counters.txt",
+                                                 "adwin::logit_pass_dma_kernel<2>"),
+                    "launch_ms": launch_ms, "launches_per_call": launches,
+                    "alg_flops_per_launch": f_stats}
+        f_stats *= launches
         f_alg = 2.0 * V * (2 * Hs + Ht) * tokens            # student fwd + teacher fwd + dz W_s
         single = ph["dz"] == 0.0                            # single-sweep scheme: no second logit sweep
         # executed: single sweep = logits once + two gradient factors through W_s;
@@ -186,6 +197,8 @@ def main() -> int:
             "grad_gemm_tflops": f_grad / (ph["grad"] * 1e-3) / 1e12}}
 
     cpu = None
+    if args.cpu_rows < 0:
+        args.cpu_rows = 8192 if logits else 2048
     if args.cpu_rows > 0:
         if logits:
             cpu, _ = _oracle_logits_baseline(w, prob, args.cpu_rows)
@@ -203,8 +216,11 @@ def main() -> int:
         "roofline": roofline, "cpu_baseline": cpu, "phase_ms": ph,
     }
     line["ceilings"] = {"copy_GBps": B.adwin_opd_ceiling_copy(), "mfma_bf16_TFLOPs": B.adwin_opd_ceiling_mfma(),
-                        "note": "measured on this box: streaming copy (read+write bytes) and a "
-                                "register-resident 32x32x16 bf16 MFMA loop"}
+                        "mfma_bf16_random_operands_TFLOPs": B.adwin_opd_ceiling_mfma_random(),
+                        "note": "measured on this box: streaming copy (read+write bytes); "
+                                "register-resident 32x32x16 bf16 MFMA loop with constant operands and "
+                                "with pseudo-random operands (the rate the power limit sustains on "
+                                "real data)"}
     line.update(extra)
     print(json.dumps(line))
     return 0

@@ -243,6 +243,10 @@ int adwin_opd_from_logits_profile(const adwin_opd_logits_problem* p, void* works
 int adwin_opd_ceiling_copy(const void* src, void* dst, size_t bytes, int reps, void* hip_stream,
                            float* ms);
 int adwin_opd_ceiling_mfma(void* scratch, int iters, void* hip_stream, float* tflops);
+/* The same loop with pseudo-random operands (signs, mantissas and exponents vary from
+ * lane to lane as in real inputs): the matrix-core rate the power limit sustains on such
+ * data, below the constant-operand figure.  Synchronises. */
+int adwin_opd_ceiling_mfma_random(void* scratch, int iters, void* hip_stream, float* tflops);
 
 #ifdef __cplusplus
 }

@@ -97,6 +97,8 @@ def _load() -> C.CDLL:
                                            C.POINTER(C.c_float)]
     lib.adwin_opd_ceiling_mfma.restype = C.c_int
     lib.adwin_opd_ceiling_mfma.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_float)]
+    lib.adwin_opd_ceiling_mfma_random.restype = C.c_int
+    lib.adwin_opd_ceiling_mfma_random.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_float)]
     return lib
 
 
@@ -353,4 +355,12 @@ def adwin_opd_ceiling_mfma(iters: int = 20000, stream=None) -> float:
     scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
     tf = C.c_float(0)
     _check(lib.adwin_opd_ceiling_mfma(_ptr(scratch), iters, _stream_handle(stream), C.byref(tf)))
+    return float(tf.value)
+
+
+def adwin_opd_ceiling_mfma_random(iters: int = 20000, stream=None) -> float:
+    """Measured bf16 MFMA rate in TFLOP/s with pseudo-random operands."""
+    scratch = torch.zeros(16, dtype=torch.float32, device="cuda")
+    tf = C.c_float(0)
+    _check(lib.adwin_opd_ceiling_mfma_random(_ptr(scratch), iters, _stream_handle(stream), C.byref(tf)))
     return float(tf.value)
