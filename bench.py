@@ -170,8 +170,8 @@ def main() -> int:
         extra = {}
     else:
         V, Hs, Ht = w.V, w.H_s, w.H_t
-        # the sweep kernel is launched once per slab of 8,192 computed rows; figures are per launch
-        launches = max(1, -(-tokens // 8192))
+        # the sweep kernel is launched once per slab of computed rows; figures are per launch
+        launches = max(1, B.adwin_opd_fused_launch_info(call.p)["slabs"])
         f_stats = 2.0 * V * (Hs + Ht) * tokens / launches   # one full-vocabulary sweep of both heads
         launch_ms = ph["stats"] / launches
         ach = f_stats / (launch_ms * 1e-3) / 1e12

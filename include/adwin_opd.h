@@ -189,6 +189,12 @@ int adwin_opd_probe_staleness(int32_t* age, const uint8_t* pending, int32_t n_pr
  * shapes, mode, offsets and window only. */
 int adwin_opd_workspace_bytes(const adwin_opd_problem* p, size_t* bytes);
 
+/* Launch geometry adwin_opd_fused will use for this problem (pure host; for benchmarks that
+ * quote per-launch figures): info[0] = rows computed, info[1] = the same padded to whole
+ * 256-row tiles, info[2] = rows per slab (the sweep and the gradient GEMM are launched once
+ * per slab), info[3] = number of slabs. */
+int adwin_opd_fused_launch_info(const adwin_opd_problem* p, int64_t info[4]);
+
 /*
  * Fused path (Sec. 4.1 loss on the prefix; Sec. 4.2 probe audit in mode
  * PREFIX_AND_FULL): LM-head projections, full-vocabulary log-softmax, KL_t, c_t,

@@ -78,6 +78,8 @@ def _load() -> C.CDLL:
                                               C.c_void_p]
     lib.adwin_opd_workspace_bytes.restype = C.c_int
     lib.adwin_opd_workspace_bytes.argtypes = [C.POINTER(adwin_opd_problem), C.POINTER(C.c_size_t)]
+    lib.adwin_opd_fused_launch_info.restype = C.c_int
+    lib.adwin_opd_fused_launch_info.argtypes = [C.POINTER(adwin_opd_problem), C.POINTER(C.c_int64)]
     lib.adwin_opd_fused.restype = C.c_int
     lib.adwin_opd_fused.argtypes = [C.POINTER(adwin_opd_problem), C.c_void_p, C.c_size_t, C.c_void_p]
     lib.adwin_opd_logits_workspace_bytes.restype = C.c_int
@@ -276,6 +278,13 @@ def adwin_opd_workspace_bytes(p: adwin_opd_problem) -> int:
     n = C.c_size_t(0)
     _check(lib.adwin_opd_workspace_bytes(C.byref(p), C.byref(n)))
     return int(n.value)
+
+
+def adwin_opd_fused_launch_info(p: adwin_opd_problem) -> dict:
+    info = (C.c_int64 * 4)()
+    _check(lib.adwin_opd_fused_launch_info(C.byref(p), info))
+    return {"rows": int(info[0]), "padded_rows": int(info[1]), "slab_rows": int(info[2]),
+            "slabs": int(info[3])}
 
 
 def adwin_opd_fused(h_s, h_t, W_s, W_t, ids, offsets, window, stream=None, **kw) -> dict:

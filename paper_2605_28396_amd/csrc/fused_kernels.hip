@@ -1172,11 +1172,27 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   if (strips1 > kMaxStrips) strips1 = kMaxStrips;
   L.strips1 = strips1;
   const int halves = L.single ? 2 : 1;     // the single sweep stores two factors per logit
-  int64_t slab = env_int("ADWIN_SLAB_ROWS", 8192);
-  slab = (int64_t)align_up((size_t)slab, kTileTokens);
+  const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
+  // Rows per slab: a multiple of 8 token tiles (whole rounds of the sweep's workgroups on
+  // 256 compute units) between 4,096 and 16,384, chosen so that the gradient GEMM's
+  // 256 x 256 output tiles of all slabs fill the fewest rounds; ties go to the larger slab
+  // (fewer launches, each of which ends in a partly idle round).
+  int64_t slab = 0;
+  if (getenv("ADWIN_SLAB_ROWS")) {
+    slab = (int64_t)align_up((size_t)env_int("ADWIN_SLAB_ROWS", 8192), kTileTokens);
+  } else {
+    int64_t best_rounds = -1;
+    for (int64_t r = 16384; r >= 4096; r -= 2048) {
+      int64_t rounds = 0;
+      for (int64_t r0 = 0; r0 < n_pad; r0 += r) {
+        const int64_t rows = n_pad - r0 < r ? n_pad - r0 : r;
+        rounds += (halves * (rows / kGradTile) * h_tiles + 255) / 256;
+      }
+      if (best_rounds < 0 || rounds < best_rounds) { best_rounds = rounds; slab = r; }
+    }
+  }
   if (slab > n_pad) slab = n_pad;
   L.slab_rows = slab;
-  const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
   const int64_t tiles = halves * (slab / kGradTile) * h_tiles;
   int ks = (int)(256 / (tiles > 0 ? tiles : 1));
   const int nk = (int)(L.Vp / kBK);
@@ -1275,6 +1291,20 @@ extern "C" int adwin_opd_workspace_bytes(const adwin_opd_problem* p, size_t* byt
   HostPlan hp = make_host_plan(p->T, p->B, p->offsets, p->window,
                                p->mode == ADWIN_PREFIX_AND_FULL, p->reduction, nullptr);
   *bytes = fused_layout(p, hp).total;
+  return ADWIN_OK;
+}
+
+extern "C" int adwin_opd_fused_launch_info(const adwin_opd_problem* p, int64_t info[4]) {
+  if (!info) return ADWIN_E_NULL;
+  int st = check_problem(p);
+  if (st != ADWIN_OK) return st;
+  HostPlan hp = make_host_plan(p->T, p->B, p->offsets, p->window,
+                               p->mode == ADWIN_PREFIX_AND_FULL, p->reduction, nullptr);
+  FusedLayout L = fused_layout(p, hp);
+  info[0] = hp.n_rows;
+  info[1] = hp.n_pad;
+  info[2] = L.slab_rows;
+  info[3] = hp.n_pad > 0 ? (hp.n_pad + L.slab_rows - 1) / L.slab_rows : 0;
   return ADWIN_OK;
 }
 

@@ -13,7 +13,7 @@ from tests import helpers as Hp
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
-K_ROWS = 40
+K_ROWS = 256
 
 
 @pytest.fixture(scope="module")
@@ -36,8 +36,10 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name):
     dev = torch.device("cuda:0")
     p = synth.hidden_problem(w, dev)
     probe = w.mode == synth.MODE_PREFIX_AND_FULL
+    cands = list(O.CANDIDATE_WINDOWS) if probe else None
     call = B.FusedCall(p["h_s"], p["h_t"], p["W_s"], p["W_t"], p["ids"], w.offsets, w.window,
-                       mode=w.mode, reduction=B.ADWIN_RED_SUM, dh_dtype=B.ADWIN_DT_F32)
+                       mode=w.mode, reduction=B.ADWIN_RED_SUM, dh_dtype=B.ADWIN_DT_F32,
+                       candidates=cands)
     st = call.run()
     assert st == 0, B.adwin_opd_strerror(st)
     torch.cuda.synchronize()
@@ -86,6 +88,23 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name):
         assert np.all(np.abs(out["batch"][2:6].cpu().numpy() - ref["batch"][2:6]) <= 1e-4)
         rp = out["rho_pooled"].cpu().numpy()
         assert np.all(rp <= 1 + 1e-6) and np.all(rp >= -1 - 1e-6)
+        # candidate audit (the paper's candidate list): per-rollout scores of the two shortest
+        # rollouts against the oracle's audit of those rollouts' gradients; aggregates by
+        # their defining properties
+        crp = out["cand_rho_pooled"].cpu().numpy()
+        crf = out["cand_rho_field"].cpu().numpy()
+        cb = out["cand_batch"].cpu().numpy()
+        for i in np.argsort(lens)[:2]:
+            o, n = int(w.offsets[i]), int(lens[i])
+            aud = O.audit_candidates(g_gpu[o:o + n], np.array([0, n]), cands, O.RED_SUM)
+            assert np.all(np.abs(crp[:, i] - aud["rho_pooled"][:, 0]) <= 1e-4), (i, crp[:, i])
+            assert np.all(np.abs(crf[:, i] - aud["rho_field"][:, 0]) <= 1e-4), (i, crf[:, i])
+        assert np.all(np.abs(cb[:, 2] - crp.mean(axis=1)) <= 1e-5)      # macro = mean over rollouts
+        assert np.all(np.abs(cb[:, 3] - crf.mean(axis=1)) <= 1e-5)
+        assert np.all(np.diff(crf, axis=0) >= -1e-6)                    # field cosine grows with L
+        k2048 = cands.index(2048)                                       # the call's own window
+        assert np.all(np.abs(crp[k2048] - rp) <= 1e-5)
+        assert np.all(np.abs(cb[k2048] - out["batch"][2:6].cpu().numpy()) <= 1e-5)
     del call, out, p
     _free()
 
