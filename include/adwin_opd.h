@@ -118,6 +118,12 @@ typedef struct adwin_opd_problem {
   float* cand_rho_field;     /* [n_candidates, B] per-rollout field cosine                      */
   float* cand_batch;         /* [n_candidates, 4] pooled micro, field micro, pooled macro,     */
                              /*                   field macro                                  */
+  /* Teacher-side drift diagnostics of Sec. 3.1, per computed row (0 on the others); NULL =
+   * not wanted.  The entropy and the rank add about 5 % to the vocabulary sweep. */
+  float* t_logp;             /* [T] log p_t(y_t) (needs ids; 0 for an id outside [0, V))        */
+  float* t_entropy;          /* [T] H[p_t] in nats; the branching factor is exp(H)              */
+  int32_t* t_rank;           /* [T] 1 + number of entries the teacher ranks strictly above y_t  */
+                             /*     (needs ids; 0 for an id outside [0, V))                     */
 } adwin_opd_problem;
 
 /*
@@ -145,6 +151,10 @@ typedef struct adwin_opd_logits_problem {
   int32_t* n_out;            /* [B]                                                            */
   int64_t* n_adm_out;        /* [1]                                                            */
   uint32_t* status_dev;      /* [1]                                                            */
+  /* teacher-side drift diagnostics of Sec. 3.1 (see adwin_opd_problem); NULL = not wanted      */
+  float* t_logp;             /* [T]                                                            */
+  float* t_entropy;          /* [T]                                                            */
+  int32_t* t_rank;           /* [T]                                                            */
 } adwin_opd_logits_problem;
 
 /* Library version: major*10000 + minor*100 + patch.  Pure host. */

@@ -334,6 +334,17 @@ def teacher_branching_factor(z_t):
     return float(np.exp(-np.sum(np.exp(lt) * lt)))
 
 
+def teacher_entropy(z_t):
+    """H[pi_phi(.|y_<t)] in nats (the logarithm of the branching factor)."""
+    lt = log_softmax(z_t)
+    return float(-np.sum(np.exp(lt) * lt))
+
+
+def teacher_logp(z_t, y):
+    """log pi_phi(y_t | y_<t): the teacher's log-probability of the sampled token."""
+    return float(log_softmax(z_t)[y])
+
+
 def teacher_rank(z_t, y):
     """Rank of y under the teacher distribution, 1 = most likely (ties: strictly
     greater logits count)."""

@@ -42,6 +42,7 @@ class adwin_opd_problem(C.Structure):
         ("n_out", C.c_void_p), ("n_adm_out", C.c_void_p), ("status_dev", C.c_void_p),
         ("candidates", C.c_void_p), ("n_candidates", C.c_int32),
         ("cand_rho_pooled", C.c_void_p), ("cand_rho_field", C.c_void_p), ("cand_batch", C.c_void_p),
+        ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
     ]
 
 
@@ -54,6 +55,7 @@ class adwin_opd_logits_problem(C.Structure):
         ("kl", C.c_void_p), ("c", C.c_void_p), ("dz", C.c_void_p),
         ("loss_prefix", C.c_void_p), ("batch", C.c_void_p),
         ("n_out", C.c_void_p), ("n_adm_out", C.c_void_p), ("status_dev", C.c_void_p),
+        ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
     ]
 
 
@@ -236,6 +238,8 @@ class FusedCall:
                 "rho_pooled": ((B,), torch.float32), "rho_field": ((B,), torch.float32),
                 "batch": ((8,), torch.float32), "n_out": ((B,), torch.int32),
                 "n_adm_out": ((1,), torch.int64), "status_dev": ((1,), torch.int32),
+                "t_logp": ((T,), torch.float32), "t_entropy": ((T,), torch.float32),
+                "t_rank": ((T,), torch.int32),
             }
             for k in want:
                 if k == "dh_full" and mode != ADWIN_PREFIX_AND_FULL:
@@ -321,6 +325,8 @@ class LogitsCall:
                 "dz": ((T, V), torch.bfloat16), "loss_prefix": ((B,), torch.float32),
                 "batch": ((8,), torch.float32), "n_out": ((B,), torch.int32),
                 "n_adm_out": ((1,), torch.int64), "status_dev": ((1,), torch.int32),
+                "t_logp": ((T,), torch.float32), "t_entropy": ((T,), torch.float32),
+                "t_rank": ((T,), torch.int32),
             }
             for k in want:
                 shp, dt = shapes[k]

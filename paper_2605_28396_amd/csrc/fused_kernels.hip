@@ -138,12 +138,15 @@ struct LogitPassArgs {
   // single-sweep mode: fixed per-row references and the offset of the second slab half
   const float* ref_s2; const float* ref_t2; const float* mu0;
   int64_t e2_off;
+  // diagnostics mode: teacher logit of the sampled token and the token id (-1: none) per row
+  const float* zy_t; const int32_t* yid;
 };
 
 // Modes of the direct-to-LDS logit kernel.
 constexpr int kModeStats = 0;   // online (running-max) statistics only
 constexpr int kModeDz = 1;      // second sweep of the two-sweep scheme: dz tiles
 constexpr int kModeSingle = 2;  // single sweep: fixed-reference statistics + E1/E2 tiles
+constexpr int kModeSingleDiag = 3;  // the same plus the teacher-side diagnostics of Sec. 3.1
 
 // Running per-token statistics held by one lane for its two token columns.
 struct LaneStats { float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2]; };
@@ -225,19 +228,24 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
 // and the unnormalised gradient factors E1 = e_s (d - mu0) and E2 = e_s can be emitted at
 // once: dz = (E1 - (mu - mu0) E2) / Z_s, hence g = (E1 W_s - (mu - mu0) E2 W_s) / Z_s.
 // E1 goes to slab rows row0.., E2 to the same rows e2_off elements further on.
-struct LaneSums { float Z_s[2], A_s[2], Z_t[2]; };
+// B_t = sum e_t z_t (teacher entropy) and cnt = entries ranked above the sampled token are
+// only maintained in diagnostics mode.
+struct LaneSums { float Z_s[2], A_s[2], Z_t[2], B_t[2]; int cnt[2]; };
 
-template <bool TAIL>
+template <bool TAIL, bool DIAG>
 __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                 LaneSums& sm, const float (&rs2)[2],
                                                 const float (&rt2)[2], const float (&mu0)[2],
+                                                const float (&zyt)[2], const int (&yid)[2],
                                                 __bf16* blk, int64_t e2_off, int wrow,
                                                 int v0, int V, int lane) {
   const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
     __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK + 4 * half;
-    float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn];
+    float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn], Bt = sm.B_t[fn];
+    int cnt = sm.cnt[fn];
+    const int vy = yid[fn] - vlane;        // position of the sampled token among this lane's entries
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
@@ -254,6 +262,10 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
           Zs += es;
           As = fmaf(es, d, As);
           Zt += et;
+          if (DIAG) {
+            Bt = fmaf(et, t, Bt);
+            cnt += (t > zyt[fn] && (fm * 32 + 8 * q + e) != vy && ok) ? 1 : 0;
+          }
           e1[e] = es * (d - mu0[fn]);
           e2[e] = es;
         }
@@ -265,9 +277,11 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
         *(uint2*)(out + e2_off + at) = o2;
       }
     sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
+    if (DIAG) { sm.B_t[fn] = Bt; sm.cnt[fn] = cnt; }
   }
 }
 
+template <bool DIAG>
 __device__ __forceinline__ void write_sums(LaneSums& sm, float* part, int strips, int strip,
                                            int64_t n_pad, int64_t row0, int lane) {
 #pragma unroll
@@ -275,12 +289,18 @@ __device__ __forceinline__ void write_sums(LaneSums& sm, float* part, int strips
     const float Zs = sm.Z_s[fn] + __shfl_xor(sm.Z_s[fn], 32, 64);
     const float As = sm.A_s[fn] + __shfl_xor(sm.A_s[fn], 32, 64);
     const float Zt = sm.Z_t[fn] + __shfl_xor(sm.Z_t[fn], 32, 64);
+    const float Bt = DIAG ? sm.B_t[fn] + __shfl_xor(sm.B_t[fn], 32, 64) : 0.f;
+    const int cnt = DIAG ? sm.cnt[fn] + __shfl_xor(sm.cnt[fn], 32, 64) : 0;
     if (lane < 32) {
       const int64_t plane = (int64_t)strips * n_pad;
       float* o = part + (int64_t)strip * n_pad + row0 + fn * 32 + lane;
       o[0 * plane] = Zs;
       o[1 * plane] = As;
       o[2 * plane] = Zt;
+      if (DIAG) {
+        o[3 * plane] = Bt;
+        o[4 * plane] = (float)cnt;     // at most V < 2^24: exact
+      }
     }
   }
 }
@@ -528,20 +548,25 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 
   LaneStats st;
   LaneSums sm;
+  constexpr bool kDiag = MODE == kModeSingleDiag;
+  constexpr bool kSingle = MODE == kModeSingle || kDiag;
   float lse2[2], mu[2], rs2[2], rt2[2];   // per-row inputs of the dz / single-sweep epilogues
+  float zyt[2];
+  int yid[2];
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
     st.m_s[fn] = kNegBig; st.Z_s[fn] = 0.f; st.A_s[fn] = 0.f; st.m_t[fn] = kNegBig; st.Z_t[fn] = 0.f;
-    sm.Z_s[fn] = 0.f; sm.A_s[fn] = 0.f; sm.Z_t[fn] = 0.f;
-    lse2[fn] = 0.f; mu[fn] = 0.f; rs2[fn] = 0.f; rt2[fn] = 0.f;
+    sm.Z_s[fn] = 0.f; sm.A_s[fn] = 0.f; sm.Z_t[fn] = 0.f; sm.B_t[fn] = 0.f; sm.cnt[fn] = 0;
+    lse2[fn] = 0.f; mu[fn] = 0.f; rs2[fn] = 0.f; rt2[fn] = 0.f; zyt[fn] = 0.f; yid[fn] = -1;
     const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
     if (MODE == kModeDz) {
       lse2[fn] = a.lse2[r];
       mu[fn] = a.mu[r];
-    } else if (MODE == kModeSingle) {
+    } else if (kSingle) {
       rs2[fn] = a.ref_s2[r];
       rt2[fn] = a.ref_t2[r];
       mu[fn] = a.mu0[r];
+      if (kDiag) { zyt[fn] = a.zy_t[r]; yid[fn] = a.yid[r]; }
     }
   }
 
@@ -640,15 +665,15 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       if (MODE == kModeDz) {
         dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
       } else if (tail) {
-        single_epilogue<true>(zs, zt, sm, rs2, rt2, mu, blk, a.e2_off, wave * 64, v0, a.V, lane);
+        single_epilogue<true, kDiag>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
       } else {
-        single_epilogue<false>(zs, zt, sm, rs2, rt2, mu, blk, a.e2_off, wave * 64, v0, a.V, lane);
+        single_epilogue<false, kDiag>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
       }
     }
   }
   const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
   if (MODE == kModeStats) write_partials(st, a.part, a.strips, strip, a.n_pad, row0, lane);
-  else if (MODE == kModeSingle) write_sums(sm, a.part, a.strips, strip, a.n_pad, row0, lane);
+  else if (kSingle) write_sums<kDiag>(sm, a.part, a.strips, strip, a.n_pad, row0, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -663,6 +688,10 @@ struct MergeArgs {
   float* lse2; float* mu; float* klr;
   float* kl; float* c;
   uint32_t* status;
+  // teacher-side diagnostics (single-sweep merge only); part planes 3 and 4 hold
+  // sum e_t z_t and the rank count when `diag` is set
+  int diag;
+  float* t_logp; float* t_entropy; int32_t* t_rank;
 };
 
 __device__ __forceinline__ float dot_bf16_row(const __bf16* x, const __bf16* y, int H, int lane) {
@@ -751,12 +780,14 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= a.n_pad) return;
   const int64_t plane = (int64_t)a.strips * a.n_pad;
-  float Zs = 0.f, A = 0.f, Zt = 0.f;
+  float Zs = 0.f, A = 0.f, Zt = 0.f, Bt = 0.f, cnt = 0.f;
   if (lane < a.strips) {
     const float* p = a.part + (int64_t)lane * a.n_pad + r;
     Zs = p[0]; A = p[plane]; Zt = p[2 * plane];
+    if (a.diag) { Bt = p[3 * plane]; cnt = p[4 * plane]; }
   }
   Zs = wave_sum(Zs); A = wave_sum(A); Zt = wave_sum(Zt);
+  if (a.diag) { Bt = wave_sum(Bt); cnt = wave_sum(cnt); }
   const float lse_s = b.ref_s2[r] * kLn2 + logf(Zs), lse_t = b.ref_t2[r] * kLn2 + logf(Zt);
   const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
   const float kl = mu - lse_s + lse_t;
@@ -767,14 +798,17 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
   }
   if (r >= a.n_rows) return;
   const int64_t t = a.row_idx[r];
-  float c = 0.f;
+  float c = 0.f, logp_t = 0.f;
+  bool have_y = false;
   uint32_t flag = 0;
-  if (a.ids && a.c) {
+  if (a.ids && (a.c || a.t_logp || a.t_rank)) {
     const int y = a.ids[t];
     if (y >= 0 && y < a.V) {
       const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
       const float zy_t = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)y * a.H_t, a.H_t, lane);
       c = (zy_s - lse_s) - (zy_t - lse_t);
+      logp_t = zy_t - lse_t;
+      have_y = true;
     } else {
       flag |= ADWIN_DEV_BAD_ID;
     }
@@ -786,7 +820,30 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
     if (flag && a.status) atomicOr(a.status, flag);
     if (a.kl) a.kl[t] = kl;
     if (a.c) a.c[t] = c;
+    if (a.t_logp) a.t_logp[t] = logp_t;
+    // H[p_t] = lse_t - E_{p_t}[z_t]; both sums are relative to the same reference
+    if (a.t_entropy) a.t_entropy[t] = lse_t - Bt / Zt;
+    if (a.t_rank) a.t_rank[t] = have_y ? (int32_t)cnt + 1 : 0;
   }
+}
+
+// Teacher logit of the sampled token, z_t[y_t] = h_t . W_t[y_t], and the token id (-1 when
+// there is none or it is out of range), per computed row: what the sweep compares against
+// to count the entries the teacher ranks above y_t (Sec. 3.1).  One wave per row.
+__global__ __launch_bounds__(256) void token_logit_kernel(const int32_t* __restrict__ row_idx,
+                                                          const int32_t* __restrict__ ids,
+                                                          const __bf16* __restrict__ h_t,
+                                                          const __bf16* __restrict__ W_t, int H_t, int V,
+                                                          int64_t n_pad, float* zy_t, int32_t* yid) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= n_pad) return;
+  const int64_t t = row_idx[r];
+  const int y = ids ? ids[t] : -1;
+  float z = 0.f;
+  const bool ok = y >= 0 && y < V;
+  if (ok) z = dot_bf16_row(h_t + t * H_t, W_t + (int64_t)y * H_t, H_t, lane);
+  if (lane == 0) { zy_t[r] = z; yid[r] = ok ? y : -1; }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1142,7 +1199,7 @@ struct FusedLayout {
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_zy_t, o_yid, total;
 };
 
 static int env_int(const char* name, int dflt) {
@@ -1227,6 +1284,8 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_uc = take(sizeof(float) * kc * (size_t)p->B * (size_t)p->H_s);
   L.o_cacc = take(sizeof(double) * 4 * kc * (size_t)p->B);
   L.o_cS = take(sizeof(double) * kc * (size_t)p->B);
+  L.o_zy_t = take(sizeof(float) * (size_t)n_pad);
+  L.o_yid = take(sizeof(int32_t) * (size_t)n_pad);
   L.total = o;
   return L;
 }
@@ -1271,6 +1330,9 @@ static hipError_t ensure_lds_opt_in() {
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingle>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingleDiag>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)grad_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1340,9 +1402,14 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   const int64_t n_pad = hp.n_pad;
 
   ADWIN_HIP_TRY(launch_fill_u32(p->status_dev, 1, 0u, stream));
-  if (!probe) {   // rows outside the windows report zero KL and cost
+  const bool diag = p->t_entropy || p->t_rank;          // need the diagnostics sweep
+  if ((diag || p->t_logp) && !L.single) return ADWIN_E_MODE;
+  if (!probe) {   // rows outside the windows report zero KL, cost and diagnostics
     ADWIN_HIP_TRY(launch_fill_f32(p->kl, p->T, 0.f, stream));
     ADWIN_HIP_TRY(launch_fill_f32(p->c, p->T, 0.f, stream));
+    ADWIN_HIP_TRY(launch_fill_f32(p->t_logp, p->T, 0.f, stream));
+    ADWIN_HIP_TRY(launch_fill_f32(p->t_entropy, p->T, 0.f, stream));
+    ADWIN_HIP_TRY(launch_fill_u32((uint32_t*)p->t_rank, p->T, 0u, stream));
   } else if (!p->ids) {
     ADWIN_HIP_TRY(launch_fill_f32(p->c, p->T, 0.f, stream));
   }
@@ -1379,6 +1446,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     m.H_s = p->H_s; m.H_t = p->H_t; m.V = p->V; m.ids = p->ids;
     m.lse2 = (float*)(ws + L.o_lse2); m.mu = (float*)(ws + L.o_mu); m.klr = klr;
     m.kl = p->kl; m.c = p->c; m.status = p->status_dev;
+    m.diag = diag ? 1 : 0; m.t_logp = p->t_logp; m.t_entropy = p->t_entropy; m.t_rank = p->t_rank;
     GradArgs ga;
     ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.nk_total = (int)(L.Vp / kBK);
     ga.g = gws; ga.H = p->H_s; ga.h_tiles = h_tiles; ga.ksplit = L.ksplit;
@@ -1396,6 +1464,13 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         ADWIN_HIP_TRY(hipGetLastError());
       }
       la.vt_total = vt_total; la.strips = L.strips1;
+      la.zy_t = (const float*)(ws + L.o_zy_t); la.yid = (const int32_t*)(ws + L.o_yid);
+      if (diag) {
+        token_logit_kernel<<<(unsigned)((n_pad + 3) / 4), 256, 0, stream>>>(
+            pl.row_idx, p->ids, la.h_t, la.W_t, p->H_t, p->V, n_pad, (float*)(ws + L.o_zy_t),
+            (int32_t*)(ws + L.o_yid));
+        ADWIN_HIP_TRY(hipGetLastError());
+      }
       ga.g_rows = 2 * n_pad; ga.half_off = n_pad;
       for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
         const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
@@ -1403,7 +1478,10 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         la.e2_off = rows * L.Vp;
         const int groups = (la.n_tiles + la.tg - 1) / la.tg;
         phase(ADWIN_PHASE_STATS);
-        logit_pass_dma_kernel<kModeSingle><<<(unsigned)(groups * la.tg * L.strips1), 256, kDmaLds, stream>>>(la);
+        if (diag)
+          logit_pass_dma_kernel<kModeSingleDiag><<<(unsigned)(groups * la.tg * L.strips1), 256, kDmaLds, stream>>>(la);
+        else
+          logit_pass_dma_kernel<kModeSingle><<<(unsigned)(groups * la.tg * L.strips1), 256, kDmaLds, stream>>>(la);
         ADWIN_HIP_TRY(hipGetLastError());
         phase(ADWIN_PHASE_GRAD);
         ga.slab_row0 = r0;

@@ -24,6 +24,8 @@ struct LogitsArgs {
   uint4* dz;
   float* klr;          // [T] workspace copy of KL_t on computed rows (compact index)
   uint32_t* status;
+  // teacher-side diagnostics (Sec. 3.1), each may be NULL
+  float* t_logp; float* t_entropy; int32_t* t_rank;
 };
 
 __device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
@@ -33,8 +35,12 @@ __device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
   f[6] = bf16_lo(q.w); f[7] = bf16_hi(q.w);
 }
 
+// DIAG: also the teacher-side drift diagnostics of Sec. 3.1 for the row: entropy of the
+// teacher distribution (H = lse_t - E_{p_t}[z_t]; the branching factor is exp(H)), the rank of
+// y_t under the teacher (1 + number of entries with a strictly larger logit) and log p_t(y_t).
+template <bool DIAG>
 __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
-  __shared__ float sh[5][kRowThreads / 64];
+  __shared__ float sh[7][kRowThreads / 64];
   __shared__ float bc[4];
   const int64_t t = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -50,11 +56,26 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
     if (tid == 0) {
       if (a.kl) a.kl[t] = 0.f;
       if (a.c) a.c[t] = 0.f;
+      if (DIAG) {
+        if (a.t_logp) a.t_logp[t] = 0.f;
+        if (a.t_entropy) a.t_entropy[t] = 0.f;
+        if (a.t_rank) a.t_rank[t] = 0;
+      }
     }
     return;
   }
   const uint4* zs = a.z_s + t * nvec;
   const uint4* zt = a.z_t + t * nvec;
+  // sampled token and its teacher logit, for the rank
+  int y = -1;
+  float zy_rank = 0.f;
+  if (DIAG && a.ids) {
+    y = a.ids[t];
+    if (y >= 0 && y < a.V) zy_rank = __uint_as_float((uint32_t)((const uint16_t*)zt)[y] << 16);
+    else y = -1;
+  }
+  float Bt = 0.f;     // sum e^{z_t - m_t} z_t
+  int cnt = 0;        // entries the teacher ranks strictly above y_t
 
   // ---- sweep 1: running max / sum-exp of both rows and A = sum e^{z_s-m}(z_s-z_t) ----
   float ms = kNegBig, Zs = 0.f, A = 0.f, mt = kNegBig, Zt = 0.f;
@@ -70,29 +91,52 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
       const float sc = fast_exp2((ms - mx) * kLog2e);
       Zs *= sc; A *= sc; ms = mx;
     }
-    if (mxt > mt) { Zt *= fast_exp2((mt - mxt) * kLog2e); mt = mxt; }
+    if (mxt > mt) {
+      const float sc = fast_exp2((mt - mxt) * kLog2e);
+      Zt *= sc; Bt *= sc; mt = mxt;
+    }
     const float ms2 = ms * kLog2e, mt2 = mt * kLog2e;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const float e = fast_exp2(fmaf(s[k], kLog2e, -ms2));
       Zs += e;
       A = fmaf(e, s[k] - u[k], A);
-      Zt += fast_exp2(fmaf(u[k], kLog2e, -mt2));
+      const float et = fast_exp2(fmaf(u[k], kLog2e, -mt2));
+      Zt += et;
+      if (DIAG) {
+        Bt = fmaf(et, u[k], Bt);
+        cnt += (u[k] > zy_rank && q * 8 + k != y) ? 1 : 0;
+      }
     }
   }
   // wave then block merge, fixed order
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     merge_mza(ms, Zs, A, __shfl_xor(ms, o, 64), __shfl_xor(Zs, o, 64), __shfl_xor(A, o, 64));
-    merge_mz(mt, Zt, __shfl_xor(mt, o, 64), __shfl_xor(Zt, o, 64));
+    if (DIAG) {
+      merge_mza(mt, Zt, Bt, __shfl_xor(mt, o, 64), __shfl_xor(Zt, o, 64), __shfl_xor(Bt, o, 64));
+      cnt += __shfl_xor(cnt, o, 64);
+    } else {
+      merge_mz(mt, Zt, __shfl_xor(mt, o, 64), __shfl_xor(Zt, o, 64));
+    }
   }
-  if (lane == 0) { sh[0][w] = ms; sh[1][w] = Zs; sh[2][w] = A; sh[3][w] = mt; sh[4][w] = Zt; }
+  if (lane == 0) {
+    sh[0][w] = ms; sh[1][w] = Zs; sh[2][w] = A; sh[3][w] = mt; sh[4][w] = Zt;
+    if (DIAG) { sh[5][w] = Bt; sh[6][w] = __int_as_float(cnt); }
+  }
   __syncthreads();
   if (tid == 0) {
     float m = sh[0][0], Z = sh[1][0], Aa = sh[2][0], m2 = sh[3][0], Z2 = sh[4][0];
+    float B2 = DIAG ? sh[5][0] : 0.f;
+    int rank = DIAG ? __float_as_int(sh[6][0]) : 0;
     for (int k = 1; k < kRowThreads / 64; ++k) {
       merge_mza(m, Z, Aa, sh[0][k], sh[1][k], sh[2][k]);
-      merge_mz(m2, Z2, sh[3][k], sh[4][k]);
+      if (DIAG) {
+        merge_mza(m2, Z2, B2, sh[3][k], sh[4][k], sh[5][k]);
+        rank += __float_as_int(sh[6][k]);
+      } else {
+        merge_mz(m2, Z2, sh[3][k], sh[4][k]);
+      }
     }
     const float lse_s = m + logf(Z), lse_t = m2 + logf(Z2);
     const float mu = Aa / Z;                       // E_{p_s}[z_s - z_t]
@@ -116,6 +160,11 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
     if (flag && a.status) atomicOr(a.status, flag);
     if (a.kl) a.kl[t] = kl;
     if (a.c) a.c[t] = c;
+    if (DIAG) {
+      if (a.t_entropy) a.t_entropy[t] = lse_t - B2 / Z2;
+      if (a.t_logp) a.t_logp[t] = y >= 0 ? zy_rank - lse_t : 0.f;
+      if (a.t_rank) a.t_rank[t] = y >= 0 ? rank + 1 : 0;
+    }
     a.klr[a.pl.comp_off[i] + j] = kl;
     bc[0] = lse_s * kLog2e;
     bc[1] = mu;
@@ -396,10 +445,14 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
     a.z_s = (const uint4*)p->z_s; a.z_t = (const uint4*)p->z_t; a.ids = p->ids;
     a.grad_scale = p->grad_scale;
     a.kl = p->kl; a.c = p->c; a.dz = (uint4*)p->dz; a.klr = klr; a.status = p->status_dev;
+    a.t_logp = p->t_logp; a.t_entropy = p->t_entropy; a.t_rank = p->t_rank;
     PhaseScope scope(timer, ADWIN_PHASE_STATS);
     static const bool streaming = getenv("ADWIN_LOGITS_STREAMING") != nullptr;
-    if (streaming) {
-      logits_row_kernel<<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
+    if (p->t_logp || p->t_entropy || p->t_rank) {
+      // the diagnostics ride on the streaming kernel (the row-resident one has no register to spare)
+      logits_row_kernel<true><<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
+    } else if (streaming) {
+      logits_row_kernel<false><<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
     } else {
       static bool opted = false;
       if (!opted) {

@@ -186,3 +186,68 @@ def test_candidate_audit_matches_oracle(B, name, reduction):
     assert B.adwin_opd_next_window(got["cand_batch"][:, 0], cands) in \
         {O.next_window(aud["micro"], cands), O.next_window(aud["micro"] - 2 * Hp.RHO_ABS, cands),
          O.next_window(aud["micro"] + 2 * Hp.RHO_ABS, cands)}
+
+
+def _teacher_reference(z_t, ids, rows, delta):
+    """Oracle diagnostics of the given rows; the rank as a band [lo, hi] that absorbs logits
+    within `delta` of the sampled token's (the two sides round the logits differently)."""
+    ent, logp, lo, hi = {}, {}, {}, {}
+    for t in rows:
+        z, y = z_t[t], int(ids[t])
+        ent[t], logp[t] = O.teacher_entropy(z), O.teacher_logp(z, y)
+        exact = O.teacher_rank(z, y)
+        near = np.abs(z - z[y]) <= delta
+        near[y] = False
+        lo[t] = exact - int(np.sum(near & (z > z[y])))
+        hi[t] = exact + int(np.sum(near & (z <= z[y])))
+    return ent, logp, lo, hi
+
+
+@pytest.mark.parametrize("name", ["tiny_probe", "ragged_small", "ragged_mid"])
+def test_teacher_diagnostics_fused(B, name):
+    """Teacher entropy, rank of the sampled token and its teacher log-probability (Sec. 3.1)
+    as by-products of the sweep."""
+    w = synth.workload(name)
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    want = ("kl", "c", "dh_prefix", "dh_full", "loss_prefix", "loss_full", "rho_pooled", "rho_field",
+            "batch", "n_out", "n_adm_out", "status_dev", "t_logp", "t_entropy", "t_rank")
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, want=want)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SUM, grad_scale=1.0, mode=w.mode)
+    _check_fused(w, got, ref, O.RED_SUM)                 # the diagnostics mode changes nothing else
+    z_t = f["h_t"] @ f["W_t"].T
+    rows = list(ref["rows"])
+    ent, logp, lo, hi = _teacher_reference(z_t, f["ids"], rows, 1e-4)
+    for t in rows:
+        assert abs(got["t_entropy"][t] - ent[t]) <= 1e-3, (t, got["t_entropy"][t], ent[t])
+        assert abs(got["t_logp"][t] - logp[t]) <= 1e-3 * max(1.0, abs(logp[t]))
+        assert lo[t] <= got["t_rank"][t] <= hi[t], (t, got["t_rank"][t], lo[t], hi[t])
+    assert sum(hi[t] - lo[t] for t in rows) <= 3 * len(rows)  # the bands are narrow: a few near-ties per row
+    other = np.setdiff1d(np.arange(w.T), ref["rows"])
+    assert not got["t_entropy"][other].any() and not got["t_rank"][other].any()
+
+
+def test_teacher_diagnostics_from_logits_exact_rank(B):
+    w = synth.workload("ragged_small")
+    p = synth.logits_problem(w)
+    f = Hp.oracle_inputs(p)
+    d = {k: v.cuda() for k, v in p.items()}
+    want = ("kl", "c", "dz", "loss_prefix", "batch", "n_out", "n_adm_out", "status_dev",
+            "t_logp", "t_entropy", "t_rank")
+    out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window,
+                                  reduction=O.RED_SUM, want=want)
+    torch.cuda.synchronize()
+    got = {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
+           for k, v in out.items()}
+    ref = O.supervise_from_logits(f["z_s"], f["z_t"], f["ids"], w.offsets, w.window, reduction=O.RED_SUM)
+    Hp.assert_kl(got["kl"], ref["kl"])
+    Hp.assert_grad(got["dz"], ref["dz"], "dz", Hp.BF16_ULP)
+    rows = O.plan(w.offsets, w.window)["rows"]
+    for t in rows:
+        z, y = f["z_t"][t], int(f["ids"][t])
+        assert got["t_rank"][t] == O.teacher_rank(z, y)                 # bf16 inputs: exact
+        assert abs(got["t_entropy"][t] - O.teacher_entropy(z)) <= 1e-4
+        assert abs(got["t_logp"][t] - O.teacher_logp(z, y)) <= 1e-4 * max(1.0, abs(O.teacher_logp(z, y)))
+    other = np.setdiff1d(np.arange(w.T), rows)
+    assert not got["t_entropy"][other].any() and not got["t_rank"][other].any()

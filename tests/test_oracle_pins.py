@@ -413,6 +413,11 @@ def test_teacher_diagnostics():
     assert [O.teacher_rank(z, y) for y in range(5)] == [4, 1, 5, 1, 3]
     p = scipy.special.softmax(z)
     assert O.teacher_branching_factor(z) == pytest.approx(math.exp(scipy.stats.entropy(p)), rel=1e-12)
+    assert O.teacher_entropy(np.zeros(37)) == pytest.approx(math.log(37.0), rel=1e-12)
+    assert O.teacher_entropy(z) == pytest.approx(scipy.stats.entropy(p), rel=1e-12)
+    assert O.teacher_entropy(z) == pytest.approx(math.log(O.teacher_branching_factor(z)), rel=1e-12)
+    assert O.teacher_logp(z, 2) == pytest.approx(math.log(p[2]), rel=1e-12)
+    assert O.teacher_logp(np.zeros(8), 3) == pytest.approx(-math.log(8.0), rel=1e-12)
     ranks = [[1, 2, 9, 1], [1, 1, 1, 1], [5, 1, 1, 1]]
     assert O.topk_survival(ranks, 3, 2) == pytest.approx(2 / 3)
     assert O.topk_survival(ranks, 3, 4) == pytest.approx(1 / 3)
