@@ -140,6 +140,8 @@ struct LogitPassArgs {
   int64_t e2_off;
   // diagnostics mode: teacher logit of the sampled token and the token id (-1: none) per row
   const float* zy_t; const int32_t* yid;
+  // direct-to-LDS kernel: tile images of the four operands (see row_image_kernel)
+  const char* Wt_img; const char* Ws_img; const char* ht_img; const char* hs_img;
 };
 
 // Modes of the direct-to-LDS logit kernel.
@@ -430,17 +432,46 @@ __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-struct DmaOffsets { uint32_t a[kTileVocab / 32]; uint32_t b[kTileTokens / 32]; };
+// Row images.  The direct-to-LDS logit kernel reads all four operands as LDS images of its
+// k-steps: [rows, H] row-major (optionally gathered through row_idx) is re-laid as tiles of
+// `th` consecutive rows; block (tile, kt) holds their k-entries 64 kt .. 64 kt + 63, row r at
+// r * 128 B, its 16-byte chunk c at chunk position c ^ ((r >> 1) & 7); rows >= n_rows are
+// zero.  Blocks of one tile are consecutive in kt.  Every wave-load then moves 1 KiB of
+// consecutive bytes and no operand needs 32-bit lane offsets from its base.
+struct RowImageArgs {
+  const uint4* src; uint4* img; const int32_t* row_idx;
+  int64_t n_rows; int H, nk, th;
+};
 
-// Wave-load I (0..11) of this wave for one stage.
+__global__ __launch_bounds__(256) void row_image_kernel(RowImageArgs a) {
+  const int kt = blockIdx.x;
+  const int64_t tile = blockIdx.y;
+  uint4* blk = a.img + ((tile * a.nk + kt) * a.th) * 8;
+  for (int q = threadIdx.x; q < a.th * 8; q += 256) {
+    const int r = q >> 3, pos = q & 7, c = pos ^ ((r >> 1) & 7);
+    const int64_t row = tile * a.th + r;
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (row < a.n_rows) {
+      const int64_t src_row = a.row_idx ? (int64_t)a.row_idx[row] : row;
+      v = a.src[src_row * (a.H >> 3) + kt * 8 + c];
+    }
+    blk[q] = v;
+  }
+}
+
+constexpr int kImgABytes = kTileVocab * kRowBytes;    // 16 KiB: one W block
+constexpr int kImgBBytes = kTileTokens * kRowBytes;   // 32 KiB: one h block
+
+// Wave-load I (0..11) of this wave for one stage: KiB (wave + 4 I) of the A block, then of
+// the B block; lane l moves bytes 16 l .. 16 l + 15 of that KiB.
 template <int I>
-__device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, const DmaOffsets& o,
-                                        const char* sA, const char* sB) {
+__device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, uint32_t voff, const char* sA,
+                                        const char* sB) {
   if constexpr (I < kTileVocab / 32)
-    dma16(lds_stage + (uint32_t)(wave + 4 * I) * 1024u, o.a[I], sA);
+    dma16(lds_stage + (uint32_t)(wave + 4 * I) * 1024u, voff, sA + (wave + 4 * I) * 1024);
   else
-    dma16(lds_stage + (uint32_t)(kTileVocab / 8 + wave + 4 * (I - kTileVocab / 32)) * 1024u,
-          o.b[I - kTileVocab / 32], sB);
+    dma16(lds_stage + (uint32_t)(kTileVocab / 8 + wave + 4 * (I - kTileVocab / 32)) * 1024u, voff,
+          sB + (wave + 4 * (I - kTileVocab / 32)) * 1024);
 }
 
 // One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  On entry fa[0],
@@ -457,7 +488,7 @@ template <bool ISSUE, bool LAST>
 __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
                                             const char* curA, const char* curB, const char* nxtA,
                                             const char* nxtB, int lane, uint32_t lds_stage, int wave,
-                                            const DmaOffsets& o, const char* sA, const char* sB) {
+                                            uint32_t voff, const char* sA, const char* sB) {
   const int key = (lane >> 1) & 7, half = lane >> 5;
   const int rowoff = (lane & 31) * kRowBytes;
   int sw[4];
@@ -470,7 +501,7 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
   acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
                                                           acc[FMI][FNI], 0, 0, 0);              \
   ADWIN_FENCE
-#define ADWIN_DMA(I) if constexpr (ISSUE) { dma_one<I>(lds_stage, wave, o, sA, sB); ADWIN_FENCE }
+#define ADWIN_DMA(I) if constexpr (ISSUE) { dma_one<I>(lds_stage, wave, voff, sA, sB); ADWIN_FENCE }
   // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from (TA, TB) when READ
 #define ADWIN_SUB(KK, READ, TA, TB, D0, D1, D2)                         \
   ADWIN_MM(KK, 0, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 0) }        \
@@ -517,34 +548,14 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   if (vt_begin >= vt_end) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
-  // lane -> (row within its 8-row group, chunk position); global chunk = pos ^ swizzle(row)
-  const int lrow = lane >> 3, lpos = lane & 7;
-  DmaOffsets os, ot;     // student / teacher operand offsets in bytes
-#pragma unroll
-  for (int j = 0; j < kTileTokens / 32; ++j) {
-    const int row = (wave + 4 * j) * 8 + lrow;                       // row in the 256-token tile
-    const int chunk = lpos ^ ((row >> 1) & 7);
-    const uint32_t r = (uint32_t)a.row_idx[(int64_t)tt * kTileTokens + row];
-    os.b[j] = r * (uint32_t)(a.H_s * 2) + chunk * 16;
-    ot.b[j] = r * (uint32_t)(a.H_t * 2) + chunk * 16;
-  }
-  // W rows of the vocabulary tile starting at v0, relative to row v0 (tail rows: a valid
-  // row, masked in the epilogue)
-  auto set_w_offsets = [&](int v0) {
-#pragma unroll
-    for (int j = 0; j < kTileVocab / 32; ++j) {
-      const int row = (wave + 4 * j) * 8 + lrow;                     // row in the 128-row W tile
-      const int chunk = lpos ^ ((row >> 1) & 7);
-      int v = v0 + row;
-      v = v < a.V ? v : a.V - 1;
-      os.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_s * 2) + chunk * 16;
-      ot.a[j] = (uint32_t)(v - v0) * (uint32_t)(a.H_t * 2) + chunk * 16;
-    }
-  };
+  const uint32_t voff = (uint32_t)lane * 16u;
   const int waveA = 0, waveB = kTileVocab * kRowBytes + wave * 64 * kRowBytes;
   const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;   // each >= 2 on this path
-  const char* sHt = (const char*)a.h_t;
-  const char* sHs = (const char*)a.h_s;
+  // blocks of this token tile (fixed) and of vocabulary tile vt, teacher and student
+  const char* sHt = a.ht_img + (int64_t)tt * nk_t * kImgBBytes;
+  const char* sHs = a.hs_img + (int64_t)tt * nk_s * kImgBBytes;
+  auto blocks_wt = [&](int vt) { return a.Wt_img + (int64_t)vt * nk_t * kImgABytes; };
+  auto blocks_ws = [&](int vt) { return a.Ws_img + (int64_t)vt * nk_s * kImgABytes; };
 
   LaneStats st;
   LaneSums sm;
@@ -577,31 +588,25 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   uint32_t wr = 0, rd = 0;     // ring slots of the next step to load / to consume
   auto slot_inc = [](uint32_t x) { return x + 1 == kDmaStages ? 0u : x + 1; };
   {
-    const int v0 = vt_begin * kTileVocab;
-    set_w_offsets(v0);
-    const char* sWt = (const char*)(a.W_t + (int64_t)v0 * a.H_t);
+    const char* sWt = blocks_wt(vt_begin);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const uint32_t dst = lds0 + wr * kLogitStage;
-      dma_one<0>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<1>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<2>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<3>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<4>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<5>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<6>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<7>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<8>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<9>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<10>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
-      dma_one<11>(dst, wave, ot, sWt + i * kRowBytes, sHt + i * kRowBytes);
+      const char* sA = sWt + i * kImgABytes;
+      const char* sB = sHt + i * kImgBBytes;
+      dma_one<0>(dst, wave, voff, sA, sB); dma_one<1>(dst, wave, voff, sA, sB);
+      dma_one<2>(dst, wave, voff, sA, sB); dma_one<3>(dst, wave, voff, sA, sB);
+      dma_one<4>(dst, wave, voff, sA, sB); dma_one<5>(dst, wave, voff, sA, sB);
+      dma_one<6>(dst, wave, voff, sA, sB); dma_one<7>(dst, wave, voff, sA, sB);
+      dma_one<8>(dst, wave, voff, sA, sB); dma_one<9>(dst, wave, voff, sA, sB);
+      dma_one<10>(dst, wave, voff, sA, sB); dma_one<11>(dst, wave, voff, sA, sB);
       wr = slot_inc(wr);
     }
   }
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int v0 = vt * kTileVocab;
-    const char* sWt = (const char*)(a.W_t + (int64_t)v0 * a.H_t);
-    const char* sWs = (const char*)(a.W_s + (int64_t)v0 * a.H_s);
+    const char* sWt = blocks_wt(vt);
+    const char* sWs = blocks_ws(vt);
     f32x16 zt[4][2], zs[4][2];
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
@@ -624,14 +629,13 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       for (int i = 0; i < 2; ++i) fb[0][i] = *(const bf16x8*)(cur + waveB + i * 32 * kRowBytes + sw0);
     }
     // one k-step: consume slot rd, prefetch fragments from the following slot, load into wr
-    auto step = [&](auto issue_c, auto last_c, f32x16 (&acc)[4][2], const DmaOffsets& o, const char* sA,
-                    const char* sB) {
+    auto step = [&](auto issue_c, auto last_c, f32x16 (&acc)[4][2], const char* sA, const char* sB) {
       constexpr bool kIssue = decltype(issue_c)::value, kLast = decltype(last_c)::value;
       const char* cur = lds + rd * kLogitStage;
       const uint32_t rn = slot_inc(rd);
       const char* nxt = lds + rn * kLogitStage;
       sweep_kstep<kIssue, kLast>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
-                                 lds0 + wr * kLogitStage, wave, o, sA, sB);
+                                 lds0 + wr * kLogitStage, wave, voff, sA, sB);
       if (kIssue) wr = slot_inc(wr);
       rd = rn;
     };
@@ -639,23 +643,22 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     const std::false_type no{};
     int s = 0;
     for (; s + 2 < nk_t; ++s)                  // teacher k-steps loading teacher k-steps
-      step(yes, no, zt, ot, sWt + (s + 2) * kRowBytes, sHt + (s + 2) * kRowBytes);
+      step(yes, no, zt, sWt + (s + 2) * kImgABytes, sHt + (s + 2) * kImgBBytes);
     for (; s < nk_t; ++s) {                    // last two teacher k-steps load student k-steps 0, 1
       const int n = s + 2 - nk_t;
-      step(yes, no, zt, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
+      step(yes, no, zt, sWs + n * kImgABytes, sHs + n * kImgBBytes);
     }
     for (; s + 2 < nk; ++s) {                  // student k-steps loading student k-steps
       const int n = s + 2 - nk_t;
-      step(yes, no, zs, os, sWs + n * kRowBytes, sHs + n * kRowBytes);
+      step(yes, no, zs, sWs + n * kImgABytes, sHs + n * kImgBBytes);
     }
     if (vt + 1 < vt_end) {                     // last two: load the next tile's teacher k-steps 0, 1
-      set_w_offsets(v0 + kTileVocab);
-      const char* sWn = (const char*)(a.W_t + (int64_t)(v0 + kTileVocab) * a.H_t);
-      step(yes, no, zs, ot, sWn, sHt);
-      step(yes, yes, zs, ot, sWn + kRowBytes, sHt + kRowBytes);
+      const char* sWn = blocks_wt(vt + 1);
+      step(yes, no, zs, sWn, sHt);
+      step(yes, yes, zs, sWn + kImgABytes, sHt + kImgBBytes);
     } else {
-      step(no, no, zs, os, sWs, sHs);
-      step(no, yes, zs, os, sWs, sHs);
+      step(no, no, zs, sWs, sHs);
+      step(no, yes, zs, sWs, sHs);
     }
     const bool tail = v0 + kTileVocab > a.V;
     if (MODE == kModeStats) {
@@ -1194,6 +1197,7 @@ __global__ __launch_bounds__(256) void pool_final_kernel(PoolArgs a) {
 struct FusedLayout {
   bool use_dma;      // logit passes staged by direct global->LDS loads
   bool single;       // single-sweep scheme (needs use_dma)
+  size_t o_wt_img, o_ws_img, o_ht_img, o_hs_img;   // tile images of the logit operands (use_dma)
   int strips1;       // vocabulary strips of the single sweep
   size_t o_ref_t2, o_delta, o_invz;
   int strips, ksplit;
@@ -1218,11 +1222,8 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   if (strips > vt_total) strips = vt_total;
   if (strips > kMaxStrips) strips = kMaxStrips;
   L.strips = strips;
-  // direct-to-LDS staging uses 32-bit byte offsets from each operand's base and a
-  // pipeline of at least two k-steps per head
-  const int64_t maxH = p->H_s > p->H_t ? p->H_s : p->H_t;
-  L.use_dma = !getenv("ADWIN_NO_DMA") && p->T * maxH * 2 < (int64_t(1) << 32) &&
-              (int64_t)p->V * maxH * 2 < (int64_t(1) << 32) && p->H_s >= 2 * kBK && p->H_t >= 2 * kBK;
+  // the direct-to-LDS logit kernel pipelines at least two k-steps per head
+  L.use_dma = !getenv("ADWIN_NO_DMA") && p->H_s >= 2 * kBK && p->H_t >= 2 * kBK;
   L.single = L.use_dma && !getenv("ADWIN_TWO_SWEEP");
   int strips1 = env_int("ADWIN_STRIPS2", 32);
   if (strips1 > vt_total) strips1 = vt_total;
@@ -1271,6 +1272,10 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_klr = take(sizeof(float) * (size_t)n_pad);
   L.o_rownorm = take(sizeof(float) * (size_t)n_pad);
   L.o_WsT = take(2 * (size_t)h_tiles * kGradTile * (size_t)L.Vp);
+  L.o_wt_img = take(L.use_dma ? 2 * (size_t)L.Vp * (size_t)p->H_t : 0);
+  L.o_ws_img = take(L.use_dma ? 2 * (size_t)L.Vp * (size_t)p->H_s : 0);
+  L.o_ht_img = take(L.use_dma ? 2 * (size_t)n_pad * (size_t)p->H_t : 0);
+  L.o_hs_img = take(L.use_dma ? 2 * (size_t)n_pad * (size_t)p->H_s : 0);
   L.o_slab = take(2 * (size_t)halves * (size_t)slab * (size_t)L.Vp);
   L.o_g = take(sizeof(float) * (size_t)ks * (size_t)halves * (size_t)n_pad * (size_t)p->H_s);
   const size_t nch = (size_t)(hp.n_chunks > 0 ? hp.n_chunks : 1);
@@ -1427,6 +1432,25 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
       ADWIN_HIP_TRY(hipGetLastError());
     }
     const bool use_dma = L.use_dma;
+    if (use_dma) {
+      // tile images of the logit operands: vocabulary tiles of 128 rows (zero beyond V),
+      // token tiles of 256 computed rows gathered through row_idx
+      RowImageArgs ia;
+      ia.row_idx = nullptr; ia.n_rows = p->V; ia.th = kTileVocab;
+      ia.src = (const uint4*)p->W_t; ia.img = (uint4*)(ws + L.o_wt_img); ia.H = p->H_t; ia.nk = p->H_t / kBK;
+      row_image_kernel<<<dim3((unsigned)ia.nk, (unsigned)vt_total), 256, 0, stream>>>(ia);
+      ADWIN_HIP_TRY(hipGetLastError());
+      ia.src = (const uint4*)p->W_s; ia.img = (uint4*)(ws + L.o_ws_img); ia.H = p->H_s; ia.nk = p->H_s / kBK;
+      row_image_kernel<<<dim3((unsigned)ia.nk, (unsigned)vt_total), 256, 0, stream>>>(ia);
+      ADWIN_HIP_TRY(hipGetLastError());
+      ia.row_idx = pl.row_idx; ia.n_rows = n_pad; ia.th = kTileTokens;
+      ia.src = (const uint4*)p->h_t; ia.img = (uint4*)(ws + L.o_ht_img); ia.H = p->H_t; ia.nk = p->H_t / kBK;
+      row_image_kernel<<<dim3((unsigned)ia.nk, (unsigned)n_tiles), 256, 0, stream>>>(ia);
+      ADWIN_HIP_TRY(hipGetLastError());
+      ia.src = (const uint4*)p->h_s; ia.img = (uint4*)(ws + L.o_hs_img); ia.H = p->H_s; ia.nk = p->H_s / kBK;
+      row_image_kernel<<<dim3((unsigned)ia.nk, (unsigned)n_tiles), 256, 0, stream>>>(ia);
+      ADWIN_HIP_TRY(hipGetLastError());
+    }
     LogitPassArgs la;
     la.h_s = (const __bf16*)p->h_s; la.h_t = (const __bf16*)p->h_t;
     la.W_s = (const __bf16*)p->W_s; la.W_t = (const __bf16*)p->W_t;
@@ -1439,6 +1463,8 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     la.ref_s2 = (const float*)(ws + L.o_lse2); la.ref_t2 = (const float*)(ws + L.o_ref_t2);
     la.mu0 = (const float*)(ws + L.o_mu); la.e2_off = 0;
     la.tg = env_int("ADWIN_TG", 4);
+    la.Wt_img = (const char*)(ws + L.o_wt_img); la.Ws_img = (const char*)(ws + L.o_ws_img);
+    la.ht_img = (const char*)(ws + L.o_ht_img); la.hs_img = (const char*)(ws + L.o_hs_img);
     MergeArgs m;
     m.part = la.part; m.strips = L.strips; m.n_pad = n_pad; m.n_rows = hp.n_rows;
     m.row_idx = pl.row_idx;
