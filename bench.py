@@ -108,6 +108,9 @@ def main() -> int:
     ap.add_argument("--cpu-rows", type=int, default=-1,
                     help="rows of the oracle sample (0 = skip; default: about 15 s of host work)")
     ap.add_argument("--dh-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--estimator", default="expected", choices=["expected", "sampled"],
+                    help="expected: gradient of the full-vocabulary KL (default, the metric's path); "
+                         "sampled: Eq. 4 on the sampled token (one gradient contraction)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
@@ -126,17 +129,19 @@ def main() -> int:
     n_adm = int(n.sum())
     logits = w.name == "logits_given"
 
+    est = B.ADWIN_EST_SAMPLED if args.estimator == "sampled" else B.ADWIN_EST_EXPECTED
     if logits:
         prob = synth.logits_problem(w, dev)
         call = B.LogitsCall(prob["z_s"], prob["z_t"], prob["ids"], w.offsets, w.window,
-                            reduction=B.ADWIN_RED_SEQ_MEAN)
+                            reduction=B.ADWIN_RED_SEQ_MEAN, estimator=est)
         profile = B.adwin_opd_from_logits_profile
         tokens = n_adm
     else:
         prob = synth.hidden_problem(w, dev)
         call = B.FusedCall(prob["h_s"], prob["h_t"], prob["W_s"], prob["W_t"], prob["ids"],
                            w.offsets, w.window, mode=w.mode, reduction=B.ADWIN_RED_SEQ_MEAN,
-                           dh_dtype=B.ADWIN_DT_BF16 if args.dh_dtype == "bf16" else B.ADWIN_DT_F32)
+                           dh_dtype=B.ADWIN_DT_BF16 if args.dh_dtype == "bf16" else B.ADWIN_DT_F32,
+                           estimator=est)
         profile = B.adwin_opd_fused_profile
         tokens = w.T if w.mode == synth.MODE_PREFIX_AND_FULL else n_adm
     torch.cuda.synchronize()
@@ -188,6 +193,8 @@ def main() -> int:
         # two sweeps = logits twice + one gradient contraction
         f_exec = 2.0 * V * ((3 * Hs + Ht) if single else (3 * Hs + 2 * Ht)) * tokens
         f_grad = 2.0 * V * Hs * tokens * (2 if single else 1)
+        if args.estimator == "sampled":                     # one factor, one contraction
+            f_exec, f_grad = f_alg, 2.0 * V * Hs * tokens
         t_s = ms_per_step * 1e-3
         extra = {"roofline_call": {
             "scheme": "single_sweep" if single else "two_sweeps",
@@ -212,7 +219,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "rollouts": w.B, "packed_rows": w.T, "computed_rows": tokens,
                    "V": w.V, "H_s": w.H_s, "H_t": w.H_t,
-                   "mode": "prefix_and_full" if w.mode else "prefix_only"},
+                   "mode": "prefix_and_full" if w.mode else "prefix_only", "estimator": args.estimator},
         "roofline": roofline, "cpu_baseline": cpu, "phase_ms": ph,
     }
     line["ceilings"] = {"copy_GBps": B.adwin_opd_ceiling_copy(), "mfma_bf16_TFLOPs": B.adwin_opd_ceiling_mfma(),

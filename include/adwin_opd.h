@@ -62,6 +62,16 @@ extern "C" {
 #define ADWIN_RED_SUM          1  /* alpha = 1                                                 */
 #define ADWIN_RED_TOKEN_MEAN   2  /* alpha^p = 1/N_adm,      alpha^f = 1/T                     */
 
+/* estimator: which per-token gradient dh / dz carries
+ *   EXPECTED  p_s (Delta - KL_t): the gradient of the full-vocabulary KL_t, i.e. Eq. 4's
+ *             per-token term in expectation over y_t ~ p_s (default)
+ *   SAMPLED   c_t (e_{y_t} - p_s): Eq. 4's per-token term itself on the sampled token, c_t held
+ *             constant; needs ids (rows with an id outside [0, V) get a zero gradient).  On
+ *             the fused path it needs one gradient contraction instead of two.
+ * KL_t, c_t, the window losses and every other output are the same under both. */
+#define ADWIN_EST_EXPECTED  0
+#define ADWIN_EST_SAMPLED   1
+
 /* dh_dtype */
 #define ADWIN_DT_BF16  0
 #define ADWIN_DT_F32   1
@@ -124,6 +134,7 @@ typedef struct adwin_opd_problem {
   float* t_entropy;          /* [T] H[p_t] in nats; the branching factor is exp(H)              */
   int32_t* t_rank;           /* [T] 1 + number of entries the teacher ranks strictly above y_t  */
                              /*     (needs ids; 0 for an id outside [0, V))                     */
+  int32_t estimator;         /* ADWIN_EST_EXPECTED | ADWIN_EST_SAMPLED                          */
 } adwin_opd_problem;
 
 /*
@@ -155,6 +166,7 @@ typedef struct adwin_opd_logits_problem {
   float* t_logp;             /* [T]                                                            */
   float* t_entropy;          /* [T]                                                            */
   int32_t* t_rank;           /* [T]                                                            */
+  int32_t estimator;         /* ADWIN_EST_EXPECTED | ADWIN_EST_SAMPLED: what dz carries         */
 } adwin_opd_logits_problem;
 
 /* Library version: major*10000 + minor*100 + patch.  Pure host. */

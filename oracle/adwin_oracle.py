@@ -47,6 +47,9 @@ RED_TOKEN_MEAN = 2
 MODE_PREFIX_ONLY = 0
 MODE_PREFIX_AND_FULL = 1
 
+EST_EXPECTED = 0     # gradient of the full-vocabulary KL_t = expectation of Eq. 4 over y_t ~ p_s
+EST_SAMPLED = 1      # Eq. 4 itself, on the sampled token y_t
+
 RHO_STAR = np.sqrt(2.0) / 2.0          # Eq. 10
 CANDIDATE_WINDOWS = (64, 128, 256, 512, 1024, 2048)   # training details, Sec. 5.1
 
@@ -114,17 +117,27 @@ def token_dz(z_s, z_t):
     return p * (delta - np.sum(p * delta))
 
 
-def token_terms(h_s, h_t, W_s, W_t, y=None):
+def token_dz_sampled(z_s, z_t, y):
+    """The per-token term of the gamma = 0 estimator (Eq. 4) in logit space:
+    c_t * d log p_s(y_t) / d z_s = c_t (e_{y_t} - p_s), with c_t held constant."""
+    p = np.exp(log_softmax(z_s))
+    e_y = np.zeros_like(p)
+    e_y[y] = 1.0
+    return token_cost(z_s, z_t, y) * (e_y - p)
+
+
+def token_terms(h_s, h_t, W_s, W_t, y=None, estimator=EST_EXPECTED):
     """Logits from hidden states, then KL_t, c_t and g_t = dz_t W_s for one row."""
     z_s = W_s @ h_s
     z_t = W_t @ h_t
     kl = token_kl(z_s, z_t)
     c = token_cost(z_s, z_t, y) if y is not None else 0.0
-    g = token_dz(z_s, z_t) @ W_s
+    dz = token_dz(z_s, z_t) if estimator == EST_EXPECTED else token_dz_sampled(z_s, z_t, y)
+    g = dz @ W_s
     return kl, c, g
 
 
-def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16):
+def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED):
     """`token_terms` for a stack of independent rows.  Rows are batched through one
     matrix product per block only to let BLAS do the inner products; each row's
     softmax/KL/gradient is the single-row definition above."""
@@ -142,7 +155,10 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16):
             kl[r] = token_kl(z_s, z_t)
             if ids is not None:
                 c[r] = token_cost(z_s, z_t, int(ids[r]))
-            D[r - r0] = token_dz(z_s, z_t)
+            if estimator == EST_EXPECTED:
+                D[r - r0] = token_dz(z_s, z_t)
+            else:
+                D[r - r0] = token_dz_sampled(z_s, z_t, int(ids[r]))
         g[r0:r1] = D @ W_s
     return kl, c, g
 
@@ -238,7 +254,7 @@ def window_outputs(kl, g, offsets, window, reduction=RED_SEQ_MEAN, grad_scale=1.
 
 
 def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
-              grad_scale=1.0, mode=MODE_PREFIX_ONLY):
+              grad_scale=1.0, mode=MODE_PREFIX_ONLY, estimator=EST_EXPECTED):
     """Whole path from hidden states (fp64 arrays holding the bf16-exact inputs)."""
     p = plan(offsets, window)
     T = int(offsets[-1])
@@ -249,7 +265,7 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
     kl, c, g = np.zeros(T), np.zeros(T), np.zeros((T, W_s.shape[1]))
     if len(rows):
         k_, c_, g_ = rows_terms(h_s[rows], h_t[rows], W_s, W_t,
-                                None if ids is None else np.asarray(ids)[rows])
+                                None if ids is None else np.asarray(ids)[rows], estimator=estimator)
         kl[rows], c[rows], g[rows] = k_, c_, g_
     out = window_outputs(kl, g, offsets, window, reduction, grad_scale, mode)
     out.update(kl=kl, c=c, g=g, rows=rows)
@@ -257,7 +273,7 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
 
 
 def supervise_from_logits(z_s, z_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
-                          grad_scale=1.0):
+                          grad_scale=1.0, estimator=EST_EXPECTED):
     """Logits-given variant: per-token KL and c on admitted rows, the loss gradient
     with respect to the student logits dz[t] = grad_scale * alpha^p_i * p_s (Delta-KL),
     and the prefix-window losses.  Rows outside the windows are zero."""
@@ -272,7 +288,10 @@ def supervise_from_logits(z_s, z_t, ids, offsets, window, reduction=RED_SEQ_MEAN
         kl[t] = token_kl(z_s[t], z_t[t])
         if ids is not None:
             c[t] = token_cost(z_s[t], z_t[t], int(ids[t]))
-        dz[t] = grad_scale * ap[i] * token_dz(z_s[t], z_t[t])
+        if estimator == EST_EXPECTED:
+            dz[t] = grad_scale * ap[i] * token_dz(z_s[t], z_t[t])
+        else:
+            dz[t] = grad_scale * ap[i] * token_dz_sampled(z_s[t], z_t[t], int(ids[t]))
         loss_p[i] += kl[t] / n[i]
         Lp += ap[i] * kl[t]
     batch = np.zeros(8)

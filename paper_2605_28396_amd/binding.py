@@ -25,6 +25,7 @@ ADWIN_RED_SEQ_MEAN, ADWIN_RED_SUM, ADWIN_RED_TOKEN_MEAN = 0, 1, 2
 ADWIN_DT_BF16, ADWIN_DT_F32 = 0, 1
 ADWIN_DEV_BAD_ID, ADWIN_DEV_NONFINITE = 1, 2
 ADWIN_MAX_CANDIDATES = 16
+ADWIN_EST_EXPECTED, ADWIN_EST_SAMPLED = 0, 1
 
 
 class adwin_opd_problem(C.Structure):
@@ -43,6 +44,7 @@ class adwin_opd_problem(C.Structure):
         ("candidates", C.c_void_p), ("n_candidates", C.c_int32),
         ("cand_rho_pooled", C.c_void_p), ("cand_rho_field", C.c_void_p), ("cand_batch", C.c_void_p),
         ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
+        ("estimator", C.c_int32),
     ]
 
 
@@ -56,6 +58,7 @@ class adwin_opd_logits_problem(C.Structure):
         ("loss_prefix", C.c_void_p), ("batch", C.c_void_p),
         ("n_out", C.c_void_p), ("n_adm_out", C.c_void_p), ("status_dev", C.c_void_p),
         ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
+        ("estimator", C.c_int32),
     ]
 
 
@@ -206,7 +209,7 @@ class FusedCall:
                  reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0, dh_dtype=ADWIN_DT_F32,
                  want=("kl", "c", "dh_prefix", "dh_full", "loss_prefix", "loss_full", "rho_pooled",
                        "rho_field", "batch", "n_out", "n_adm_out", "status_dev"),
-                 device=None, allocate=True, candidates=None):
+                 device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.candidates = None if candidates is None else _host_i32(candidates)
         self.inputs = (h_s, h_t, W_s, W_t, ids)
@@ -222,6 +225,7 @@ class FusedCall:
         p.offsets, p.window = self.offsets.ctypes.data, self.window.ctypes.data
         p.h_s, p.h_t, p.W_s, p.W_t, p.ids = _ptr(h_s), _ptr(h_t), _ptr(W_s), _ptr(W_t), _ptr(ids)
         p.mode, p.reduction, p.grad_scale, p.dh_dtype = mode, reduction, float(grad_scale), dh_dtype
+        p.estimator = estimator
         K = 0 if self.candidates is None else int(self.candidates.shape[0])
         if K:
             p.candidates, p.n_candidates = self.candidates.ctypes.data, K
@@ -303,7 +307,7 @@ class LogitsCall:
 
     def __init__(self, z_s, z_t, ids, offsets, window, reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0,
                  want=("kl", "c", "dz", "loss_prefix", "batch", "n_out", "n_adm_out", "status_dev"),
-                 allocate=True):
+                 allocate=True, estimator=ADWIN_EST_EXPECTED):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.inputs = (z_s, z_t, ids)
         B = int(self.window.shape[0])
@@ -315,6 +319,7 @@ class LogitsCall:
         p.offsets, p.window = self.offsets.ctypes.data, self.window.ctypes.data
         p.z_s, p.z_t, p.ids = _ptr(z_s), _ptr(z_t), _ptr(ids)
         p.reduction, p.grad_scale = reduction, float(grad_scale)
+        p.estimator = estimator
         self.p = p
         self.out = {}
         self.workspace = None

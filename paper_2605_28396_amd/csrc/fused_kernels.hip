@@ -149,6 +149,8 @@ constexpr int kModeStats = 0;   // online (running-max) statistics only
 constexpr int kModeDz = 1;      // second sweep of the two-sweep scheme: dz tiles
 constexpr int kModeSingle = 2;  // single sweep: fixed-reference statistics + E1/E2 tiles
 constexpr int kModeSingleDiag = 3;  // the same plus the teacher-side diagnostics of Sec. 3.1
+constexpr int kModeSingleE2 = 4;      // single sweep that emits only the E2 factor (sampled estimator)
+constexpr int kModeSingleE2Diag = 5;  // the same plus the diagnostics
 
 // Running per-token statistics held by one lane for its two token columns.
 struct LaneStats { float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2]; };
@@ -234,7 +236,7 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
 // only maintained in diagnostics mode.
 struct LaneSums { float Z_s[2], A_s[2], Z_t[2], B_t[2]; int cnt[2]; };
 
-template <bool TAIL, bool DIAG>
+template <bool TAIL, bool DIAG, bool WRITE_E1>
 __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                 LaneSums& sm, const float (&rs2)[2],
                                                 const float (&rt2)[2], const float (&mu0)[2],
@@ -275,7 +277,7 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
         o1.x = pack_bf16(e1[0], e1[1]); o1.y = pack_bf16(e1[2], e1[3]);
         o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
         const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
-        *(uint2*)(out + at) = o1;
+        if (WRITE_E1) *(uint2*)(out + at) = o1;
         *(uint2*)(out + e2_off + at) = o2;
       }
     sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
@@ -559,8 +561,9 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 
   LaneStats st;
   LaneSums sm;
-  constexpr bool kDiag = MODE == kModeSingleDiag;
-  constexpr bool kSingle = MODE == kModeSingle || kDiag;
+  constexpr bool kDiag = MODE == kModeSingleDiag || MODE == kModeSingleE2Diag;
+  constexpr bool kE1 = MODE == kModeSingle || MODE == kModeSingleDiag;
+  constexpr bool kSingle = MODE >= kModeSingle;
   float lse2[2], mu[2], rs2[2], rt2[2];   // per-row inputs of the dz / single-sweep epilogues
   float zyt[2];
   int yid[2];
@@ -668,9 +671,9 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       if (MODE == kModeDz) {
         dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
       } else if (tail) {
-        single_epilogue<true, kDiag>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
+        single_epilogue<true, kDiag, kE1>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
       } else {
-        single_epilogue<false, kDiag>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
+        single_epilogue<false, kDiag, kE1>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
       }
     }
   }
@@ -695,6 +698,7 @@ struct MergeArgs {
   // sum e_t z_t and the rank count when `diag` is set
   int diag;
   float* t_logp; float* t_entropy; int32_t* t_rank;
+  float* cr;     // [n_pad] c_t per computed row, for the sampled estimator (else NULL)
 };
 
 __device__ __forceinline__ float dot_bf16_row(const __bf16* x, const __bf16* y, int H, int lane) {
@@ -804,7 +808,7 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
   float c = 0.f, logp_t = 0.f;
   bool have_y = false;
   uint32_t flag = 0;
-  if (a.ids && (a.c || a.t_logp || a.t_rank)) {
+  if (a.ids && (a.c || a.t_logp || a.t_rank || a.cr)) {
     const int y = a.ids[t];
     if (y >= 0 && y < a.V) {
       const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
@@ -827,6 +831,7 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
     // H[p_t] = lse_t - E_{p_t}[z_t]; both sums are relative to the same reference
     if (a.t_entropy) a.t_entropy[t] = lse_t - Bt / Zt;
     if (a.t_rank) a.t_rank[t] = have_y ? (int32_t)cnt + 1 : 0;
+    if (a.cr) a.cr[r] = c;
   }
 }
 
@@ -1085,6 +1090,8 @@ struct FinalizeArgs {
   float* g; int ksplit; int64_t n_pad; int H;
   int64_t g_rows;                          // rows per k-split plane of g
   const float* delta; const float* inv_z;  // single-sweep mode: g = (G1 - delta G2) inv_z, else NULL
+  // sampled estimator (Eq. 4): g = c_t (W_s[y_t] - G2 inv_z); cr NULL selects the expected one
+  const float* cr; const int32_t* ids; const __bf16* W_s; int V;
   float grad_scale; int dh_bf16;
   void* dh_prefix; void* dh_full;
   float* rownorm;
@@ -1120,6 +1127,34 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a) {
   const float sf = a.grad_scale * a.pl.alpha_f[i];
   float nrm = 0.f;
   const float dl = a.delta ? a.delta[r] : 0.f, iz = a.inv_z ? a.inv_z[r] : 1.f;
+  if (a.cr) {
+    const float c = a.cr[r];
+    const int y = a.ids[t];
+    const bool ok = y >= 0 && y < a.V;            // c is 0 otherwise
+    const uint2* wy = (const uint2*)(a.W_s + (int64_t)(ok ? y : 0) * a.H);
+    for (int h = lane * 4; h < a.H; h += 256) {
+      float4 g2 = *(const float4*)(a.g + (a.n_pad + r) * a.H + h);
+      for (int s = 1; s < a.ksplit; ++s) {
+        const float4 q = *(const float4*)(a.g + ((int64_t)s * a.g_rows + a.n_pad + r) * a.H + h);
+        g2.x += q.x; g2.y += q.y; g2.z += q.z; g2.w += q.w;
+      }
+      const uint2 w = wy[h >> 2];
+      float4 g;
+      g.x = c * (bf16_lo(w.x) - g2.x * iz); g.y = c * (bf16_hi(w.x) - g2.y * iz);
+      g.z = c * (bf16_lo(w.y) - g2.z * iz); g.w = c * (bf16_hi(w.y) - g2.w * iz);
+      *(float4*)(a.g + r * a.H + h) = g;
+      nrm = fmaf(g.x, g.x, fmaf(g.y, g.y, fmaf(g.z, g.z, fmaf(g.w, g.w, nrm))));
+      const float4 p = {g.x * sp, g.y * sp, g.z * sp, g.w * sp};
+      store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, p);
+      if (a.probe) {
+        const float4 f = {g.x * sf, g.y * sf, g.z * sf, g.w * sf};
+        store_dh(a.dh_full, a.dh_bf16, t, a.H, h, f);
+      }
+    }
+    nrm = wave_sum(nrm);
+    if (lane == 0) a.rownorm[r] = nrm;
+    return;
+  }
   for (int h = lane * 4; h < a.H; h += 256) {
     float4 g = *(const float4*)(a.g + r * a.H + h);
     for (int s = 1; s < a.ksplit; ++s) {
@@ -1203,7 +1238,7 @@ struct FusedLayout {
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_zy_t, o_yid, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, total;
 };
 
 static int env_int(const char* name, int dflt) {
@@ -1230,6 +1265,8 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   if (strips1 > kMaxStrips) strips1 = kMaxStrips;
   L.strips1 = strips1;
   const int halves = L.single ? 2 : 1;     // the single sweep stores two factors per logit
+  // ... of which the sampled estimator contracts only the second
+  const int gemm_halves = (L.single && p->estimator == ADWIN_EST_SAMPLED) ? 1 : halves;
   const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
   // Rows per slab: a multiple of 8 token tiles (whole rounds of the sweep's workgroups on
   // 256 compute units) between 4,096 and 16,384, chosen so that the gradient GEMM's
@@ -1244,14 +1281,14 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
       int64_t rounds = 0;
       for (int64_t r0 = 0; r0 < n_pad; r0 += r) {
         const int64_t rows = n_pad - r0 < r ? n_pad - r0 : r;
-        rounds += (halves * (rows / kGradTile) * h_tiles + 255) / 256;
+        rounds += (gemm_halves * (rows / kGradTile) * h_tiles + 255) / 256;
       }
       if (best_rounds < 0 || rounds < best_rounds) { best_rounds = rounds; slab = r; }
     }
   }
   if (slab > n_pad) slab = n_pad;
   L.slab_rows = slab;
-  const int64_t tiles = halves * (slab / kGradTile) * h_tiles;
+  const int64_t tiles = gemm_halves * (slab / kGradTile) * h_tiles;
   int ks = (int)(256 / (tiles > 0 ? tiles : 1));
   const int nk = (int)(L.Vp / kBK);
   if (ks > 16) ks = 16;
@@ -1289,6 +1326,7 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_uc = take(sizeof(float) * kc * (size_t)p->B * (size_t)p->H_s);
   L.o_cacc = take(sizeof(double) * 4 * kc * (size_t)p->B);
   L.o_cS = take(sizeof(double) * kc * (size_t)p->B);
+  L.o_cr = take(sizeof(float) * (size_t)n_pad);
   L.o_zy_t = take(sizeof(float) * (size_t)n_pad);
   L.o_yid = take(sizeof(int32_t) * (size_t)n_pad);
   L.total = o;
@@ -1309,6 +1347,7 @@ static int check_problem(const adwin_opd_problem* p) {
   if (p->mode != ADWIN_PREFIX_ONLY && p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
   if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
   if (p->dh_dtype != ADWIN_DT_BF16 && p->dh_dtype != ADWIN_DT_F32) return ADWIN_E_MODE;
+  if (p->estimator != ADWIN_EST_EXPECTED && p->estimator != ADWIN_EST_SAMPLED) return ADWIN_E_MODE;
   if (p->n_candidates < 0 || p->n_candidates > ADWIN_MAX_CANDIDATES) return ADWIN_E_SHAPE;
   if (p->candidates && p->n_candidates > 0) {
     if (p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
@@ -1338,6 +1377,12 @@ static hipError_t ensure_lds_opt_in() {
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingleDiag>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingleE2>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingleE2Diag>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)grad_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1390,6 +1435,11 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   FusedLayout L = fused_layout(p, hp);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total)
     return ADWIN_E_WORKSPACE;
+  const bool diag = p->t_entropy || p->t_rank;          // need the diagnostics sweep
+  const bool sampled = p->estimator == ADWIN_EST_SAMPLED;
+  // the diagnostics and the sampled estimator ride on the single-sweep kernels
+  if ((diag || p->t_logp || sampled) && !L.single) return ADWIN_E_MODE;
+  if (sampled && !p->ids) return ADWIN_E_NULL;
   hipStream_t stream = (hipStream_t)hip_stream;
   unsigned char* ws = (unsigned char*)workspace;
   ADWIN_HIP_TRY(ensure_lds_opt_in());
@@ -1407,8 +1457,6 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   const int64_t n_pad = hp.n_pad;
 
   ADWIN_HIP_TRY(launch_fill_u32(p->status_dev, 1, 0u, stream));
-  const bool diag = p->t_entropy || p->t_rank;          // need the diagnostics sweep
-  if ((diag || p->t_logp) && !L.single) return ADWIN_E_MODE;
   if (!probe) {   // rows outside the windows report zero KL, cost and diagnostics
     ADWIN_HIP_TRY(launch_fill_f32(p->kl, p->T, 0.f, stream));
     ADWIN_HIP_TRY(launch_fill_f32(p->c, p->T, 0.f, stream));
@@ -1473,6 +1521,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     m.lse2 = (float*)(ws + L.o_lse2); m.mu = (float*)(ws + L.o_mu); m.klr = klr;
     m.kl = p->kl; m.c = p->c; m.status = p->status_dev;
     m.diag = diag ? 1 : 0; m.t_logp = p->t_logp; m.t_entropy = p->t_entropy; m.t_rank = p->t_rank;
+    m.cr = sampled ? (float*)(ws + L.o_cr) : nullptr;
     GradArgs ga;
     ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.nk_total = (int)(L.Vp / kBK);
     ga.g = gws; ga.H = p->H_s; ga.h_tiles = h_tiles; ga.ksplit = L.ksplit;
@@ -1504,14 +1553,20 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         la.e2_off = rows * L.Vp;
         const int groups = (la.n_tiles + la.tg - 1) / la.tg;
         phase(ADWIN_PHASE_STATS);
-        if (diag)
-          logit_pass_dma_kernel<kModeSingleDiag><<<(unsigned)(groups * la.tg * L.strips1), 256, kDmaLds, stream>>>(la);
-        else
-          logit_pass_dma_kernel<kModeSingle><<<(unsigned)(groups * la.tg * L.strips1), 256, kDmaLds, stream>>>(la);
+        const unsigned sweep_grid = (unsigned)(groups * la.tg * L.strips1);
+        if (sampled && diag) logit_pass_dma_kernel<kModeSingleE2Diag><<<sweep_grid, 256, kDmaLds, stream>>>(la);
+        else if (sampled) logit_pass_dma_kernel<kModeSingleE2><<<sweep_grid, 256, kDmaLds, stream>>>(la);
+        else if (diag) logit_pass_dma_kernel<kModeSingleDiag><<<sweep_grid, 256, kDmaLds, stream>>>(la);
+        else logit_pass_dma_kernel<kModeSingle><<<sweep_grid, 256, kDmaLds, stream>>>(la);
         ADWIN_HIP_TRY(hipGetLastError());
         phase(ADWIN_PHASE_GRAD);
         ga.slab_row0 = r0;
-        ga.half_tiles = (int)(rows / kGradTile); ga.row_tiles = 2 * ga.half_tiles;
+        if (sampled) {       // only the E2 half of the slab, into the second half of g
+          ga.slab = la.slab + la.e2_off;
+          ga.half_tiles = 0; ga.row_tiles = (int)(rows / kGradTile);
+        } else {
+          ga.half_tiles = (int)(rows / kGradTile); ga.row_tiles = 2 * ga.half_tiles;
+        }
         launch_grad(ga, L, stream);
         ADWIN_HIP_TRY(hipGetLastError());
       }
@@ -1568,6 +1623,8 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     f.g_rows = L.single ? 2 * n_pad : n_pad;
     f.delta = L.single ? (const float*)(ws + L.o_delta) : nullptr;
     f.inv_z = L.single ? (const float*)(ws + L.o_invz) : nullptr;
+    f.cr = (L.single && p->estimator == ADWIN_EST_SAMPLED) ? (const float*)(ws + L.o_cr) : nullptr;
+    f.ids = p->ids; f.W_s = (const __bf16*)p->W_s; f.V = p->V;
     f.grad_scale = p->grad_scale; f.dh_bf16 = p->dh_dtype == ADWIN_DT_BF16;
     f.dh_prefix = p->dh_prefix; f.dh_full = p->dh_full; f.rownorm = rownorm;
     finalize_kernel<<<(unsigned)((p->T + 3) / 4), 256, 0, stream>>>(f);

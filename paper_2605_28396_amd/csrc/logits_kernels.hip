@@ -26,7 +26,15 @@ struct LogitsArgs {
   uint32_t* status;
   // teacher-side diagnostics (Sec. 3.1), each may be NULL
   float* t_logp; float* t_entropy; int32_t* t_rank;
+  int sampled;         // dz = scale c_t (e_y - p_s) (Eq. 4 on the sampled token) instead of scale p_s (Delta - KL_t)
 };
+
+// The one-hot part of the sampled estimator: dz[y] = k (1 - p_s(y)), k = scale c_t, written
+// over the -k p_s(y) the vector sweep stored there.
+__device__ __forceinline__ void store_onehot(uint4* dzr, int y, float k, float zy_s, float lse_s) {
+  const float v = k * (1.f - __expf(zy_s - lse_s));
+  ((uint16_t*)dzr)[y] = (uint16_t)(pack_bf16(v, 0.f) & 0xffffu);
+}
 
 __device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
   f[0] = bf16_lo(q.x); f[1] = bf16_hi(q.x);
@@ -168,12 +176,15 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
     a.klr[a.pl.comp_off[i] + j] = kl;
     bc[0] = lse_s * kLog2e;
     bc[1] = mu;
+    bc[2] = c;
+    bc[3] = lse_s;
   }
   __syncthreads();
   if (!dzr) return;
-  // ---- sweep 2: dz = scale * p_s * ((z_s - z_t) - mu) --------------------------------
-  const float lse2 = bc[0], mu = bc[1];
+  // ---- sweep 2: dz = scale * p_s * ((z_s - z_t) - mu), or scale * c_t * (e_y - p_s) ---
+  const float lse2 = bc[0];
   const float scale = a.grad_scale * a.pl.alpha_p[i];
+  const float ca = a.sampled ? 0.f : 1.f, cb = a.sampled ? -bc[2] : -bc[1];
   for (int q = tid; q < nvec; q += kRowThreads) {
     const uint4 qs = zs[q], qt = zt[q];
     float s[8], u[8], d[8];
@@ -181,13 +192,21 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
     unpack8(qt, u);
 #pragma unroll
     for (int k = 0; k < 8; ++k)
-      d[k] = scale * fast_exp2(fmaf(s[k], kLog2e, -lse2)) * ((s[k] - u[k]) - mu);
+      d[k] = scale * fast_exp2(fmaf(s[k], kLog2e, -lse2)) * fmaf(s[k] - u[k], ca, cb);
     uint4 o;
     o.x = pack_bf16(d[0], d[1]);
     o.y = pack_bf16(d[2], d[3]);
     o.z = pack_bf16(d[4], d[5]);
     o.w = pack_bf16(d[6], d[7]);
     nt_store16(dzr + q, o);
+  }
+  if (a.sampled) {
+    __syncthreads();
+    if (tid == 0 && a.ids) {
+      const int yy = a.ids[t];
+      if (yy >= 0 && yy < a.V)
+        store_onehot(dzr, yy, scale * bc[2], __uint_as_float((uint32_t)((const uint16_t*)zs)[yy] << 16), bc[3]);
+    }
   }
 }
 
@@ -363,13 +382,19 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
     a.klr[a.pl.comp_off[i] + j] = kl;
     sh[20] = lse_s * kLog2e;
     sh[21] = mu;
+    sh[22] = c;
+    sh[23] = lse_s;
   }
   __syncthreads();
   if (!dzr) return;
   // ---- sweep 2: dz from the resident copy ----------------------------------------------
+  // expected: scale p_s ((z_s - z_t) - mu); sampled: -k p_s with k = scale c_t (the one-hot
+  // term follows); |scale| resp. |k| is folded into the exponent, the sign into the factor
   const float scale = a.grad_scale * a.pl.alpha_p[i];
-  const float sgn = scale < 0.f ? -1.f : 1.f;
-  const float lse2 = sh[20] - log2f(fabsf(scale)), nmu = -sgn * sh[21];
+  const float k_s = a.sampled ? scale * sh[22] : scale;
+  const float sg = k_s < 0.f ? -1.f : 1.f;
+  const float sgn = a.sampled ? 0.f : sg;
+  const float lse2 = sh[20] - log2f(fabsf(k_s)), nmu = a.sampled ? -sg : -sg * sh[21];
   static_for<kResIters>([&](auto it_c) {
     constexpr int it = decltype(it_c)::value;
     if (it * kResThreads < nvec) {
@@ -382,6 +407,14 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
   });
   for (int q = kResVec + tid; q < nvec; q += kResThreads)
     nt_store16(dzr + q, dz_vector(zs[q], zt[q], lse2, sgn, nmu));
+  if (a.sampled) {
+    __syncthreads();
+    if (tid == 0 && a.ids) {
+      const int yy = a.ids[t];
+      if (yy >= 0 && yy < a.V)
+        store_onehot(dzr, yy, k_s, __uint_as_float((uint32_t)((const uint16_t*)zs)[yy] << 16), sh[23]);
+    }
+  }
 }
 
 struct LogitsLayout {
@@ -403,6 +436,8 @@ static int check_logits_problem(const adwin_opd_logits_problem* p) {
   if (st != ADWIN_OK) return st;
   if (p->V <= 0 || (p->V & 7)) return ADWIN_E_SHAPE;
   if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
+  if (p->estimator != ADWIN_EST_EXPECTED && p->estimator != ADWIN_EST_SAMPLED) return ADWIN_E_MODE;
+  if (p->estimator == ADWIN_EST_SAMPLED && !p->ids) return ADWIN_E_NULL;
   return ADWIN_OK;
 }
 
@@ -446,6 +481,7 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
     a.grad_scale = p->grad_scale;
     a.kl = p->kl; a.c = p->c; a.dz = (uint4*)p->dz; a.klr = klr; a.status = p->status_dev;
     a.t_logp = p->t_logp; a.t_entropy = p->t_entropy; a.t_rank = p->t_rank;
+    a.sampled = p->estimator == ADWIN_EST_SAMPLED;
     PhaseScope scope(timer, ADWIN_PHASE_STATS);
     static const bool streaming = getenv("ADWIN_LOGITS_STREAMING") != nullptr;
     if (p->t_logp || p->t_entropy || p->t_rank) {

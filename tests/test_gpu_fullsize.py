@@ -29,9 +29,10 @@ def _free():
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name", ["strong_to_weak", "same_family", "probe_alignment"])
-def test_fused_full_size_sampled_rows_and_reductions(B, name):
-    print(f"[case] fused full size {name}", flush=True)
+@pytest.mark.parametrize("name,estimator", [("strong_to_weak", 0), ("same_family", 0),
+                                            ("probe_alignment", 0), ("strong_to_weak", 1)])
+def test_fused_full_size_sampled_rows_and_reductions(B, name, estimator):
+    print(f"[case] fused full size {name} estimator {estimator}", flush=True)
     w = synth.workload(name)
     dev = torch.device("cuda:0")
     p = synth.hidden_problem(w, dev)
@@ -39,7 +40,7 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name):
     cands = list(O.CANDIDATE_WINDOWS) if probe else None
     call = B.FusedCall(p["h_s"], p["h_t"], p["W_s"], p["W_t"], p["ids"], w.offsets, w.window,
                        mode=w.mode, reduction=B.ADWIN_RED_SUM, dh_dtype=B.ADWIN_DT_F32,
-                       candidates=cands)
+                       candidates=cands, estimator=estimator)
     st = call.run()
     assert st == 0, B.adwin_opd_strerror(st)
     torch.cuda.synchronize()
@@ -54,7 +55,7 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name):
     idx = torch.from_numpy(rows).to(dev)
     Ws, Wt = synth.to_f64(p["W_s"]), synth.to_f64(p["W_t"])
     kl, c, g = O.rows_terms(synth.to_f64(p["h_s"][idx]), synth.to_f64(p["h_t"][idx]), Ws, Wt,
-                            p["ids"][idx].cpu().numpy())
+                            p["ids"][idx].cpu().numpy(), estimator=estimator)
     del Ws, Wt
     Hp.assert_kl(out["kl"][idx].cpu().numpy(), kl)
     Hp.assert_cost(out["c"][idx].cpu().numpy(), c)

@@ -251,3 +251,47 @@ def test_teacher_diagnostics_from_logits_exact_rank(B):
         assert abs(got["t_logp"][t] - O.teacher_logp(z, y)) <= 1e-4 * max(1.0, abs(O.teacher_logp(z, y)))
     other = np.setdiff1d(np.arange(w.T), rows)
     assert not got["t_entropy"][other].any() and not got["t_rank"][other].any()
+
+
+@pytest.mark.parametrize("name,reduction", [("tiny", O.RED_SUM), ("tiny_probe", O.RED_SEQ_MEAN),
+                                            ("ragged_small", O.RED_SUM), ("ragged_mid", O.RED_TOKEN_MEAN)])
+def test_sampled_estimator_fused(B, name, reduction):
+    """Eq. 4 on the sampled token, c_t (e_y - p_s), back to the hidden state; every other
+    output as with the expected estimator."""
+    w = synth.workload(name)
+    p = synth.hidden_problem(w)
+    if name.startswith("tiny"):
+        p["ids"] = _sample_ids_from_student(w, p)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=reduction, grad_scale=1.0, mode=w.mode, estimator=O.EST_SAMPLED)
+    got = _run_fused(B, w, p, "cuda", reduction=reduction, grad_scale=1.0, dh_dtype=B.ADWIN_DT_F32,
+                     estimator=B.ADWIN_EST_SAMPLED)
+    _check_fused(w, got, ref, reduction)
+    exp = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=reduction, grad_scale=1.0, mode=w.mode)
+    assert np.abs(ref["dh_prefix"] - exp["dh_prefix"]).max() > 0.1 * np.abs(exp["dh_prefix"]).max()
+
+
+@pytest.mark.parametrize("env", [{}, {"ADWIN_LOGITS_STREAMING": "1"}])
+def test_sampled_estimator_from_logits(B, env, monkeypatch):
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    w = synth.workload("ragged_small")
+    p = synth.logits_problem(w)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise_from_logits(f["z_s"], f["z_t"], f["ids"], w.offsets, w.window,
+                                  reduction=O.RED_SEQ_MEAN, grad_scale=-2.0, estimator=O.EST_SAMPLED)
+    d = {k: v.cuda() for k, v in p.items()}
+    out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window,
+                                  reduction=O.RED_SEQ_MEAN, grad_scale=-2.0, estimator=B.ADWIN_EST_SAMPLED)
+    torch.cuda.synchronize()
+    got = {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
+           for k, v in out.items()}
+    Hp.assert_kl(got["kl"], ref["kl"])
+    Hp.assert_cost(got["c"], ref["c"])
+    Hp.assert_grad(got["dz"], ref["dz"], "dz", Hp.BF16_ULP)
+    rows = O.plan(w.offsets, w.window)["rows"]
+    y = f["ids"][rows]
+    # the one-hot entry carries the sign of c_t * scale, every other entry the opposite one
+    assert np.all(np.sign(got["dz"][rows, y]) == np.sign(-2.0 * ref["c"][rows]))

@@ -149,6 +149,39 @@ def test_dz_is_expected_sampled_token_gradient():
     assert np.allclose(O.token_dz(z_s, z_t), acc, rtol=1e-12, atol=1e-15)
 
 
+def test_sampled_estimator_gradient():
+    # Eq. 4 at one position: c_t held fixed multiplies the score of the sampled token
+    V = 11
+    z_s, z_t = RNG.normal(0, 2, V), RNG.normal(0, 2, V)
+    p = scipy.special.softmax(z_s)
+    for y in (0, 4, V - 1):
+        dz = O.token_dz_sampled(z_s, z_t, y)
+        c = scipy.special.log_softmax(z_s)[y] - scipy.special.log_softmax(z_t)[y]
+        assert abs(dz.sum()) < 1e-12                       # a score: sums to zero
+        eps = 1e-6                                          # finite differences of c * log p_s(y)
+        for v in range(V):
+            e = np.zeros(V); e[v] = eps
+            fd = c * (scipy.special.log_softmax(z_s + e)[y] - scipy.special.log_softmax(z_s - e)[y]) / (2 * eps)
+            assert dz[v] == pytest.approx(fd, rel=1e-6, abs=1e-9)
+    # its expectation over y ~ p_s is the gradient of the full-vocabulary KL
+    acc = sum(p[y] * O.token_dz_sampled(z_s, z_t, y) for y in range(V))
+    assert np.allclose(acc, O.token_dz(z_s, z_t), rtol=1e-12, atol=1e-15)
+    # teacher == student: c_t = 0, no update
+    assert not O.token_dz_sampled(z_s, z_s, 3).any()
+    # through the hidden state: g = dz W_s, and the batched path agrees with the single row
+    Hs, Ht = 5, 4
+    W_s, W_t = RNG.normal(0, 0.7, (V, Hs)), RNG.normal(0, 0.7, (V, Ht))
+    H_s, H_t = RNG.normal(0, 1, (3, Hs)), RNG.normal(0, 1, (3, Ht))
+    ids = np.array([2, 7, 0])
+    _, c, g = O.rows_terms(H_s, H_t, W_s, W_t, ids, estimator=O.EST_SAMPLED)
+    for r in range(3):
+        pr = scipy.special.softmax(W_s @ H_s[r])
+        want = c[r] * (W_s[ids[r]] - pr @ W_s)
+        assert np.allclose(g[r], want, rtol=1e-12, atol=1e-15)
+        assert np.allclose(g[r], O.token_terms(H_s[r], H_t[r], W_s, W_t, int(ids[r]), O.EST_SAMPLED)[2],
+                           rtol=1e-12, atol=1e-15)
+
+
 def test_hidden_gradient_finite_differences_and_layout():
     V, Hs, Ht = 13, 5, 4
     W_s, W_t = RNG.normal(0, 0.7, (V, Hs)), RNG.normal(0, 0.7, (V, Ht))
