@@ -188,19 +188,15 @@ def main() -> int:
                     "alg_flops_per_launch": f_stats}
         f_stats *= launches
         f_alg = 2.0 * V * (2 * Hs + Ht) * tokens            # student fwd + teacher fwd + dz W_s
-        single = ph["dz"] == 0.0                            # single-sweep scheme: no second logit sweep
-        # executed: single sweep = logits once + two gradient factors through W_s;
-        # two sweeps = logits twice + one gradient contraction
-        f_exec = 2.0 * V * ((3 * Hs + Ht) if single else (3 * Hs + 2 * Ht)) * tokens
-        f_grad = 2.0 * V * Hs * tokens * (2 if single else 1)
-        if args.estimator == "sampled":                     # one factor, one contraction
-            f_exec, f_grad = f_alg, 2.0 * V * Hs * tokens
+        # executed = algorithmic on the single-sweep scheme: logits once, one gradient contraction
+        f_exec = f_alg
+        f_grad = 2.0 * V * Hs * tokens
         t_s = ms_per_step * 1e-3
         extra = {"roofline_call": {
-            "scheme": "single_sweep" if single else "two_sweeps",
+            "scheme": "single_sweep",
             "alg_tflops": f_alg / t_s / 1e12, "alg_frac": f_alg / t_s / 1e12 / PEAK_BF16_TFLOPS,
             "exec_tflops": f_exec / t_s / 1e12, "exec_frac": f_exec / t_s / 1e12 / PEAK_BF16_TFLOPS,
-            "dz_pass_tflops": None if single else f_stats / (ph["dz"] * 1e-3) / 1e12,
+            "combine_GBps": None if ph["dz"] == 0.0 else 6.0 * V * tokens / (ph["dz"] * 1e-3) / 1e9,
             "grad_gemm_tflops": f_grad / (ph["grad"] * 1e-3) / 1e12}}
 
     cpu = None

@@ -197,6 +197,7 @@ __device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f
 // 8-entry chunk c at chunk position c ^ ((r >> 1) & 7).  A 256 x 128 logit tile covers the
 // two consecutive blocks 2 vt and 2 vt + 1 of its row tile; `blk` points at the first.
 constexpr int kSlabBlock = kTileTokens * kBK;   // elements per block
+constexpr int kImgBytesSlab = kSlabBlock * 2;   // 32 KiB
 
 // dz = p_s ((z_s - z_t) - mu), rounded to bf16, into rows wrow + fn*32 + lane%32 of the tile.
 __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
@@ -779,13 +780,14 @@ struct MergeSingleArgs {
   MergeArgs m;                 // part: [3][strips][n_pad] sums Z_s, A, Z_t
   const float* ref_s2; const float* ref_t2; const float* mu0;
   float* delta; float* inv_z;
+  int64_t row0, rows;          // computed rows [row0, row0 + rows) of this launch (one slab)
 };
 
 __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
   const MergeArgs& a = b.m;
   const int lane = threadIdx.x & 63;
-  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= a.n_pad) return;
+  const int64_t r = b.row0 + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= b.row0 + b.rows) return;
   const int64_t plane = (int64_t)a.strips * a.n_pad;
   float Zs = 0.f, A = 0.f, Zt = 0.f, Bt = 0.f, cnt = 0.f;
   if (lane < a.strips) {
@@ -893,6 +895,40 @@ __global__ __launch_bounds__(256) void wst_image_kernel(const uint16_t* __restri
     o.x = w[0] | ((uint32_t)w[1] << 16); o.y = w[2] | ((uint32_t)w[3] << 16);
     o.z = w[4] | ((uint32_t)w[5] << 16); o.w = w[6] | ((uint32_t)w[7] << 16);
     *(uint4*)(blk + q * 8) = o;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Combine.  Once a slab's rows have their mu (all strips merged), the two gradient factors
+// collapse into the logit gradient itself, dz = (E1 - (mu - mu0) E2) / Z_s = p_s (d - mu),
+// written over E1 in the same image order, and the gradient GEMM runs on one factor.  A
+// streaming pass: 4 B read + 2 B written per slab element.
+// ---------------------------------------------------------------------------------------
+struct CombineArgs {
+  uint4* slab; int64_t e2_vec;          // E2 lies e2_vec 16-byte vectors after E1
+  const float* delta; const float* inv_z;   // per computed row
+  int64_t row0;                         // computed-row index of slab row 0
+  int nk;                               // k-steps (blocks) per row tile
+};
+
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
+  // one workgroup per block (row tile, kt): 2048 vectors of 8 entries, row = vector / 8
+  const int64_t blk = (int64_t)blockIdx.y * a.nk + blockIdx.x;
+  uint4* p1 = a.slab + blk * (kImgBytesSlab / 16);
+  const uint4* p2 = p1 + a.e2_vec;
+  const int64_t rbase = a.row0 + (int64_t)blockIdx.y * kTileTokens;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int q = i * 256 + threadIdx.x;
+    const int64_t r = rbase + (q >> 3);
+    const float dl = a.delta[r], iz = a.inv_z[r];
+    const uint4 x = p1[q], y = p2[q];
+    uint4 o;
+    o.x = pack_bf16((bf16_lo(x.x) - dl * bf16_lo(y.x)) * iz, (bf16_hi(x.x) - dl * bf16_hi(y.x)) * iz);
+    o.y = pack_bf16((bf16_lo(x.y) - dl * bf16_lo(y.y)) * iz, (bf16_hi(x.y) - dl * bf16_hi(y.y)) * iz);
+    o.z = pack_bf16((bf16_lo(x.z) - dl * bf16_lo(y.z)) * iz, (bf16_hi(x.z) - dl * bf16_hi(y.z)) * iz);
+    o.w = pack_bf16((bf16_lo(x.w) - dl * bf16_lo(y.w)) * iz, (bf16_hi(x.w) - dl * bf16_hi(y.w)) * iz);
+    p1[q] = o;
   }
 }
 
@@ -1089,8 +1125,9 @@ struct FinalizeArgs {
   DevicePlan pl; int B; int64_t T; int probe;
   float* g; int ksplit; int64_t n_pad; int H;
   int64_t g_rows;                          // rows per k-split plane of g
-  const float* delta; const float* inv_z;  // single-sweep mode: g = (G1 - delta G2) inv_z, else NULL
-  // sampled estimator (Eq. 4): g = c_t (W_s[y_t] - G2 inv_z); cr NULL selects the expected one
+  const float* inv_z;                      // 1 / Z_s per computed row (sampled estimator)
+  // sampled estimator (Eq. 4): g = c_t (W_s[y_t] - G2 inv_z), G2 = E2 W_s in the second half of
+  // g; cr NULL: g is the contraction of the logit gradient itself, in the first half
   const float* cr; const int32_t* ids; const __bf16* W_s; int V;
   float grad_scale; int dh_bf16;
   void* dh_prefix; void* dh_full;
@@ -1126,9 +1163,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a) {
   const float sp = admitted ? a.grad_scale * a.pl.alpha_p[i] : 0.f;
   const float sf = a.grad_scale * a.pl.alpha_f[i];
   float nrm = 0.f;
-  const float dl = a.delta ? a.delta[r] : 0.f, iz = a.inv_z ? a.inv_z[r] : 1.f;
   if (a.cr) {
-    const float c = a.cr[r];
+    const float c = a.cr[r], iz = a.inv_z[r];
     const int y = a.ids[t];
     const bool ok = y >= 0 && y < a.V;            // c is 0 otherwise
     const uint2* wy = (const uint2*)(a.W_s + (int64_t)(ok ? y : 0) * a.H);
@@ -1161,16 +1197,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a) {
       const float4 q = *(const float4*)(a.g + ((int64_t)s * a.g_rows + r) * a.H + h);
       g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w;
     }
-    if (a.delta) {
-      float4 g2 = *(const float4*)(a.g + (a.n_pad + r) * a.H + h);
-      for (int s = 1; s < a.ksplit; ++s) {
-        const float4 q = *(const float4*)(a.g + ((int64_t)s * a.g_rows + a.n_pad + r) * a.H + h);
-        g2.x += q.x; g2.y += q.y; g2.z += q.z; g2.w += q.w;
-      }
-      g.x = (g.x - dl * g2.x) * iz; g.y = (g.y - dl * g2.y) * iz;
-      g.z = (g.z - dl * g2.z) * iz; g.w = (g.w - dl * g2.w) * iz;
-    }
-    if (a.ksplit > 1 || a.delta) *(float4*)(a.g + r * a.H + h) = g;
+    if (a.ksplit > 1) *(float4*)(a.g + r * a.H + h) = g;
     nrm = fmaf(g.x, g.x, fmaf(g.y, g.y, fmaf(g.z, g.z, fmaf(g.w, g.w, nrm))));
     const float4 p = {g.x * sp, g.y * sp, g.z * sp, g.w * sp};
     store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, p);
@@ -1265,8 +1292,8 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   if (strips1 > kMaxStrips) strips1 = kMaxStrips;
   L.strips1 = strips1;
   const int halves = L.single ? 2 : 1;     // the single sweep stores two factors per logit
-  // ... of which the sampled estimator contracts only the second
-  const int gemm_halves = (L.single && p->estimator == ADWIN_EST_SAMPLED) ? 1 : halves;
+  // ... but the gradient GEMM contracts one: the combined logit gradient, or E2 (sampled estimator)
+  const int gemm_halves = 1;
   const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
   // Rows per slab: a multiple of 8 token tiles (whole rounds of the sweep's workgroups on
   // 256 compute units) between 4,096 and 16,384, chosen so that the gradient GEMM's
@@ -1559,24 +1586,33 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         else if (diag) logit_pass_dma_kernel<kModeSingleDiag><<<sweep_grid, 256, kDmaLds, stream>>>(la);
         else logit_pass_dma_kernel<kModeSingle><<<sweep_grid, 256, kDmaLds, stream>>>(la);
         ADWIN_HIP_TRY(hipGetLastError());
-        phase(ADWIN_PHASE_GRAD);
+        // this slab's rows are complete: KL_t, c_t, mu; then the logit gradient proper
+        phase(ADWIN_PHASE_MERGE);
+        MergeSingleArgs ms;
+        ms.m = m; ms.m.strips = L.strips1;
+        ms.ref_s2 = la.ref_s2; ms.ref_t2 = la.ref_t2; ms.mu0 = la.mu0;
+        ms.delta = (float*)(ws + L.o_delta); ms.inv_z = (float*)(ws + L.o_invz);
+        ms.row0 = r0; ms.rows = rows;
+        merge_single_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, stream>>>(ms);
+        ADWIN_HIP_TRY(hipGetLastError());
         ga.slab_row0 = r0;
-        if (sampled) {       // only the E2 half of the slab, into the second half of g
+        ga.row_tiles = (int)(rows / kGradTile);
+        if (sampled) {       // contract the E2 factor; c_t and W_s[y_t] enter in finalize_kernel
           ga.slab = la.slab + la.e2_off;
-          ga.half_tiles = 0; ga.row_tiles = (int)(rows / kGradTile);
+          ga.half_tiles = 0;                       // output rows in the second half of g
         } else {
-          ga.half_tiles = (int)(rows / kGradTile); ga.row_tiles = 2 * ga.half_tiles;
+          phase(ADWIN_PHASE_DZ);
+          CombineArgs ca;
+          ca.slab = (uint4*)la.slab; ca.e2_vec = la.e2_off / 8;
+          ca.delta = ms.delta; ca.inv_z = ms.inv_z; ca.row0 = r0; ca.nk = ga.nk_total;
+          combine_kernel<<<dim3((unsigned)ga.nk_total, (unsigned)ga.row_tiles), 256, 0, stream>>>(ca);
+          ADWIN_HIP_TRY(hipGetLastError());
+          ga.half_tiles = ga.row_tiles;            // output rows in the first half of g
         }
+        phase(ADWIN_PHASE_GRAD);
         launch_grad(ga, L, stream);
         ADWIN_HIP_TRY(hipGetLastError());
       }
-      phase(ADWIN_PHASE_MERGE);
-      MergeSingleArgs ms;
-      ms.m = m; ms.m.strips = L.strips1;
-      ms.ref_s2 = la.ref_s2; ms.ref_t2 = la.ref_t2; ms.mu0 = la.mu0;
-      ms.delta = (float*)(ws + L.o_delta); ms.inv_z = (float*)(ws + L.o_invz);
-      merge_single_kernel<<<(unsigned)((n_pad + 3) / 4), 256, 0, stream>>>(ms);
-      ADWIN_HIP_TRY(hipGetLastError());
     } else {
       // Two sweeps: statistics over all token tiles, merge, then per row slab the dz sweep
       // and its GEMM with W_s.
@@ -1621,7 +1657,6 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     f.pl = pl; f.B = p->B; f.T = p->T; f.probe = probe;
     f.g = gws; f.ksplit = L.ksplit; f.n_pad = n_pad; f.H = p->H_s;
     f.g_rows = L.single ? 2 * n_pad : n_pad;
-    f.delta = L.single ? (const float*)(ws + L.o_delta) : nullptr;
     f.inv_z = L.single ? (const float*)(ws + L.o_invz) : nullptr;
     f.cr = (L.single && p->estimator == ADWIN_EST_SAMPLED) ? (const float*)(ws + L.o_cr) : nullptr;
     f.ids = p->ids; f.W_s = (const __bf16*)p->W_s; f.V = p->V;
