@@ -41,6 +41,11 @@ struct DevicePlan {
 
 int validate_ragged(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window);
 
+// True the first time it is called for (slot, current device): function attributes such as
+// the dynamic-LDS opt-in are per device, so they are set once on every device that is used.
+// `slot` distinguishes call sites (0..3).  Thread-safe.
+bool first_use_on_device(int slot);
+
 const char* last_hip_error_text();
 void set_last_hip_error(hipError_t e, const char* where);
 

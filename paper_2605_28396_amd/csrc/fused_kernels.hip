@@ -1385,8 +1385,7 @@ static int check_problem(const adwin_opd_problem* p) {
 }
 
 static hipError_t ensure_lds_opt_in() {
-  static bool done = false;
-  if (done) return hipSuccess;
+  if (!first_use_on_device(0)) return hipSuccess;
   hipError_t e;
   e = hipFuncSetAttribute((const void*)logit_pass_kernel<false>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kLogitLds);
@@ -1415,7 +1414,6 @@ static hipError_t ensure_lds_opt_in() {
   e = hipFuncSetAttribute((const void*)grad_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                           kGradLds);
   if (e != hipSuccess) return e;
-  done = true;
   return hipSuccess;
 }
 

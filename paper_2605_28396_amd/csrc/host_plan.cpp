@@ -19,6 +19,14 @@ void set_last_hip_error(hipError_t e, const char* where) {
            hipGetErrorString(e), where);
 }
 
+bool first_use_on_device(int slot) {
+  static std::atomic<unsigned long long> seen[4];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63 || slot < 0 || slot > 3) return true;
+  const unsigned long long bit = 1ull << dev;
+  return (seen[slot].fetch_or(bit) & bit) == 0;
+}
+
 int validate_ragged(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window) {
   if (!offsets || !window) return ADWIN_E_NULL;
   if (B < 1 || T < 0 || T >= (int64_t(1) << 31)) return ADWIN_E_SHAPE;

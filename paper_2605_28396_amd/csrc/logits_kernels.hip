@@ -490,12 +490,9 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
     } else if (streaming) {
       logits_row_kernel<false><<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
     } else {
-      static bool opted = false;
-      if (!opted) {
+      if (first_use_on_device(1))
         ADWIN_HIP_TRY(hipFuncSetAttribute((const void*)logits_row_resident_kernel,
                                           hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes));
-        opted = true;
-      }
       logits_row_resident_kernel<<<(unsigned)p->T, kResThreads, kResLdsBytes, stream>>>(a);
     }
     ADWIN_HIP_TRY(hipGetLastError());

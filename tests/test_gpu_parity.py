@@ -295,3 +295,30 @@ def test_sampled_estimator_from_logits(B, env, monkeypatch):
     y = f["ids"][rows]
     # the one-hot entry carries the sign of c_t * scale, every other entry the opposite one
     assert np.all(np.sign(got["dz"][rows, y]) == np.sign(-2.0 * ref["c"][rows]))
+
+
+def test_degenerate_batches(B):
+    """Nothing admitted (all windows zero), and no rows at all: every output is defined and zero."""
+    w = synth.workload("ragged_small")
+    p = synth.hidden_problem(w)
+    d = {k: v.cuda() for k, v in p.items()}
+    zero_w = np.zeros(w.B, np.int32)
+    out = B.adwin_opd_fused(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, zero_w,
+                            mode=B.ADWIN_PREFIX_ONLY, reduction=B.ADWIN_RED_SEQ_MEAN)
+    torch.cuda.synchronize()
+    assert int(out["n_adm_out"][0]) == 0 and not out["n_out"].any() and int(out["status_dev"][0]) == 0
+    for k in ("kl", "c", "dh_prefix", "loss_prefix", "loss_full", "rho_pooled", "rho_field", "batch"):
+        assert not out[k].any(), k
+    lo = synth.logits_problem(w)
+    dl = {k: v.cuda() for k, v in lo.items()}
+    out = B.adwin_opd_from_logits(dl["z_s"], dl["z_t"], dl["ids"], w.offsets, zero_w)
+    torch.cuda.synchronize()
+    assert not out["dz"].view(torch.int16).any() and not out["kl"].any() and not out["batch"].any()
+    # no rows at all: three empty rollouts
+    off0 = np.zeros(4, np.int64)
+    e = {k: v[:0].contiguous() for k, v in d.items() if k in ("h_s", "h_t", "ids")}
+    out = B.adwin_opd_fused(e["h_s"], e["h_t"], d["W_s"], d["W_t"], e["ids"], off0, np.array([5, 0, 9], np.int32),
+                            mode=B.ADWIN_PREFIX_AND_FULL)
+    torch.cuda.synchronize()
+    assert int(out["n_adm_out"][0]) == 0 and not out["batch"].any() and not out["loss_full"].any()
+    assert not out["rho_pooled"].any() and int(out["status_dev"][0]) == 0
