@@ -111,6 +111,9 @@ def main() -> int:
     ap.add_argument("--estimator", default="expected", choices=["expected", "sampled"],
                     help="expected: gradient of the full-vocabulary KL (default, the metric's path); "
                          "sampled: Eq. 4 on the sampled token (one gradient contraction)")
+    ap.add_argument("--head-grad", action="store_true",
+                    help="also emit the gradient with respect to the student LM-head weights "
+                         "(dW_s, one more contraction per objective; not part of the headline metric)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
@@ -141,7 +144,8 @@ def main() -> int:
         call = B.FusedCall(prob["h_s"], prob["h_t"], prob["W_s"], prob["W_t"], prob["ids"],
                            w.offsets, w.window, mode=w.mode, reduction=B.ADWIN_RED_SEQ_MEAN,
                            dh_dtype=B.ADWIN_DT_BF16 if args.dh_dtype == "bf16" else B.ADWIN_DT_F32,
-                           estimator=est)
+                           estimator=est,
+                           want=B.FusedCall.DEFAULT_OUTPUTS + (("dW_prefix", "dW_full") if args.head_grad else ()))
         profile = B.adwin_opd_fused_profile
         tokens = w.T if w.mode == synth.MODE_PREFIX_AND_FULL else n_adm
     torch.cuda.synchronize()
@@ -188,6 +192,8 @@ def main() -> int:
                     "alg_flops_per_launch": f_stats}
         f_stats *= launches
         f_alg = 2.0 * V * (2 * Hs + Ht) * tokens            # student fwd + teacher fwd + dz W_s
+        if args.head_grad:                                  # + dz^T h_s per objective
+            f_alg += 2.0 * V * Hs * tokens * (2 if w.mode == synth.MODE_PREFIX_AND_FULL else 1)
         # executed = algorithmic on the single-sweep scheme: logits once, one gradient contraction
         f_exec = f_alg
         f_grad = 2.0 * V * Hs * tokens
@@ -215,7 +221,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "rollouts": w.B, "packed_rows": w.T, "computed_rows": tokens,
                    "V": w.V, "H_s": w.H_s, "H_t": w.H_t,
-                   "mode": "prefix_and_full" if w.mode else "prefix_only", "estimator": args.estimator},
+                   "mode": "prefix_and_full" if w.mode else "prefix_only", "estimator": args.estimator, "head_grad": bool(args.head_grad)},
         "roofline": roofline, "cpu_baseline": cpu, "phase_ms": ph,
     }
     line["ceilings"] = {"copy_GBps": B.adwin_opd_ceiling_copy(), "mfma_bf16_TFLOPs": B.adwin_opd_ceiling_mfma(),

@@ -135,6 +135,11 @@ typedef struct adwin_opd_problem {
   int32_t* t_rank;           /* [T] 1 + number of entries the teacher ranks strictly above y_t  */
                              /*     (needs ids; 0 for an id outside [0, V))                     */
   int32_t estimator;         /* ADWIN_EST_EXPECTED | ADWIN_EST_SAMPLED                          */
+  /* Gradients of the batch objectives with respect to the student LM-head weights (z = W h):
+   * sum_t grad_scale * alpha_i * dz_t^T h_s[t], the third contraction of the LM-head backward.
+   * NULL = not wanted; each costs one more 2 V H_s FLOP per token.  Estimator EXPECTED only. */
+  float* dW_prefix;          /* [V, H_s] prefix-window objective                                */
+  float* dW_full;            /* [V, H_s] full-rollout objective (mode PREFIX_AND_FULL only)     */
 } adwin_opd_problem;
 
 /*

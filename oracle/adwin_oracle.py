@@ -137,14 +137,23 @@ def token_terms(h_s, h_t, W_s, W_t, y=None, estimator=EST_EXPECTED):
     return kl, c, g
 
 
-def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED):
+def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, head_weights=None):
     """`token_terms` for a stack of independent rows.  Rows are batched through one
     matrix product per block only to let BLAS do the inner products; each row's
-    softmax/KL/gradient is the single-row definition above."""
+    softmax/KL/gradient is the single-row definition above.
+
+    head_weights: optional list of per-row weight vectors w; for each one the gradient of
+    sum_r w[r] KL_r with respect to the student LM-head weights, sum_r w[r] dz_r^T h_s[r]
+    (z = W h, so d z[v] / d W[v, k] = h[k]), is returned as a fourth value, and as a fifth the
+    Euclidean norm over r of the summands of each element, sqrt(sum_r (w[r] dz_r[v] h_s[r][k])^2):
+    the scale of the rounding error of any implementation that rounds the factors of the
+    summands independently (tests bound a reduced-precision result with it)."""
     K = H_s.shape[0]
     kl = np.zeros(K)
     c = np.zeros(K)
     g = np.zeros((K, W_s.shape[1]))
+    dW = None if head_weights is None else [np.zeros(W_s.shape) for _ in head_weights]
+    dW_sq = None if head_weights is None else [np.zeros(W_s.shape) for _ in head_weights]
     for r0 in range(0, K, block):
         r1 = min(K, r0 + block)
         Z_s = H_s[r0:r1] @ W_s.T
@@ -160,6 +169,13 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED):
             else:
                 D[r - r0] = token_dz_sampled(z_s, z_t, int(ids[r]))
         g[r0:r1] = D @ W_s
+        if dW is not None:
+            for k, w in enumerate(head_weights):
+                wD = D * np.asarray(w)[r0:r1, None]
+                dW[k] += wD.T @ H_s[r0:r1]
+                dW_sq[k] += (wD ** 2).T @ (H_s[r0:r1] ** 2)
+    if dW is not None:
+        return kl, c, g, dW, [np.sqrt(x) for x in dW_sq]
     return kl, c, g
 
 
@@ -254,8 +270,13 @@ def window_outputs(kl, g, offsets, window, reduction=RED_SEQ_MEAN, grad_scale=1.
 
 
 def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
-              grad_scale=1.0, mode=MODE_PREFIX_ONLY, estimator=EST_EXPECTED):
-    """Whole path from hidden states (fp64 arrays holding the bf16-exact inputs)."""
+              grad_scale=1.0, mode=MODE_PREFIX_ONLY, estimator=EST_EXPECTED, head_gradient=False,
+              block=16):
+    """Whole path from hidden states (fp64 arrays holding the bf16-exact inputs).
+    head_gradient: also dW_prefix / dW_full, the gradients of the prefix and full-rollout
+    batch objectives (times grad_scale) with respect to the student LM-head weights, and
+    dW_prefix_l2 / dW_full_l2, the Euclidean norms of their per-token summands.
+    block: rows per library matrix product in `rows_terms` (batching only)."""
     p = plan(offsets, window)
     T = int(offsets[-1])
     if mode == MODE_PREFIX_AND_FULL:
@@ -263,12 +284,31 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
     else:
         rows = p["rows"]
     kl, c, g = np.zeros(T), np.zeros(T), np.zeros((T, W_s.shape[1]))
+    dW = dW_l2 = None
+    hw = None
+    if head_gradient:
+        ap, af = row_weights(p["len"], p["n"], reduction)
+        wp, wf = np.zeros(T), np.zeros(T)
+        for i in range(len(p["n"])):
+            o = int(offsets[i])
+            wp[o:o + int(p["n"][i])] = grad_scale * ap[i]
+            wf[o:o + int(p["len"][i])] = grad_scale * af[i]
+        hw = [wp[rows], wf[rows]]
     if len(rows):
-        k_, c_, g_ = rows_terms(h_s[rows], h_t[rows], W_s, W_t,
-                                None if ids is None else np.asarray(ids)[rows], estimator=estimator)
-        kl[rows], c[rows], g[rows] = k_, c_, g_
+        res = rows_terms(h_s[rows], h_t[rows], W_s, W_t,
+                         None if ids is None else np.asarray(ids)[rows], block=block,
+                         estimator=estimator, head_weights=hw)
+        kl[rows], c[rows], g[rows] = res[0], res[1], res[2]
+        if head_gradient:
+            dW, dW_l2 = res[3], res[4]
     out = window_outputs(kl, g, offsets, window, reduction, grad_scale, mode)
     out.update(kl=kl, c=c, g=g, rows=rows)
+    if head_gradient:
+        zero = np.zeros(W_s.shape)
+        out["dW_prefix"] = dW[0] if dW is not None else zero
+        out["dW_full"] = (dW[1] if dW is not None else zero) if mode == MODE_PREFIX_AND_FULL else zero
+        out["dW_prefix_l2"] = dW_l2[0] if dW is not None else zero
+        out["dW_full_l2"] = (dW_l2[1] if dW is not None else zero) if mode == MODE_PREFIX_AND_FULL else zero
     return out
 
 

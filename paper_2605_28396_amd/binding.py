@@ -45,6 +45,7 @@ class adwin_opd_problem(C.Structure):
         ("cand_rho_pooled", C.c_void_p), ("cand_rho_field", C.c_void_p), ("cand_batch", C.c_void_p),
         ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
         ("estimator", C.c_int32),
+        ("dW_prefix", C.c_void_p), ("dW_full", C.c_void_p),
     ]
 
 
@@ -205,11 +206,12 @@ class FusedCall:
     """A marshalled adwin_opd_fused call: problem struct, output tensors and workspace,
     all allocated once; `run()` only enqueues."""
 
+    DEFAULT_OUTPUTS = ("kl", "c", "dh_prefix", "dh_full", "loss_prefix", "loss_full", "rho_pooled",
+                       "rho_field", "batch", "n_out", "n_adm_out", "status_dev")
+
     def __init__(self, h_s, h_t, W_s, W_t, ids, offsets, window, mode=ADWIN_PREFIX_ONLY,
                  reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0, dh_dtype=ADWIN_DT_F32,
-                 want=("kl", "c", "dh_prefix", "dh_full", "loss_prefix", "loss_full", "rho_pooled",
-                       "rho_field", "batch", "n_out", "n_adm_out", "status_dev"),
-                 device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED):
+                 want=DEFAULT_OUTPUTS, device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.candidates = None if candidates is None else _host_i32(candidates)
         self.inputs = (h_s, h_t, W_s, W_t, ids)
@@ -244,9 +246,10 @@ class FusedCall:
                 "n_adm_out": ((1,), torch.int64), "status_dev": ((1,), torch.int32),
                 "t_logp": ((T,), torch.float32), "t_entropy": ((T,), torch.float32),
                 "t_rank": ((T,), torch.int32),
+                "dW_prefix": ((V, H_s), torch.float32), "dW_full": ((V, H_s), torch.float32),
             }
             for k in want:
-                if k == "dh_full" and mode != ADWIN_PREFIX_AND_FULL:
+                if k in ("dh_full", "dW_full") and mode != ADWIN_PREFIX_AND_FULL:
                     continue
                 shp, dt = shapes[k]
                 self.out[k] = torch.empty(shp, dtype=dt, device=dev)

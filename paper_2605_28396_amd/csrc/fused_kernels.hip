@@ -909,26 +909,129 @@ struct CombineArgs {
   const float* delta; const float* inv_z;   // per computed row
   int64_t row0;                         // computed-row index of slab row 0
   int nk;                               // k-steps (blocks) per row tile
+  // TR: also the transpose of w * dz as tile images for the head-weight GEMMs (rows =
+  // vocabulary entries in tiles of 256, k = slab rows): block (vt, kr) with kr = 4 rt + j,
+  // j = 0..3.  w = grad_scale * alpha of the row under the prefix objective (dzT_p; 0 outside
+  // the window) and under the full-rollout objective (dzT_f); the weight is applied in fp32
+  // before the one rounding to bf16.  Either image may be NULL.
+  uint4* dzT_p; uint4* dzT_f; int nkr;  // k-steps (of 64 slab rows) per vocabulary tile
+  DevicePlan pl; int64_t n_rows; float grad_scale;
 };
 
+template <bool TR>
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
-  // one workgroup per block (row tile, kt): 2048 vectors of 8 entries, row = vector / 8
-  const int64_t blk = (int64_t)blockIdx.y * a.nk + blockIdx.x;
+  // one workgroup per block (row tile rt = blockIdx.y, kt = blockIdx.x): 2048 vectors of 8
+  // entries; vector q holds row q / 8, chunk position q % 8
+  __shared__ __align__(16) uint16_t tile[TR ? kTileTokens : 1][TR ? kBK + 8 : 1];   // [row][entry], padded
+  __shared__ float wrow[2][TR ? kTileTokens : 1];
+  const int kt = blockIdx.x, rt = blockIdx.y;
+  const int64_t blk = (int64_t)rt * a.nk + kt;
   uint4* p1 = a.slab + blk * (kImgBytesSlab / 16);
   const uint4* p2 = p1 + a.e2_vec;
-  const int64_t rbase = a.row0 + (int64_t)blockIdx.y * kTileTokens;
+  const int64_t rbase = a.row0 + (int64_t)rt * kTileTokens;
+  if (TR) {
+    const int64_t r = rbase + threadIdx.x;
+    float wp = 0.f, wf = 0.f;
+    if (r < a.n_rows) {
+      const int i = a.pl.row_seq[r];
+      wf = a.grad_scale * a.pl.alpha_f[i];
+      wp = (r - a.pl.comp_off[i]) < a.pl.n[i] ? a.grad_scale * a.pl.alpha_p[i] : 0.f;
+    }
+    wrow[0][threadIdx.x] = wp;
+    wrow[1][threadIdx.x] = wf;
+    __syncthreads();
+  }
+  float dz[TR ? 8 : 1][8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int q = i * 256 + threadIdx.x;
     const int64_t r = rbase + (q >> 3);
     const float dl = a.delta[r], iz = a.inv_z[r];
     const uint4 x = p1[q], y = p2[q];
+    float d[8];
+    d[0] = (bf16_lo(x.x) - dl * bf16_lo(y.x)) * iz; d[1] = (bf16_hi(x.x) - dl * bf16_hi(y.x)) * iz;
+    d[2] = (bf16_lo(x.y) - dl * bf16_lo(y.y)) * iz; d[3] = (bf16_hi(x.y) - dl * bf16_hi(y.y)) * iz;
+    d[4] = (bf16_lo(x.z) - dl * bf16_lo(y.z)) * iz; d[5] = (bf16_hi(x.z) - dl * bf16_hi(y.z)) * iz;
+    d[6] = (bf16_lo(x.w) - dl * bf16_lo(y.w)) * iz; d[7] = (bf16_hi(x.w) - dl * bf16_hi(y.w)) * iz;
     uint4 o;
-    o.x = pack_bf16((bf16_lo(x.x) - dl * bf16_lo(y.x)) * iz, (bf16_hi(x.x) - dl * bf16_hi(y.x)) * iz);
-    o.y = pack_bf16((bf16_lo(x.y) - dl * bf16_lo(y.y)) * iz, (bf16_hi(x.y) - dl * bf16_hi(y.y)) * iz);
-    o.z = pack_bf16((bf16_lo(x.z) - dl * bf16_lo(y.z)) * iz, (bf16_hi(x.z) - dl * bf16_hi(y.z)) * iz);
-    o.w = pack_bf16((bf16_lo(x.w) - dl * bf16_lo(y.w)) * iz, (bf16_hi(x.w) - dl * bf16_hi(y.w)) * iz);
+    o.x = pack_bf16(d[0], d[1]); o.y = pack_bf16(d[2], d[3]);
+    o.z = pack_bf16(d[4], d[5]); o.w = pack_bf16(d[6], d[7]);
     p1[q] = o;
+    if (TR) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dz[i][e] = d[e];
+    }
+  }
+  if (TR) {
+    // this block's 64 entries are image rows (kt % 4) * 64 .. + 64 of vocabulary tile kt / 4;
+    // its 256 slab rows are the k-steps 4 rt .. 4 rt + 3.  Vector u: k-step u / 512, image
+    // row (u / 8) % 64, chunk position u % 8 -> one wave instruction writes 8 whole rows.
+    const int vt = kt >> 2, row0 = (kt & 3) * kBK;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      uint4* dst = which == 0 ? a.dzT_p : a.dzT_f;
+      if (!dst) continue;
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int q = i * 256 + threadIdx.x;
+        const int rl = q >> 3;
+        const float w = wrow[which][rl];
+        const int c = (q & 7) ^ ((rl >> 1) & 7);             // logical chunk: entries 8 c .. 8 c + 7
+        uint4 o = make_uint4(0u, 0u, 0u, 0u);     // rows of weight zero (padding too) are exact zeros
+        if (w != 0.f) {
+          o.x = pack_bf16(w * dz[i][0], w * dz[i][1]); o.y = pack_bf16(w * dz[i][2], w * dz[i][3]);
+          o.z = pack_bf16(w * dz[i][4], w * dz[i][5]); o.w = pack_bf16(w * dz[i][6], w * dz[i][7]);
+        }
+        *(uint4*)&tile[rl][c * 8] = o;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int u = i * 256 + threadIdx.x;
+        const int j = u >> 9, vl = (u >> 3) & 63, pos = u & 7;
+        const int imgrow = row0 + vl;
+        const int c = pos ^ ((imgrow >> 1) & 7);             // slab rows 64 j + 8 c .. + 7
+        const int rl = j * kBK + c * 8;
+        uint4 o;
+        o.x = tile[rl + 0][vl] | ((uint32_t)tile[rl + 1][vl] << 16);
+        o.y = tile[rl + 2][vl] | ((uint32_t)tile[rl + 3][vl] << 16);
+        o.z = tile[rl + 4][vl] | ((uint32_t)tile[rl + 5][vl] << 16);
+        o.w = tile[rl + 6][vl] | ((uint32_t)tile[rl + 7][vl] << 16);
+        dst[(((int64_t)vt * a.nkr + 4 * rt + j) * kGradTile + imgrow) * 8 + pos] = o;
+      }
+    }
+  }
+}
+
+// Tile images of the transpose of the student hidden states of one slab, the B operand of
+// the head-weight GEMMs: image row = hidden column (tiles of 256), k = slab row; entry =
+// h_s[row_idx[r0 + r]][h] (zero beyond H).  One workgroup per (k-step of 64 rows, hidden tile).
+struct HstImageArgs {
+  const uint16_t* h_s; const int32_t* row_idx;
+  int64_t row0;
+  int H, nkr;
+  uint16_t* img;
+};
+
+__global__ __launch_bounds__(256) void hst_image_kernel(HstImageArgs a) {
+  __shared__ uint16_t tile[kBK][kGradTile + 2];
+  const int kr = blockIdx.x, ht = blockIdx.y, tid = threadIdx.x;
+  for (int i = 0; i < kBK; ++i) {
+    const int64_t r = a.row0 + (int64_t)kr * kBK + i;
+    const int h = ht * kGradTile + tid;
+    tile[i][tid] = h < a.H ? a.h_s[(int64_t)a.row_idx[r] * a.H + h] : (uint16_t)0;
+  }
+  __syncthreads();
+  uint16_t* blk = a.img + ((int64_t)ht * a.nkr + kr) * kImgElems;
+  for (int q = tid; q < kGradTile * 8; q += 256) {
+    const int r = q >> 3, pos = q & 7, c = pos ^ ((r >> 1) & 7);
+    uint4 o;
+    o.x = tile[c * 8 + 0][r] | ((uint32_t)tile[c * 8 + 1][r] << 16);
+    o.y = tile[c * 8 + 2][r] | ((uint32_t)tile[c * 8 + 3][r] << 16);
+    o.z = tile[c * 8 + 4][r] | ((uint32_t)tile[c * 8 + 5][r] << 16);
+    o.w = tile[c * 8 + 6][r] | ((uint32_t)tile[c * 8 + 7][r] << 16);
+    *(uint4*)(blk + q * 8) = o;
   }
 }
 
@@ -952,6 +1055,8 @@ struct GradArgs {
   int row_tiles, h_tiles, ksplit;
   int half_tiles;           // slab row tiles >= half_tiles hold the E2 factor: output rows
   int64_t half_off;         // half_off + slab_row0 + ... (single-sweep mode; else half_tiles = row_tiles)
+  int64_t out_rows;         // rows of g that exist (rows at or beyond are not stored)
+  int accumulate;           // add to g instead of overwriting it
 };
 
 constexpr int kGradStage = 2 * kImgBytes;     // 64 KiB
@@ -1111,7 +1216,10 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int64_t r = out_row0 + wm * 128 + fm * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-          g[r * a.H + h] = acc[fm][fn][e];
+          if (r < a.out_rows) {
+            float* o = g + r * a.H + h;
+            *o = a.accumulate ? *o + acc[fm][fn][e] : acc[fm][fn][e];
+          }
         }
       }
     }
@@ -1265,7 +1373,7 @@ struct FusedLayout {
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, total;
 };
 
 static int env_int(const char* name, int dflt) {
@@ -1356,6 +1464,13 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_cr = take(sizeof(float) * (size_t)n_pad);
   L.o_zy_t = take(sizeof(float) * (size_t)n_pad);
   L.o_yid = take(sizeof(int32_t) * (size_t)n_pad);
+  const bool head = p->dW_prefix || p->dW_full;       // transposed slab + weighted h_s^T images
+  // vocabulary tiles of 256 image rows: the last one may be half used (its upper rows are
+  // never written, and their output rows do not exist)
+  const size_t v_img = align_up((size_t)L.Vp, (size_t)kGradTile);
+  L.o_dzT_p = take(p->dW_prefix ? 2 * (size_t)slab * v_img : 0);
+  L.o_dzT_f = take(p->dW_full ? 2 * (size_t)slab * v_img : 0);
+  L.o_hsT = take(head ? 2 * (size_t)h_tiles * kGradTile * (size_t)slab : 0);
   L.total = o;
   return L;
 }
@@ -1463,8 +1578,12 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   const bool diag = p->t_entropy || p->t_rank;          // need the diagnostics sweep
   const bool sampled = p->estimator == ADWIN_EST_SAMPLED;
   // the diagnostics and the sampled estimator ride on the single-sweep kernels
-  if ((diag || p->t_logp || sampled) && !L.single) return ADWIN_E_MODE;
+  const bool head = p->dW_prefix || p->dW_full;
+  if ((diag || p->t_logp || sampled || head) && !L.single) return ADWIN_E_MODE;
   if (sampled && !p->ids) return ADWIN_E_NULL;
+  if (head && sampled) return ADWIN_E_MODE;
+  if (p->dW_full && p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
+  if (((uintptr_t)p->dW_prefix | (uintptr_t)p->dW_full) & 15) return ADWIN_E_ALIGN;
   hipStream_t stream = (hipStream_t)hip_stream;
   unsigned char* ws = (unsigned char*)workspace;
   ADWIN_HIP_TRY(ensure_lds_opt_in());
@@ -1550,6 +1669,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     GradArgs ga;
     ga.slab = la.slab; ga.WsT = (const __bf16*)(ws + L.o_WsT); ga.nk_total = (int)(L.Vp / kBK);
     ga.g = gws; ga.H = p->H_s; ga.h_tiles = h_tiles; ga.ksplit = L.ksplit;
+    ga.out_rows = (int64_t)1 << 62; ga.accumulate = 0;
     if (L.single) {
       // Single sweep.  (1) online statistics of vocabulary tile 0 give each row its fixed
       // references; (2) per row slab: one sweep over the vocabulary producing the strip sums
@@ -1603,13 +1723,41 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
           CombineArgs ca;
           ca.slab = (uint4*)la.slab; ca.e2_vec = la.e2_off / 8;
           ca.delta = ms.delta; ca.inv_z = ms.inv_z; ca.row0 = r0; ca.nk = ga.nk_total;
-          combine_kernel<<<dim3((unsigned)ga.nk_total, (unsigned)ga.row_tiles), 256, 0, stream>>>(ca);
+          ca.dzT_p = p->dW_prefix ? (uint4*)(ws + L.o_dzT_p) : nullptr;
+          ca.dzT_f = p->dW_full ? (uint4*)(ws + L.o_dzT_f) : nullptr;
+          ca.nkr = (int)(rows / kBK); ca.pl = pl; ca.n_rows = hp.n_rows; ca.grad_scale = p->grad_scale;
+          const dim3 cgrid((unsigned)ga.nk_total, (unsigned)ga.row_tiles);
+          if (head) combine_kernel<true><<<cgrid, 256, 0, stream>>>(ca);
+          else combine_kernel<false><<<cgrid, 256, 0, stream>>>(ca);
           ADWIN_HIP_TRY(hipGetLastError());
           ga.half_tiles = ga.row_tiles;            // output rows in the first half of g
         }
         phase(ADWIN_PHASE_GRAD);
         launch_grad(ga, L, stream);
         ADWIN_HIP_TRY(hipGetLastError());
+        if (head) {
+          // head-weight gradient of this slab: dW += dz^T (w h_s), k = the slab's rows
+          GradArgs wa = ga;
+          wa.WsT = (const __bf16*)(ws + L.o_hsT);
+          wa.nk_total = (int)(rows / kBK);
+          wa.H = p->H_s; wa.h_tiles = h_tiles; wa.ksplit = 1;
+          wa.slab_row0 = 0; wa.row_tiles = (int)((L.Vp + kGradTile - 1) / kGradTile); wa.half_tiles = wa.row_tiles;
+          wa.half_off = 0; wa.g_rows = 0; wa.out_rows = p->V; wa.accumulate = r0 > 0;
+          HstImageArgs ha;
+          ha.h_s = (const uint16_t*)p->h_s; ha.row_idx = pl.row_idx;
+          ha.row0 = r0; ha.H = p->H_s; ha.nkr = wa.nk_total;
+          ha.img = (uint16_t*)(ws + L.o_hsT);
+          hst_image_kernel<<<dim3((unsigned)ha.nkr, (unsigned)h_tiles), 256, 0, stream>>>(ha);
+          ADWIN_HIP_TRY(hipGetLastError());
+          for (int which = 0; which < 2; ++which) {
+            float* out = which == 0 ? p->dW_prefix : p->dW_full;
+            if (!out) continue;
+            wa.slab = (const __bf16*)(ws + (which == 0 ? L.o_dzT_p : L.o_dzT_f));
+            wa.g = out;
+            grad_gemm_kernel<<<(unsigned)(wa.row_tiles * wa.h_tiles), 256, kGradLds, stream>>>(wa);
+            ADWIN_HIP_TRY(hipGetLastError());
+          }
+        }
       }
     } else {
       // Two sweeps: statistics over all token tiles, merge, then per row slab the dz sweep
@@ -1647,6 +1795,10 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         ADWIN_HIP_TRY(hipGetLastError());
       }
     }
+  }
+  if (hp.n_rows == 0) {     // nothing computed: the head-weight gradients are zero
+    ADWIN_HIP_TRY(launch_fill_f32(p->dW_prefix, (int64_t)p->V * p->H_s, 0.f, stream));
+    ADWIN_HIP_TRY(launch_fill_f32(p->dW_full, (int64_t)p->V * p->H_s, 0.f, stream));
   }
   // finalize over every packed row (also zero-fills rows outside the windows)
   phase(ADWIN_PHASE_REDUCE);

@@ -13,6 +13,15 @@ DH_REL = 2e-3
 RHO_ABS = 2e-3
 LOSS_REL = 1e-3
 BF16_ULP = 2.0 ** -8   # storage rounding of a bf16 output element, relative
+# Head-weight gradient dW[v][k] = sum_r w_r dz_r[v] h_s[r][k]: the kernels round the dz factor
+# of every summand to bf16 three times (the two stored gradient factors, then w dz), each a
+# relative error uniform in +-2^-9 at worst, rms 2^-9 / sqrt(3); the three together have rms
+# 2^-9 and are independent across summands, so the error of an element has standard deviation
+# <= 2^-9 * (Euclidean norm of its summands).  With few hundred rows the summands are heavy-
+# tailed and an element can be one summand, so no fraction of max|dW| below 2^-8 is safe; the
+# per-element bound is, and a dropped or misplaced row breaks it for most elements.
+DW_SIGMA = 2.0 ** -9
+DW_SIGMAS = 8.0        # max over ~1e6..1e9 elements of a sum of bounded errors stays below 6 sigma
 
 
 def oracle_inputs(p: dict) -> dict:

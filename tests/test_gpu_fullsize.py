@@ -110,6 +110,39 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name, estimator):
     _free()
 
 
+def test_head_weight_gradient_full_vocabulary(B):
+    """dW_s at the benchmark's vocabulary size (all 594 vocabulary tiles; 4 hidden tiles) over a
+    batch and hidden sizes small enough for the oracle: every row feeds every element, so rows
+    cannot be sampled; the batch is what is reduced."""
+    print("[case] head-weight gradient, full vocabulary", flush=True)
+    full = synth.workload("strong_to_weak")
+    lens = [40, 0, 70, 21]
+    w = synth.Workload("head_full_vocab", full.V, 1024, 1024, synth._offsets(lens),
+                       np.array([30, 7, 100, 0], np.int32))
+    dev = torch.device("cuda:0")
+    p = synth.hidden_problem(w, dev)
+    want = ("kl", "c", "dh_prefix", "loss_prefix", "loss_full", "rho_pooled", "rho_field", "batch",
+            "n_out", "n_adm_out", "status_dev", "dW_prefix")
+    call = B.FusedCall(p["h_s"], p["h_t"], p["W_s"], p["W_t"], p["ids"], w.offsets, w.window,
+                       mode=w.mode, reduction=B.ADWIN_RED_SEQ_MEAN, grad_scale=3.0, dh_dtype=B.ADWIN_DT_F32,
+                       want=want)
+    assert call.run() == 0
+    torch.cuda.synchronize()
+    f = {k: synth.to_f64(p[k]) for k in ("h_s", "h_t", "W_s", "W_t")}
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], p["ids"].cpu().numpy(), w.offsets, w.window,
+                      reduction=O.RED_SEQ_MEAN, grad_scale=3.0, mode=w.mode, head_gradient=True, block=128)
+    print("[case] oracle done", flush=True)
+    got = call.out["dW_prefix"].double().cpu().numpy()
+    scale = np.abs(ref["dW_prefix"]).max()
+    err = np.abs(got - ref["dW_prefix"])
+    tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["dW_prefix_l2"] + 1e-6 * scale
+    assert (err <= tol).all(), (err.max(), scale, (err / tol).max())
+    Hp.assert_grad(call.out["dh_prefix"].cpu().numpy(), ref["dh_prefix"], "dh_prefix")
+    del call, p, f, ref
+    _free()
+
+
+
 def test_logits_given_full_size_sampled_rows(B):
     print("[case] logits-given full size", flush=True)
     w = synth.workload("logits_given")

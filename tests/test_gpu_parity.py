@@ -304,10 +304,12 @@ def test_degenerate_batches(B):
     d = {k: v.cuda() for k, v in p.items()}
     zero_w = np.zeros(w.B, np.int32)
     out = B.adwin_opd_fused(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, zero_w,
-                            mode=B.ADWIN_PREFIX_ONLY, reduction=B.ADWIN_RED_SEQ_MEAN)
+                            mode=B.ADWIN_PREFIX_ONLY, reduction=B.ADWIN_RED_SEQ_MEAN,
+                            want=("kl", "c", "dh_prefix", "loss_prefix", "loss_full", "rho_pooled", "rho_field",
+                                  "batch", "n_out", "n_adm_out", "status_dev", "dW_prefix"))
     torch.cuda.synchronize()
     assert int(out["n_adm_out"][0]) == 0 and not out["n_out"].any() and int(out["status_dev"][0]) == 0
-    for k in ("kl", "c", "dh_prefix", "loss_prefix", "loss_full", "rho_pooled", "rho_field", "batch"):
+    for k in ("kl", "c", "dh_prefix", "loss_prefix", "loss_full", "rho_pooled", "rho_field", "batch", "dW_prefix"):
         assert not out[k].any(), k
     lo = synth.logits_problem(w)
     dl = {k: v.cuda() for k, v in lo.items()}
@@ -322,3 +324,55 @@ def test_degenerate_batches(B):
     torch.cuda.synchronize()
     assert int(out["n_adm_out"][0]) == 0 and not out["batch"].any() and not out["loss_full"].any()
     assert not out["rho_pooled"].any() and int(out["status_dev"][0]) == 0
+
+
+WANT_HEAD = ("kl", "c", "dh_prefix", "dh_full", "loss_prefix", "loss_full", "rho_pooled", "rho_field",
+             "batch", "n_out", "n_adm_out", "status_dev", "dW_prefix", "dW_full")
+
+
+def _check_head_gradient(got, ref, probe):
+    for k in ("dW_prefix", "dW_full") if probe else ("dW_prefix",):
+        scale = np.abs(ref[k]).max()
+        err = np.abs(got[k] - ref[k])
+        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref[k + "_l2"] + 1e-6 * scale
+        assert (err <= tol).all(), (k, err.max(), scale, (err / tol).max())
+        assert err.max() <= 2.0 ** -7 * scale
+        # every dz row sums to zero over the vocabulary, so every column of dW does
+        assert np.abs(got[k].astype(np.float64).sum(axis=0)).max() <= 1e-3 * np.abs(got[k]).sum(axis=0).max()
+
+
+@pytest.mark.parametrize("name,reduction", [("tiny_probe", O.RED_SUM), ("ragged_small", O.RED_SEQ_MEAN),
+                                            ("ragged_mid", O.RED_TOKEN_MEAN), ("tiny", O.RED_SUM)])
+def test_head_weight_gradient(B, name, reduction):
+    """dW_s of the prefix and of the full-rollout objective: the third contraction of the
+    LM-head backward, sum_t w_t dz_t^T h_s[t]."""
+    w = synth.workload(name)
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    probe = w.mode == synth.MODE_PREFIX_AND_FULL
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=reduction, grad_scale=-1.5, mode=w.mode, head_gradient=True)
+    got = _run_fused(B, w, p, "cuda", reduction=reduction, grad_scale=-1.5, want=WANT_HEAD)
+    _check_fused(w, got, ref, reduction)
+    _check_head_gradient(got, ref, probe)
+
+
+def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
+    """Rows split over several slabs: every slab adds its product to dW."""
+    monkeypatch.setenv("ADWIN_SLAB_ROWS", "512")
+    w = synth.workload("ragged_mid")
+    p = synth.hidden_problem(w)
+    d = {k: v.cuda() for k, v in p.items()}
+    call = B.FusedCall(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window, mode=w.mode,
+                       reduction=O.RED_SUM, want=WANT_HEAD)
+    assert B.adwin_opd_fused_launch_info(call.p)["slabs"] >= 4
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SUM, mode=w.mode, head_gradient=True)
+    for _ in range(2):          # a second run over the same buffers overwrites, never adds to, the first
+        assert call.run() == 0
+        torch.cuda.synchronize()
+        got = {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
+               for k, v in call.out.items()}
+        _check_fused(w, got, ref, O.RED_SUM)
+        _check_head_gradient(got, ref, True)

@@ -438,6 +438,50 @@ def test_audit_field_cosine_closed_form():
         assert np.all(a["macro_field"] == pytest.approx(a["rho_field"].mean(axis=1)))
 
 
+def test_head_weight_gradient_finite_differences():
+    # dW = gradient of the batch objective with respect to the student LM-head weights
+    V, Hs, Ht = 7, 4, 3
+    W_s, W_t = RNG.normal(0, 0.7, (V, Hs)), RNG.normal(0, 0.7, (V, Ht))
+    lens = np.array([3, 5])
+    offsets = np.concatenate([[0], np.cumsum(lens)])
+    T = int(offsets[-1])
+    h_s, h_t = RNG.normal(0, 1, (T, Hs)), RNG.normal(0, 1, (T, Ht))
+    window = np.array([2, 9])
+    for red in (O.RED_SEQ_MEAN, O.RED_SUM, O.RED_TOKEN_MEAN):
+        out = O.supervise(h_s, h_t, W_s, W_t, None, offsets, window, reduction=red, grad_scale=1.5,
+                          mode=O.MODE_PREFIX_AND_FULL, head_gradient=True)
+
+        def objectives(W):
+            o = O.supervise(h_s, h_t, W, W_t, None, offsets, window, reduction=red,
+                            mode=O.MODE_PREFIX_AND_FULL)
+            return o["batch"][0], o["batch"][1]
+        eps = 1e-6
+        for v, k in ((0, 0), (3, 2), (6, 3)):
+            E = np.zeros_like(W_s); E[v, k] = eps
+            (pp, fp), (pm, fm) = objectives(W_s + E), objectives(W_s - E)
+            assert out["dW_prefix"][v, k] == pytest.approx(1.5 * (pp - pm) / (2 * eps), rel=1e-6, abs=1e-9)
+            assert out["dW_full"][v, k] == pytest.approx(1.5 * (fp - fm) / (2 * eps), rel=1e-6, abs=1e-9)
+        assert np.allclose(out["dW_prefix"].sum(axis=0), 0, atol=1e-12)      # rows of dz sum to zero
+    # consistent with the hidden-state gradient: both are contractions of the same dz
+    out = O.supervise(h_s, h_t, W_s, W_t, None, offsets, window, reduction=O.RED_SUM,
+                      mode=O.MODE_PREFIX_AND_FULL, head_gradient=True)
+    x = RNG.normal(0, 1, V)       # x^T dW_full = sum_t (x . dz_t) h_s[t]; check through dz directly
+    dz = np.stack([O.token_dz(W_s @ h_s[t], W_t @ h_t[t]) for t in range(T)])
+    assert np.allclose(x @ out["dW_full"], (dz @ x) @ h_s, rtol=1e-12)
+    same = O.supervise(h_s, h_s, W_s, W_s, None, offsets, window, mode=O.MODE_PREFIX_AND_FULL,
+                       head_gradient=True)
+    assert np.abs(same["dW_full"]).max() < 1e-15
+    # the summand norm: one admitted token -> the norm is the summand itself; in general it lies
+    # between |dW| / sqrt(#summands) and the sum of magnitudes
+    one = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.array([1, 0]), reduction=O.RED_SUM,
+                      head_gradient=True)
+    assert np.allclose(one["dW_prefix_l2"], np.abs(one["dW_prefix"]), rtol=1e-12)
+    assert np.allclose(one["dW_prefix"], np.outer(dz[0], h_s[0]), rtol=1e-12)
+    l1 = np.abs(dz).T @ np.abs(h_s)
+    assert (out["dW_full_l2"] <= l1 + 1e-15).all()
+    assert (np.abs(out["dW_full"]) <= np.sqrt(T) * out["dW_full_l2"] + 1e-15).all()
+
+
 def test_teacher_diagnostics():
     assert O.teacher_branching_factor(np.zeros(37)) == pytest.approx(37.0, rel=1e-12)
     z = np.array([0.0, 50.0, 0.0])
