@@ -137,7 +137,10 @@ typedef struct adwin_opd_problem {
   int32_t estimator;         /* ADWIN_EST_EXPECTED | ADWIN_EST_SAMPLED                          */
   /* Gradients of the batch objectives with respect to the student LM-head weights (z = W h):
    * sum_t grad_scale * alpha_i * dz_t^T h_s[t], the third contraction of the LM-head backward.
-   * NULL = not wanted; each costs one more 2 V H_s FLOP per token.  Estimator EXPECTED only. */
+   * NULL = not wanted; each costs one more 2 V H_s FLOP per token.  Device, 16-byte aligned
+   * (else ADWIN_E_ALIGN), overwritten in full (zeros when no row is computed).  Estimator
+   * EXPECTED only, and dW_full only in mode PREFIX_AND_FULL (else ADWIN_E_MODE).  Each element
+   * is a sum over rows of products whose dz factor is rounded to bf16. */
   float* dW_prefix;          /* [V, H_s] prefix-window objective                                */
   float* dW_full;            /* [V, H_s] full-rollout objective (mode PREFIX_AND_FULL only)     */
 } adwin_opd_problem;
