@@ -414,3 +414,50 @@ def topk_survival(ranks_by_rollout, k, T):
     """S_T^(k): fraction of rollouts with every rank up to position T within top-k."""
     alive = [all(r <= k for r in ranks[:T]) for ranks in ranks_by_rollout]
     return float(np.mean(alive)) if alive else 0.0
+
+
+def first_rejection(ranks, k):
+    """Position (0-based) of a rollout's first top-k rejection, r_t > k; the number of positions
+    if there is none.  A rollout survives through position T (Sec. 3.1) iff this is >= T."""
+    for j, r in enumerate(ranks):
+        if r > k:
+            return j
+    return len(ranks)
+
+
+def region_means(values, offsets, n, computed):
+    """Mean of a per-token quantity over the window (positions j < n_i) and over the rest of
+    the computed positions (n_i <= j < computed_i) of every rollout -- the prefix / suffix
+    split of the teacher log-probability (App. C, cascading effect) -- and, last row, the same
+    over all rollouts' tokens.  An empty region has mean 0.  Returns [B + 1, 2]."""
+    B = len(n)
+    out = np.zeros((B + 1, 2))
+    tot = np.zeros(2)
+    cnt = np.zeros(2)
+    for i in range(B):
+        o = int(offsets[i])
+        regions = ((0, int(n[i])), (int(n[i]), int(computed[i])))
+        for c, (lo, hi) in enumerate(regions):
+            if hi > lo:
+                seg = np.asarray(values[o + lo:o + hi], dtype=np.float64)
+                out[i, c] = seg.sum() / (hi - lo)
+                tot[c] += seg.sum()
+                cnt[c] += hi - lo
+    for c in range(2):
+        out[B, c] = tot[c] / cnt[c] if cnt[c] > 0 else 0.0
+    return out
+
+
+def loss_share(kl, offsets, computed, candidates):
+    """Share of the batch's summed token loss that falls on positions j < L, for every L of
+    the list: the cumulative loss distribution over response positions (App. C, loss
+    distribution on prefix) read at the candidate windows.  0 when the total is 0."""
+    total = 0.0
+    part = np.zeros(len(candidates))
+    for i in range(len(computed)):
+        o, m = int(offsets[i]), int(computed[i])
+        seg = np.asarray(kl[o:o + m], dtype=np.float64)
+        total += seg.sum()
+        for k, L in enumerate(candidates):
+            part[k] += seg[:min(int(L), m)].sum()
+    return part / total if total != 0.0 else np.zeros(len(candidates))

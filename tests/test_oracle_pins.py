@@ -499,3 +499,34 @@ def test_teacher_diagnostics():
     assert O.topk_survival(ranks, 3, 2) == pytest.approx(2 / 3)
     assert O.topk_survival(ranks, 3, 4) == pytest.approx(1 / 3)
     assert O.topk_survival(ranks, 10, 4) == 1.0
+
+
+def test_rollout_summaries_of_the_diagnostics():
+    # first rejection <-> survival fraction: S_T^(k) = share of rollouts whose first rejection is >= T
+    g = np.random.default_rng(11)
+    ranks = [list(g.integers(1, 9, size=int(n))) for n in (5, 1, 9, 0, 7, 12)]
+    for k in (1, 3, 5, 8):
+        fr = [O.first_rejection(r, k) for r in ranks]
+        for T in range(0, 13):
+            assert O.topk_survival(ranks, k, T) == pytest.approx(np.mean([f >= min(T, len(r)) for f, r in zip(fr, ranks)]))
+    assert O.first_rejection([1, 2, 7, 1], 3) == 2 and O.first_rejection([1, 2, 3], 3) == 3
+    assert O.first_rejection([], 3) == 0 and O.first_rejection([9], 3) == 0
+    # region means: hand example, empty regions, batch row weighted by tokens
+    offsets = np.array([0, 4, 4, 7])
+    v = np.array([1.0, 3.0, 5.0, 7.0, 10.0, 20.0, 60.0])
+    m = O.region_means(v, offsets, n=[1, 0, 3], computed=[4, 0, 3])
+    assert np.allclose(m, [[1.0, 5.0], [0.0, 0.0], [30.0, 0.0], [(1 + 90) / 4, 5.0]])
+    m = O.region_means(v, offsets, n=[1, 0, 3], computed=[1, 0, 3])       # prefix-only: no suffix anywhere
+    assert np.allclose(m[:, 1], 0) and m[3, 0] == pytest.approx(91 / 4)
+    # loss share: uniform loss -> share of positions; monotone; 1 at L >= longest; hand example
+    lens = np.array([3, 10, 6]); off = np.concatenate([[0], np.cumsum(lens)])
+    cands = [1, 2, 4, 8, 16]
+    sh = O.loss_share(np.full(19, 0.25), off, lens, cands)
+    assert np.allclose(sh, [np.minimum(L, lens).sum() / 19 for L in cands])
+    kl = g.random(19)
+    sh = O.loss_share(kl, off, lens, cands)
+    assert np.all(np.diff(sh) >= 0) and sh[-1] == pytest.approx(1.0)
+    assert sh[0] == pytest.approx((kl[0] + kl[3] + kl[13]) / kl.sum())
+    assert not O.loss_share(np.zeros(19), off, lens, cands).any()
+    sh = O.loss_share(kl, off, [2, 0, 6], [1, 4])                         # computed rows only
+    assert sh[1] == pytest.approx((kl[0] + kl[1] + kl[13:17].sum()) / (kl[0] + kl[1] + kl[13:19].sum()))
