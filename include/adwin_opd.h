@@ -143,6 +143,21 @@ typedef struct adwin_opd_problem {
    * is a sum over rows of products whose dz factor is rounded to bf16. */
   float* dW_prefix;          /* [V, H_s] prefix-window objective                                */
   float* dW_full;            /* [V, H_s] full-rollout objective (mode PREFIX_AND_FULL only)     */
+  /* Rollout-level summaries of the per-row outputs over each rollout's computed positions
+   * (j < n_i; every position in mode PREFIX_AND_FULL).  Device pointers, NULL = not wanted.
+   * t_first_reject: Sec. 3.1 top-k rejection -- the survival fraction S_T^(k) is the share of
+   *   rollouts whose first rejection is at or beyond T.  Needs t_rank (else ADWIN_E_NULL) and
+   *   topk > 0 (else ADWIN_E_SHAPE).
+   * t_logp_mean: mean teacher log-probability of the sampled tokens inside the window and
+   *   beyond it (App. C, cascading effect on the suffix); an empty region gives 0.  Needs t_logp.
+   * cand_loss_share: share of the summed KL of all rows that lies on positions j < L_k, the
+   *   cumulative loss distribution over positions (App. C) read at the candidate windows;
+   *   0 when the total is 0.  Needs candidates (mode PREFIX_AND_FULL). */
+  int32_t topk;              /* k of the top-k rejection                                       */
+  int32_t* t_first_reject;   /* [B] first position j (0-based) with t_rank > topk; the number   */
+                             /*     of computed positions of the rollout if there is none      */
+  float* t_logp_mean;        /* [B + 1, 2] per rollout: window, beyond; row B: over all tokens  */
+  float* cand_loss_share;    /* [n_candidates]                                                  */
 } adwin_opd_problem;
 
 /*

@@ -46,6 +46,8 @@ class adwin_opd_problem(C.Structure):
         ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
         ("estimator", C.c_int32),
         ("dW_prefix", C.c_void_p), ("dW_full", C.c_void_p),
+        ("topk", C.c_int32), ("t_first_reject", C.c_void_p), ("t_logp_mean", C.c_void_p),
+        ("cand_loss_share", C.c_void_p),
     ]
 
 
@@ -211,7 +213,7 @@ class FusedCall:
 
     def __init__(self, h_s, h_t, W_s, W_t, ids, offsets, window, mode=ADWIN_PREFIX_ONLY,
                  reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0, dh_dtype=ADWIN_DT_F32,
-                 want=DEFAULT_OUTPUTS, device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED):
+                 want=DEFAULT_OUTPUTS, topk=0, device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.candidates = None if candidates is None else _host_i32(candidates)
         self.inputs = (h_s, h_t, W_s, W_t, ids)
@@ -228,6 +230,7 @@ class FusedCall:
         p.h_s, p.h_t, p.W_s, p.W_t, p.ids = _ptr(h_s), _ptr(h_t), _ptr(W_s), _ptr(W_t), _ptr(ids)
         p.mode, p.reduction, p.grad_scale, p.dh_dtype = mode, reduction, float(grad_scale), dh_dtype
         p.estimator = estimator
+        p.topk = int(topk)
         K = 0 if self.candidates is None else int(self.candidates.shape[0])
         if K:
             p.candidates, p.n_candidates = self.candidates.ctypes.data, K
@@ -247,6 +250,8 @@ class FusedCall:
                 "t_logp": ((T,), torch.float32), "t_entropy": ((T,), torch.float32),
                 "t_rank": ((T,), torch.int32),
                 "dW_prefix": ((V, H_s), torch.float32), "dW_full": ((V, H_s), torch.float32),
+                "t_first_reject": ((B,), torch.int32), "t_logp_mean": ((B + 1, 2), torch.float32),
+                "cand_loss_share": ((K,), torch.float32),
             }
             for k in want:
                 if k in ("dh_full", "dW_full") and mode != ADWIN_PREFIX_AND_FULL:

@@ -1373,7 +1373,7 @@ struct FusedLayout {
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, o_summ, total;
 };
 
 static int env_int(const char* name, int dflt) {
@@ -1471,6 +1471,8 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_dzT_p = take(p->dW_prefix ? 2 * (size_t)slab * v_img : 0);
   L.o_dzT_f = take(p->dW_full ? 2 * (size_t)slab * v_img : 0);
   L.o_hsT = take(head ? 2 * (size_t)h_tiles * kGradTile * (size_t)slab : 0);
+  L.o_summ = take((p->t_first_reject || p->t_logp_mean || p->cand_loss_share)
+                      ? sizeof(double) * (size_t)p->B * kSummarySlots : 0);
   L.total = o;
   return L;
 }
@@ -1496,6 +1498,10 @@ static int check_problem(const adwin_opd_problem* p) {
     for (int k = 0; k < p->n_candidates; ++k)
       if (p->candidates[k] <= 0) return ADWIN_E_WINDOW;
   }
+  if (p->t_first_reject && !p->t_rank) return ADWIN_E_NULL;
+  if (p->t_first_reject && p->topk <= 0) return ADWIN_E_SHAPE;
+  if (p->t_logp_mean && !p->t_logp) return ADWIN_E_NULL;
+  if (p->cand_loss_share && !(p->candidates && p->n_candidates > 0)) return ADWIN_E_NULL;
   return ADWIN_OK;
 }
 
@@ -1853,6 +1859,17 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     ca.uc = (float*)(ws + L.o_uc); ca.cacc = (double*)(ws + L.o_cacc); ca.cS = (double*)(ws + L.o_cS);
     ca.rho_pooled = p->cand_rho_pooled; ca.rho_field = p->cand_rho_field; ca.batch = p->cand_batch;
     ADWIN_HIP_TRY(launch_candidate_audit(ca, stream));
+  }
+  if (p->t_first_reject || p->t_logp_mean || p->cand_loss_share) {
+    SummaryArgs sa{};
+    sa.pl = pl; sa.B = p->B; sa.probe = probe; sa.topk = p->topk;
+    sa.K = p->cand_loss_share ? p->n_candidates : 0;
+    for (int k = 0; k < sa.K; ++k) sa.L[k] = p->candidates[k];
+    sa.t_rank = p->t_rank; sa.t_logp = p->t_logp;
+    sa.kl = klr;             // per computed row = per packed row in the full-rollout mode
+    sa.acc = (double*)(ws + L.o_summ);
+    sa.first_reject = p->t_first_reject; sa.logp_mean = p->t_logp_mean; sa.loss_share = p->cand_loss_share;
+    ADWIN_HIP_TRY(launch_summaries(sa, stream));
   }
   return ADWIN_OK;
 }

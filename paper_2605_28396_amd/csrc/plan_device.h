@@ -79,6 +79,26 @@ struct CandArgs {
 };
 hipError_t launch_candidate_audit(const CandArgs& a, hipStream_t st);
 
+// Rollout-level summaries of per-row outputs (Sec. 3.1 top-k rejection; App. C loss
+// distribution and prefix / suffix teacher log-probability).  Rows are packed positions;
+// rollout i's computed positions are j < computed_i = (probe ? len_i : n_i).
+struct SummaryArgs {
+  DevicePlan pl;
+  int32_t B, K;
+  int probe;
+  int32_t topk;
+  int32_t L[ADWIN_MAX_CANDIDATES];
+  const int32_t* t_rank;     // [T] or NULL
+  const float* t_logp;       // [T] or NULL
+  const float* kl;           // [T] or NULL
+  double* acc;               // [B][kSummarySlots] scratch
+  int32_t* first_reject;     // [B] or NULL (needs t_rank)
+  float* logp_mean;          // [B + 1][2] or NULL (needs t_logp)
+  float* loss_share;         // [K] or NULL (needs kl)
+};
+constexpr int kSummarySlots = ADWIN_MAX_CANDIDATES + 3;   // K candidate sums, total, logp prefix, logp suffix
+hipError_t launch_summaries(const SummaryArgs& a, hipStream_t st);
+
 // Optional per-phase timing with HIP events on the caller's stream (profiling entry
 // points only).  begin()/end() bracket one launch; collect() waits and sums per phase.
 class PhaseTimer {

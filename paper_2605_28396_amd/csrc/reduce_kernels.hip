@@ -357,9 +357,125 @@ __global__ __launch_bounds__(256) void cand_batch_kernel(CandArgs a) {
   }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Rollout-level summaries of the per-row outputs.  One workgroup per rollout; every thread
+// takes positions tid, tid + 256, ... in ascending order with double accumulators, and the
+// 256 partials are folded by a fixed tree, so the results do not depend on scheduling.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double block_sum_256(double v, double* sh) {
+  const int tid = threadIdx.x;
+  sh[tid] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) sh[tid] += sh[tid + s];
+    __syncthreads();
+  }
+  const double r = sh[0];
+  __syncthreads();
+  return r;
+}
+
+__global__ __launch_bounds__(256) void summary_rollout_kernel(SummaryArgs a) {
+  __shared__ double sh[256];
+  __shared__ int sh_first[256];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  const int64_t base = a.pl.offsets[i];
+  const int64_t len = a.pl.offsets[i + 1] - base;
+  const int64_t n = a.pl.n[i];
+  const int64_t m = a.probe ? len : n;          // computed positions of this rollout
+  double* acc = a.acc + (size_t)i * kSummarySlots;
+  if (a.first_reject) {
+    int64_t first = m;
+    for (int64_t j = tid; j < m; j += 256)
+      if (a.t_rank[base + j] > a.topk) { first = j; break; }
+    sh_first[tid] = (int)first;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+      if (tid < s) sh_first[tid] = min(sh_first[tid], sh_first[tid + s]);
+      __syncthreads();
+    }
+    if (tid == 0) a.first_reject[i] = sh_first[0];
+    __syncthreads();
+  }
+  if (a.logp_mean) {
+    double sp = 0.0, ss = 0.0;
+    for (int64_t j = tid; j < m; j += 256) {
+      const double v = (double)a.t_logp[base + j];
+      if (j < n) sp += v; else ss += v;
+    }
+    sp = block_sum_256(sp, sh);
+    ss = block_sum_256(ss, sh);
+    if (tid == 0) {
+      acc[ADWIN_MAX_CANDIDATES + 1] = sp;
+      acc[ADWIN_MAX_CANDIDATES + 2] = ss;
+      a.logp_mean[2 * i + 0] = n > 0 ? (float)(sp / (double)n) : 0.f;
+      a.logp_mean[2 * i + 1] = m > n ? (float)(ss / (double)(m - n)) : 0.f;
+    }
+  }
+  if (a.loss_share) {
+    double part[ADWIN_MAX_CANDIDATES];
+#pragma unroll
+    for (int k = 0; k < ADWIN_MAX_CANDIDATES; ++k) part[k] = 0.0;
+    double tot = 0.0;
+    for (int64_t j = tid; j < m; j += 256) {
+      const double v = (double)a.kl[base + j];
+      tot += v;
+#pragma unroll
+      for (int k = 0; k < ADWIN_MAX_CANDIDATES; ++k)
+        if (k < a.K && j < a.L[k]) part[k] += v;
+    }
+    tot = block_sum_256(tot, sh);
+    if (tid == 0) acc[ADWIN_MAX_CANDIDATES] = tot;
+#pragma unroll
+    for (int k = 0; k < ADWIN_MAX_CANDIDATES; ++k) {
+      if (k < a.K) {                              // uniform across the workgroup
+        const double r = block_sum_256(part[k], sh);
+        if (tid == 0) acc[k] = r;
+      }
+    }
+  }
+}
+
+// Batch rows of the summaries: sums over rollouts in index order.
+__global__ __launch_bounds__(64) void summary_batch_kernel(SummaryArgs a) {
+  const int tid = threadIdx.x;
+  if (a.loss_share && tid < a.K) {
+    double part = 0.0, tot = 0.0;
+    for (int i = 0; i < a.B; ++i) {
+      part += a.acc[(size_t)i * kSummarySlots + tid];
+      tot += a.acc[(size_t)i * kSummarySlots + ADWIN_MAX_CANDIDATES];
+    }
+    a.loss_share[tid] = tot != 0.0 ? (float)(part / tot) : 0.f;
+  }
+  if (a.logp_mean && tid >= 32 && tid < 34) {
+    const int c = tid - 32;
+    double sum = 0.0;
+    int64_t cnt = 0;
+    for (int i = 0; i < a.B; ++i) {
+      const int64_t len = a.pl.offsets[i + 1] - a.pl.offsets[i];
+      const int64_t n = a.pl.n[i], m = a.probe ? len : n;
+      sum += a.acc[(size_t)i * kSummarySlots + ADWIN_MAX_CANDIDATES + 1 + c];
+      cnt += c == 0 ? n : m - n;
+    }
+    a.logp_mean[2 * a.B + c] = cnt > 0 ? (float)(sum / (double)cnt) : 0.f;
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
+hipError_t launch_summaries(const SummaryArgs& a, hipStream_t st) {
+  if (!a.first_reject && !a.logp_mean && !a.loss_share) return hipSuccess;
+  summary_rollout_kernel<<<(unsigned)a.B, 256, 0, st>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.logp_mean || a.loss_share) {
+    summary_batch_kernel<<<1, 64, 0, st>>>(a);
+    e = hipGetLastError();
+  }
+  return e;
+}
 hipError_t launch_candidate_audit(const CandArgs& a, hipStream_t st) {
   if (a.K <= 0) return hipSuccess;
   cand_pool_kernel<<<dim3((unsigned)(a.K * a.B), (unsigned)((a.H + 255) / 256)), 256, 0, st>>>(a);

@@ -38,9 +38,12 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name, estimator):
     p = synth.hidden_problem(w, dev)
     probe = w.mode == synth.MODE_PREFIX_AND_FULL
     cands = list(O.CANDIDATE_WINDOWS) if probe else None
+    want = B.FusedCall.DEFAULT_OUTPUTS
+    if probe:       # the audit step also takes the teacher-side diagnostics and their summaries
+        want += ("t_logp", "t_entropy", "t_rank", "t_first_reject", "t_logp_mean", "cand_loss_share")
     call = B.FusedCall(p["h_s"], p["h_t"], p["W_s"], p["W_t"], p["ids"], w.offsets, w.window,
                        mode=w.mode, reduction=B.ADWIN_RED_SUM, dh_dtype=B.ADWIN_DT_F32,
-                       candidates=cands, estimator=estimator)
+                       candidates=cands, estimator=estimator, want=want, topk=20)
     st = call.run()
     assert st == 0, B.adwin_opd_strerror(st)
     torch.cuda.synchronize()
@@ -103,6 +106,26 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name, estimator):
         assert np.all(np.abs(cb[:, 2] - crp.mean(axis=1)) <= 1e-5)      # macro = mean over rollouts
         assert np.all(np.abs(cb[:, 3] - crf.mean(axis=1)) <= 1e-5)
         assert np.all(np.diff(crf, axis=0) >= -1e-6)                    # field cosine grows with L
+        # diagnostics on the sampled rows, their summaries by the oracle's reductions of the
+        # call's own per-row values
+        z_rows = synth.to_f64(p["h_t"][idx]) @ synth.to_f64(p["W_t"]).T
+        ids_rows = p["ids"][idx].cpu().numpy()
+        t_ent, t_lp, t_rk = (out[k][idx].cpu().numpy() for k in ("t_entropy", "t_logp", "t_rank"))
+        for q in range(0, len(rows), 8):
+            assert abs(t_ent[q] - O.teacher_entropy(z_rows[q])) <= 1e-3
+            lp = O.teacher_logp(z_rows[q], int(ids_rows[q]))
+            assert abs(t_lp[q] - lp) <= 1e-3 * max(1.0, abs(lp))
+            above = int(np.sum(z_rows[q] > z_rows[q][ids_rows[q]] + 1e-3))
+            near = int(np.sum(np.abs(z_rows[q] - z_rows[q][ids_rows[q]]) <= 1e-3))
+            assert above + 1 <= t_rk[q] <= above + near
+        del z_rows
+        rk = out["t_rank"].cpu().numpy()
+        fr = [O.first_rejection(rk[w.offsets[i]:w.offsets[i + 1]], 20) for i in range(w.B)]
+        assert np.array_equal(out["t_first_reject"].cpu().numpy(), fr)
+        ref_mean = O.region_means(out["t_logp"].double().cpu().numpy(), w.offsets, plan["n"], lens)
+        assert np.allclose(out["t_logp_mean"].cpu().numpy(), ref_mean, rtol=1e-5, atol=1e-5)
+        ref_share = O.loss_share(kl_gpu, w.offsets, lens, cands)
+        assert np.allclose(out["cand_loss_share"].cpu().numpy(), ref_share, rtol=1e-5, atol=1e-6)
         k2048 = cands.index(2048)                                       # the call's own window
         assert np.all(np.abs(crp[k2048] - rp) <= 1e-5)
         assert np.all(np.abs(cb[k2048] - out["batch"][2:6].cpu().numpy()) <= 1e-5)

@@ -376,3 +376,43 @@ def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
                for k, v in call.out.items()}
         _check_fused(w, got, ref, O.RED_SUM)
         _check_head_gradient(got, ref, True)
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_probe", "ragged_small", "ragged_mid"])
+def test_rollout_summaries(B, name):
+    """First top-k rejection, prefix / suffix means of the teacher log-probability and the loss
+    share inside every candidate window: the oracle's reductions applied to the call's own
+    per-row outputs (which the tests above compare with the oracle row by row), and against
+    the oracle end to end where no rank sits on a near-tie."""
+    w = synth.workload(name)
+    p = synth.hidden_problem(w)
+    probe = w.mode == synth.MODE_PREFIX_AND_FULL
+    cands = [1, 7, 64, 100, 300, 5000] if probe else None
+    want = B.FusedCall.DEFAULT_OUTPUTS + ("t_logp", "t_entropy", "t_rank", "t_first_reject", "t_logp_mean")
+    if probe:
+        want += ("cand_loss_share",)
+    K_TOP = 20                                     # the paper's evaluation-time top-k (Sec. 5.1)
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, want=want, topk=K_TOP, candidates=cands)
+    plan = O.plan(w.offsets, w.window)
+    lens = np.diff(w.offsets)
+    computed = lens if probe else plan["n"]
+    ranks = [got["t_rank"][w.offsets[i]:w.offsets[i] + computed[i]] for i in range(w.B)]
+    assert np.array_equal(got["t_first_reject"], [O.first_rejection(r, K_TOP) for r in ranks])
+    assert (got["t_first_reject"] < computed).any()          # the case has rejections at all
+    ref_mean = O.region_means(got["t_logp"].astype(np.float64), w.offsets, plan["n"], computed)
+    assert np.allclose(got["t_logp_mean"], ref_mean, rtol=1e-6, atol=1e-6)
+    if probe:
+        ref_share = O.loss_share(got["kl"].astype(np.float64), w.offsets, computed, cands)
+        assert np.allclose(got["cand_loss_share"], ref_share, rtol=1e-6, atol=1e-7)
+        assert got["cand_loss_share"][-1] == pytest.approx(1.0, abs=1e-6)
+        # end to end against the oracle: same tolerance class as the per-row quantities
+        f = Hp.oracle_inputs(p)
+        ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                          reduction=O.RED_SUM, mode=w.mode)
+        assert np.allclose(got["cand_loss_share"], O.loss_share(ref["kl"], w.offsets, computed, cands),
+                           rtol=Hp.KL_REL, atol=1e-6)
+        z_t = f["h_t"] @ f["W_t"].T
+        logp = np.array([O.teacher_logp(z_t[t], int(f["ids"][t])) for t in range(w.T)])
+        assert np.allclose(got["t_logp_mean"], O.region_means(logp, w.offsets, plan["n"], computed),
+                           rtol=1e-3, atol=1e-3)
+

@@ -128,6 +128,11 @@ def test_workspace_bytes_and_argument_errors_without_gpu(B):
     assert st_ws(_problem(B, dW_prefix=8192, estimator=B.ADWIN_EST_SAMPLED, ids=4096)) == B.ADWIN_E_MODE
     assert st_ws(_problem(B, mode=0, dW_full=8192)) == B.ADWIN_E_MODE
     assert st_ws(_problem(B, dW_prefix=8200)) == B.ADWIN_E_ALIGN
+    # rollout summaries need the per-row outputs they reduce
+    assert st(_problem(B, t_first_reject=4096, topk=5)) == B.ADWIN_E_NULL             # no t_rank
+    assert st(_problem(B, t_first_reject=4096, t_rank=4096, topk=0)) == B.ADWIN_E_SHAPE
+    assert st(_problem(B, t_logp_mean=4096)) == B.ADWIN_E_NULL                         # no t_logp
+    assert st(_problem(B, mode=1, cand_loss_share=4096)) == B.ADWIN_E_NULL             # no candidates
 
     lp = B.adwin_opd_logits_problem()
     lp.struct_bytes = C.sizeof(B.adwin_opd_logits_problem)
