@@ -113,7 +113,8 @@ typedef struct adwin_opd_problem {
   float* rho_pooled;         /* [B] cos(sum_t dh_prefix[t], sum_t dh_full[t]) over rollout i    */
   float* rho_field;          /* [B] cos of the two [len_i, H_s] gradient arrays of rollout i    */
   float* batch;              /* [8] L^p, L^f, pooled micro, field micro, pooled macro, field   */
-                             /*     macro, 0, 0 (alignment entries zero in PREFIX_ONLY)        */
+                             /*     macro, head-block cosine (see dW_full), 0; the alignment    */
+                             /*     entries are zero in PREFIX_ONLY                            */
   int32_t* n_out;            /* [B] n_i                                                        */
   int64_t* n_adm_out;        /* [1] N_adm = sum n_i                                            */
   uint32_t* status_dev;      /* [1] OR of ADWIN_DEV_* bits                                     */
@@ -140,7 +141,9 @@ typedef struct adwin_opd_problem {
    * NULL = not wanted; each costs one more 2 V H_s FLOP per token.  Device, 16-byte aligned
    * (else ADWIN_E_ALIGN), overwritten in full (zeros when no row is computed).  Estimator
    * EXPECTED only, and dW_full only in mode PREFIX_AND_FULL (else ADWIN_E_MODE).  Each element
-   * is a sum over rows of products whose dz factor is rounded to bf16. */
+   * is a sum over rows of products whose dz factor is rounded to bf16.  With both requested,
+   * batch[6] = cos(dW_prefix, dW_full): Sec. 4.2's alignment taken in the LM-head parameter
+   * block (0 if either is zero). */
   float* dW_prefix;          /* [V, H_s] prefix-window objective                                */
   float* dW_full;            /* [V, H_s] full-rollout objective (mode PREFIX_AND_FULL only)     */
   /* Rollout-level summaries of the per-row outputs over each rollout's computed positions

@@ -307,6 +307,9 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
         zero = np.zeros(W_s.shape)
         out["dW_prefix"] = dW[0] if dW is not None else zero
         out["dW_full"] = (dW[1] if dW is not None else zero) if mode == MODE_PREFIX_AND_FULL else zero
+        # alignment of the two objectives in the LM-head parameter block (Sec. 4.2's cosine taken
+        # over the one parameter block this path differentiates)
+        out["rho_head"] = cosine(out["dW_prefix"].ravel(), out["dW_full"].ravel())
         out["dW_prefix_l2"] = dW_l2[0] if dW is not None else zero
         out["dW_full_l2"] = (dW_l2[1] if dW is not None else zero) if mode == MODE_PREFIX_AND_FULL else zero
     return out

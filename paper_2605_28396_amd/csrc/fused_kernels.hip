@@ -1373,7 +1373,7 @@ struct FusedLayout {
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, o_summ, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, o_summ, o_cosp, total;
 };
 
 static int env_int(const char* name, int dflt) {
@@ -1471,6 +1471,7 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_dzT_p = take(p->dW_prefix ? 2 * (size_t)slab * v_img : 0);
   L.o_dzT_f = take(p->dW_full ? 2 * (size_t)slab * v_img : 0);
   L.o_hsT = take(head ? 2 * (size_t)h_tiles * kGradTile * (size_t)slab : 0);
+  L.o_cosp = take((p->dW_prefix && p->dW_full) ? sizeof(double) * 3 * kCosineBlocks : 0);
   L.o_summ = take((p->t_first_reject || p->t_logp_mean || p->cand_loss_share)
                       ? sizeof(double) * (size_t)p->B * kSummarySlots : 0);
   L.total = o;
@@ -1860,6 +1861,10 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     ca.rho_pooled = p->cand_rho_pooled; ca.rho_field = p->cand_rho_field; ca.batch = p->cand_batch;
     ADWIN_HIP_TRY(launch_candidate_audit(ca, stream));
   }
+  // alignment of the two objectives in the LM-head parameter block: batch[6]
+  if (p->dW_prefix && p->dW_full && p->batch)
+    ADWIN_HIP_TRY(launch_cosine(p->dW_prefix, p->dW_full, (int64_t)p->V * p->H_s,
+                                (double*)(ws + L.o_cosp), p->batch + 6, stream));
   if (p->t_first_reject || p->t_logp_mean || p->cand_loss_share) {
     SummaryArgs sa{};
     sa.pl = pl; sa.B = p->B; sa.probe = probe; sa.topk = p->topk;

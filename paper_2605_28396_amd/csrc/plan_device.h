@@ -99,6 +99,12 @@ struct SummaryArgs {
 constexpr int kSummarySlots = ADWIN_MAX_CANDIDATES + 3;   // K candidate sums, total, logp prefix, logp suffix
 hipError_t launch_summaries(const SummaryArgs& a, hipStream_t st);
 
+// Cosine of two fp32 arrays of n elements into *out (0 if either norm is 0): fixed partition
+// into kCosineBlocks contiguous pieces, double sums, pieces added in index order.
+constexpr int kCosineBlocks = 1024;
+hipError_t launch_cosine(const float* x, const float* y, int64_t n, double* partials /* [kCosineBlocks][3] */,
+                         float* out, hipStream_t st);
+
 // Optional per-phase timing with HIP events on the caller's stream (profiling entry
 // points only).  begin()/end() bracket one launch; collect() waits and sums per phase.
 class PhaseTimer {

@@ -463,8 +463,49 @@ __global__ __launch_bounds__(64) void summary_batch_kernel(SummaryArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Cosine of two long fp32 arrays (the two head-weight gradients).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void cosine_partial_kernel(const float* x, const float* y, int64_t n,
+                                                             double* partials) {
+  __shared__ double sh[256];
+  const int64_t per = (n + kCosineBlocks - 1) / kCosineBlocks;
+  const int64_t lo = (int64_t)blockIdx.x * per;
+  const int64_t hi = lo + per < n ? lo + per : n;
+  double xy = 0.0, xx = 0.0, yy = 0.0;
+  for (int64_t q = lo + threadIdx.x; q < hi; q += 256) {
+    const double a = (double)x[q], b = (double)y[q];
+    xy += a * b; xx += a * a; yy += b * b;
+  }
+  xy = block_sum_256(xy, sh);
+  xx = block_sum_256(xx, sh);
+  yy = block_sum_256(yy, sh);
+  if (threadIdx.x == 0) {
+    partials[3 * blockIdx.x + 0] = xy;
+    partials[3 * blockIdx.x + 1] = xx;
+    partials[3 * blockIdx.x + 2] = yy;
+  }
+}
+
+__global__ void cosine_final_kernel(const double* partials, float* out) {
+  if (threadIdx.x != 0) return;
+  double xy = 0.0, xx = 0.0, yy = 0.0;
+  for (int b = 0; b < kCosineBlocks; ++b) {
+    xy += partials[3 * b + 0]; xx += partials[3 * b + 1]; yy += partials[3 * b + 2];
+  }
+  *out = (xx > 0.0 && yy > 0.0) ? (float)(xy / (sqrt(xx) * sqrt(yy))) : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
+hipError_t launch_cosine(const float* x, const float* y, int64_t n, double* partials, float* out,
+                         hipStream_t st) {
+  cosine_partial_kernel<<<kCosineBlocks, 256, 0, st>>>(x, y, n, partials);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  cosine_final_kernel<<<1, 64, 0, st>>>(partials, out);
+  return hipGetLastError();
+}
 hipError_t launch_summaries(const SummaryArgs& a, hipStream_t st) {
   if (!a.first_reject && !a.logp_mean && !a.loss_share) return hipSuccess;
   summary_rollout_kernel<<<(unsigned)a.B, 256, 0, st>>>(a);

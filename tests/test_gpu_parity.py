@@ -339,6 +339,11 @@ def _check_head_gradient(got, ref, probe):
         assert err.max() <= 2.0 ** -7 * scale
         # every dz row sums to zero over the vocabulary, so every column of dW does
         assert np.abs(got[k].astype(np.float64).sum(axis=0)).max() <= 1e-3 * np.abs(got[k]).sum(axis=0).max()
+    if probe:      # the two objectives' alignment in the LM-head parameter block
+        assert abs(got["batch"][6] - ref["rho_head"]) <= Hp.RHO_ABS, (got["batch"][6], ref["rho_head"])
+        assert 0.0 < ref["rho_head"] < 1.0
+    else:
+        assert got["batch"][6] == 0
 
 
 @pytest.mark.parametrize("name,reduction", [("tiny_probe", O.RED_SUM), ("ragged_small", O.RED_SEQ_MEAN),

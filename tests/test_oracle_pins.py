@@ -530,3 +530,32 @@ def test_rollout_summaries_of_the_diagnostics():
     assert not O.loss_share(np.zeros(19), off, lens, cands).any()
     sh = O.loss_share(kl, off, [2, 0, 6], [1, 4])                         # computed rows only
     assert sh[1] == pytest.approx((kl[0] + kl[1] + kl[13:17].sum()) / (kl[0] + kl[1] + kl[13:19].sum()))
+
+
+def test_head_block_alignment():
+    # rho_head = cos(dW_prefix, dW_full): pinned through the Gram identity
+    # <dW_p, dW_f> = sum_{r, r'} w^p_r w^f_r' (dz_r . dz_r') (h_r . h_r'), never forming dW
+    V, Hs, Ht = 9, 5, 4
+    W_s, W_t = RNG.normal(0, 0.7, (V, Hs)), RNG.normal(0, 0.7, (V, Ht))
+    lens = np.array([4, 6, 2]); offsets = np.concatenate([[0], np.cumsum(lens)]); T = int(offsets[-1])
+    h_s, h_t = RNG.normal(0, 1, (T, Hs)), RNG.normal(0, 1, (T, Ht))
+    window = np.array([2, 3, 0])
+    out = O.supervise(h_s, h_t, W_s, W_t, None, offsets, window, reduction=O.RED_SEQ_MEAN, grad_scale=2.0,
+                      mode=O.MODE_PREFIX_AND_FULL, head_gradient=True)
+    dz = np.stack([O.token_dz(W_s @ h_s[t], W_t @ h_t[t]) for t in range(T)])
+    ap, af = O.row_weights(lens, np.minimum(window, lens), O.RED_SEQ_MEAN)
+    wp, wf = np.zeros(T), np.zeros(T)
+    for i in range(3):
+        o = offsets[i]
+        wp[o:o + min(window[i], lens[i])] = ap[i]
+        wf[o:o + lens[i]] = af[i]
+    G = (dz @ dz.T) * (h_s @ h_s.T)
+    want = (wp @ G @ wf) / math.sqrt((wp @ G @ wp) * (wf @ G @ wf))
+    assert out["rho_head"] == pytest.approx(want, rel=1e-10)
+    # the window covers everything -> the two objectives coincide
+    full = O.supervise(h_s, h_t, W_s, W_t, None, offsets, lens + 3, mode=O.MODE_PREFIX_AND_FULL,
+                       head_gradient=True)
+    assert full["rho_head"] == pytest.approx(1.0, abs=1e-12)
+    none = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.zeros(3, int), mode=O.MODE_PREFIX_AND_FULL,
+                       head_gradient=True)
+    assert none["rho_head"] == 0.0
