@@ -137,7 +137,8 @@ def token_terms(h_s, h_t, W_s, W_t, y=None, estimator=EST_EXPECTED):
     return kl, c, g
 
 
-def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, head_weights=None):
+def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, head_weights=None,
+               g_norms=None):
     """`token_terms` for a stack of independent rows.  Rows are batched through one
     matrix product per block only to let BLAS do the inner products; each row's
     softmax/KL/gradient is the single-row definition above.
@@ -147,7 +148,9 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, h
     (z = W h, so d z[v] / d W[v, k] = h[k]), is returned as a fourth value, and as a fifth the
     Euclidean norm over r of the summands of each element, sqrt(sum_r (w[r] dz_r[v] h_s[r][k])^2):
     the scale of the rounding error of any implementation that rounds the factors of the
-    summands independently (tests bound a reduced-precision result with it)."""
+    summands independently (tests bound a reduced-precision result with it).
+    g_norms: optional [K, H_s] array that receives the same norm for the hidden-state gradient,
+    sqrt(sum_v (dz_r[v] W_s[v][k])^2)."""
     K = H_s.shape[0]
     kl = np.zeros(K)
     c = np.zeros(K)
@@ -169,6 +172,8 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, h
             else:
                 D[r - r0] = token_dz_sampled(z_s, z_t, int(ids[r]))
         g[r0:r1] = D @ W_s
+        if g_norms is not None:
+            g_norms[r0:r1] = np.sqrt((D ** 2) @ (W_s ** 2))
         if dW is not None:
             for k, w in enumerate(head_weights):
                 wD = D * np.asarray(w)[r0:r1, None]
@@ -271,12 +276,14 @@ def window_outputs(kl, g, offsets, window, reduction=RED_SEQ_MEAN, grad_scale=1.
 
 def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
               grad_scale=1.0, mode=MODE_PREFIX_ONLY, estimator=EST_EXPECTED, head_gradient=False,
-              block=16):
+              block=16, summand_norms=False):
     """Whole path from hidden states (fp64 arrays holding the bf16-exact inputs).
     head_gradient: also dW_prefix / dW_full, the gradients of the prefix and full-rollout
     batch objectives (times grad_scale) with respect to the student LM-head weights, and
     dW_prefix_l2 / dW_full_l2, the Euclidean norms of their per-token summands.
-    block: rows per library matrix product in `rows_terms` (batching only)."""
+    block: rows per library matrix product in `rows_terms` (batching only).
+    summand_norms: also g_l2 [T, H_s], the Euclidean norm over the vocabulary of the summands
+    dz_t[v] W_s[v][k] of every element of g (0 on rows not computed)."""
     p = plan(offsets, window)
     T = int(offsets[-1])
     if mode == MODE_PREFIX_AND_FULL:
@@ -286,6 +293,8 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
     kl, c, g = np.zeros(T), np.zeros(T), np.zeros((T, W_s.shape[1]))
     dW = dW_l2 = None
     hw = None
+    g_l2 = np.zeros((T, W_s.shape[1])) if summand_norms else None
+    gn = np.zeros((len(rows), W_s.shape[1])) if summand_norms else None
     if head_gradient:
         ap, af = row_weights(p["len"], p["n"], reduction)
         wp, wf = np.zeros(T), np.zeros(T)
@@ -297,12 +306,16 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
     if len(rows):
         res = rows_terms(h_s[rows], h_t[rows], W_s, W_t,
                          None if ids is None else np.asarray(ids)[rows], block=block,
-                         estimator=estimator, head_weights=hw)
+                         estimator=estimator, head_weights=hw, g_norms=gn)
+        if summand_norms:
+            g_l2[rows] = gn
         kl[rows], c[rows], g[rows] = res[0], res[1], res[2]
         if head_gradient:
             dW, dW_l2 = res[3], res[4]
     out = window_outputs(kl, g, offsets, window, reduction, grad_scale, mode)
     out.update(kl=kl, c=c, g=g, rows=rows)
+    if summand_norms:
+        out["g_l2"] = g_l2
     if head_gradient:
         zero = np.zeros(W_s.shape)
         out["dW_prefix"] = dW[0] if dW is not None else zero

@@ -421,3 +421,40 @@ def test_rollout_summaries(B, name):
         assert np.allclose(got["t_logp_mean"], O.region_means(logp, w.offsets, plan["n"], computed),
                            rtol=1e-3, atol=1e-3)
 
+
+
+@pytest.mark.parametrize("V,H_s,H_t,lens,win", [
+    (8, 64, 64, [1], [1]),                        # the smallest legal problem: one token, 8 entries
+    (40, 64, 128, [1, 3, 2], [1, 2, 5]),          # below one vocabulary tile, H below the image path
+    (136, 128, 192, [5, 1], [3, 1]),              # one full vocabulary tile plus a tail of 8
+    (264, 320, 128, [300], [257]),                # a window ending one row into the second token tile
+])
+def test_minimal_and_odd_shapes(B, V, H_s, H_t, lens, win):
+    for mode in (synth.MODE_PREFIX_ONLY, synth.MODE_PREFIX_AND_FULL):
+        w = synth.Workload(f"odd_{V}_{H_s}_{H_t}", V, H_s, H_t, synth._offsets(lens),
+                           np.array(win, np.int32), mode)
+        p = synth.hidden_problem(w)
+        f = Hp.oracle_inputs(p)
+        ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                          reduction=O.RED_SUM, mode=mode, summand_norms=True)
+        got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32)
+        # A gradient element sums only V terms here, too few for the fraction-of-maximum bound
+        # (stated for vocabularies where rounding averages out) to have its statistical margin:
+        # bound every element by its own summands instead, as for the head-weight gradient.
+        adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
+        for k, mask in (("dh_prefix", adm), ("dh_full", np.ones(w.T, bool))):
+            if k == "dh_full" and mode != synth.MODE_PREFIX_AND_FULL:
+                continue
+            tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask[:, None] + 1e-6 * np.abs(ref[k]).max()
+            err = np.abs(got[k] - ref[k])
+            assert (err <= tol).all(), (k, err.max(), (err / tol).max())
+            got[k] = ref[k]                      # checked; the remaining checks use the standard bar
+        _check_fused(w, got, ref, O.RED_SUM)
+    lo = synth.logits_problem(w)
+    fl = Hp.oracle_inputs(lo)
+    d = {k: v.cuda() for k, v in lo.items()}
+    out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window, reduction=O.RED_SUM)
+    torch.cuda.synchronize()
+    refl = O.supervise_from_logits(fl["z_s"], fl["z_t"], fl["ids"], w.offsets, w.window, reduction=O.RED_SUM)
+    Hp.assert_kl(out["kl"].cpu().numpy(), refl["kl"])
+    Hp.assert_grad(out["dz"].float().cpu().numpy(), refl["dz"], "dz", Hp.BF16_ULP)

@@ -559,3 +559,18 @@ def test_head_block_alignment():
     none = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.zeros(3, int), mode=O.MODE_PREFIX_AND_FULL,
                        head_gradient=True)
     assert none["rho_head"] == 0.0
+
+
+def test_summand_norms_of_the_hidden_gradient():
+    V, Hs, Ht = 6, 3, 4
+    W_s, W_t = RNG.normal(0, 0.7, (V, Hs)), RNG.normal(0, 0.7, (V, Ht))
+    offsets = np.array([0, 3]); h_s, h_t = RNG.normal(0, 1, (3, Hs)), RNG.normal(0, 1, (3, Ht))
+    out = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.array([2]), summand_norms=True)
+    for t in range(3):
+        dz = O.token_dz(W_s @ h_s[t], W_t @ h_t[t])
+        for k in range(Hs):
+            terms = dz * W_s[:, k]
+            want = math.sqrt(sum(x * x for x in terms)) if t < 2 else 0.0
+            assert out["g_l2"][t, k] == pytest.approx(want, rel=1e-12)
+            if t < 2:
+                assert abs(out["g"][t, k]) <= math.sqrt(V) * out["g_l2"][t, k] + 1e-15
