@@ -1218,7 +1218,11 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
           const int64_t r = out_row0 + wm * 128 + fm * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
           if (r < a.out_rows) {
             float* o = g + r * a.H + h;
-            *o = a.accumulate ? *o + acc[fm][fn][e] : acc[fm][fn][e];
+            // accumulate: every element is added to by exactly one lane of this launch and
+            // launches are ordered on the stream, so the hardware add keeps the sum
+            // deterministic while sparing the lane the round trip of a load
+            if (a.accumulate) unsafeAtomicAdd(o, acc[fm][fn][e]);
+            else *o = acc[fm][fn][e];
           }
         }
       }
