@@ -374,6 +374,7 @@ def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
     f = Hp.oracle_inputs(p)
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
                       reduction=O.RED_SUM, mode=w.mode, head_gradient=True)
+    first = None
     for _ in range(2):          # a second run over the same buffers overwrites, never adds to, the first
         assert call.run() == 0
         torch.cuda.synchronize()
@@ -381,6 +382,10 @@ def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
                for k, v in call.out.items()}
         _check_fused(w, got, ref, O.RED_SUM)
         _check_head_gradient(got, ref, True)
+        if first is None:
+            first = got
+    for k in ("dW_prefix", "dW_full", "dh_full", "kl", "batch"):      # and reproduces it bit for bit
+        assert np.array_equal(first[k], got[k]), k
 
 
 @pytest.mark.parametrize("name", ["tiny", "tiny_probe", "ragged_small", "ragged_mid"])
