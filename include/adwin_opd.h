@@ -193,6 +193,10 @@ typedef struct adwin_opd_logits_problem {
   float* t_entropy;          /* [T]                                                            */
   int32_t* t_rank;           /* [T]                                                            */
   int32_t estimator;         /* ADWIN_EST_EXPECTED | ADWIN_EST_SAMPLED: what dz carries         */
+  /* rollout-level summaries over the admitted positions (see adwin_opd_problem)                */
+  int32_t topk;              /* > 0 when t_first_reject is wanted                              */
+  int32_t* t_first_reject;   /* [B] needs t_rank                                               */
+  float* t_logp_mean;        /* [B + 1, 2] needs t_logp; the second column is 0 on this path    */
 } adwin_opd_logits_problem;
 
 /* Library version: major*10000 + minor*100 + patch.  Pure host. */

@@ -62,6 +62,7 @@ class adwin_opd_logits_problem(C.Structure):
         ("n_out", C.c_void_p), ("n_adm_out", C.c_void_p), ("status_dev", C.c_void_p),
         ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
         ("estimator", C.c_int32),
+        ("topk", C.c_int32), ("t_first_reject", C.c_void_p), ("t_logp_mean", C.c_void_p),
     ]
 
 
@@ -315,7 +316,7 @@ class LogitsCall:
 
     def __init__(self, z_s, z_t, ids, offsets, window, reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0,
                  want=("kl", "c", "dz", "loss_prefix", "batch", "n_out", "n_adm_out", "status_dev"),
-                 allocate=True, estimator=ADWIN_EST_EXPECTED):
+                 allocate=True, estimator=ADWIN_EST_EXPECTED, topk=0):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.inputs = (z_s, z_t, ids)
         B = int(self.window.shape[0])
@@ -328,12 +329,14 @@ class LogitsCall:
         p.z_s, p.z_t, p.ids = _ptr(z_s), _ptr(z_t), _ptr(ids)
         p.reduction, p.grad_scale = reduction, float(grad_scale)
         p.estimator = estimator
+        p.topk = int(topk)
         self.p = p
         self.out = {}
         self.workspace = None
         self.workspace_bytes = 0
         if allocate:
             shapes = {
+                "t_first_reject": ((B,), torch.int32), "t_logp_mean": ((B + 1, 2), torch.float32),
                 "kl": ((T,), torch.float32), "c": ((T,), torch.float32),
                 "dz": ((T, V), torch.bfloat16), "loss_prefix": ((B,), torch.float32),
                 "batch": ((8,), torch.float32), "n_out": ((B,), torch.int32),

@@ -418,13 +418,14 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
 }
 
 struct LogitsLayout {
-  size_t o_plan, o_klr, o_seg, o_racc, total;
+  size_t o_plan, o_klr, o_seg, o_racc, o_summ, total;
   LogitsLayout(int32_t B, int64_t T) {
     size_t o = 0;
     o_plan = o; o += PlanBlobLayout(B).bytes;
     o_klr = o;  o = align_up(o + sizeof(float) * (size_t)(T > 0 ? T : 1), 256);
     o_seg = o;  o = align_up(o + sizeof(double) * 4 * (size_t)B, 256);
     o_racc = o; o = align_up(o + sizeof(double) * 4 * (size_t)B, 256);
+    o_summ = o; o = align_up(o + sizeof(double) * kSummarySlots * (size_t)B, 256);
     total = o;
   }
 };
@@ -438,6 +439,9 @@ static int check_logits_problem(const adwin_opd_logits_problem* p) {
   if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
   if (p->estimator != ADWIN_EST_EXPECTED && p->estimator != ADWIN_EST_SAMPLED) return ADWIN_E_MODE;
   if (p->estimator == ADWIN_EST_SAMPLED && !p->ids) return ADWIN_E_NULL;
+  if (p->t_first_reject && !p->t_rank) return ADWIN_E_NULL;
+  if (p->t_first_reject && p->topk <= 0) return ADWIN_E_SHAPE;
+  if (p->t_logp_mean && !p->t_logp) return ADWIN_E_NULL;
   return ADWIN_OK;
 }
 
@@ -505,6 +509,14 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
   b.rho_pooled = nullptr; b.rho_field = nullptr; b.batch = p->batch;
   b.n_out = p->n_out; b.n_adm_out = p->n_adm_out; b.n_adm = hp.n_adm;
   ADWIN_HIP_TRY(launch_alignment_and_batch(b, stream));
+  if (p->t_first_reject || p->t_logp_mean) {
+    SummaryArgs sa{};
+    sa.pl = pl; sa.B = p->B; sa.probe = 0; sa.topk = p->topk; sa.K = 0;
+    sa.t_rank = p->t_rank; sa.t_logp = p->t_logp; sa.kl = nullptr;
+    sa.acc = (double*)(ws + L.o_summ);
+    sa.first_reject = p->t_first_reject; sa.logp_mean = p->t_logp_mean; sa.loss_share = nullptr;
+    ADWIN_HIP_TRY(launch_summaries(sa, stream));
+  }
   return ADWIN_OK;
 }
 

@@ -234,9 +234,9 @@ def test_teacher_diagnostics_from_logits_exact_rank(B):
     f = Hp.oracle_inputs(p)
     d = {k: v.cuda() for k, v in p.items()}
     want = ("kl", "c", "dz", "loss_prefix", "batch", "n_out", "n_adm_out", "status_dev",
-            "t_logp", "t_entropy", "t_rank")
+            "t_logp", "t_entropy", "t_rank", "t_first_reject", "t_logp_mean")
     out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window,
-                                  reduction=O.RED_SUM, want=want)
+                                  reduction=O.RED_SUM, want=want, topk=2000)
     torch.cuda.synchronize()
     got = {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
            for k, v in out.items()}
@@ -251,6 +251,14 @@ def test_teacher_diagnostics_from_logits_exact_rank(B):
         assert abs(got["t_logp"][t] - O.teacher_logp(z, y)) <= 1e-4 * max(1.0, abs(O.teacher_logp(z, y)))
     other = np.setdiff1d(np.arange(w.T), rows)
     assert not got["t_entropy"][other].any() and not got["t_rank"][other].any()
+    # rollout summaries over the admitted positions (ranks are exact here, so end to end);
+    # ids are uniform, so ranks are too: k = 2000 of 8000 rejects most rollouts somewhere
+    n = O.plan(w.offsets, w.window)["n"]
+    fr = [O.first_rejection([O.teacher_rank(f["z_t"][t], int(f["ids"][t])) for t in range(w.offsets[i], w.offsets[i] + n[i])],
+                            2000) for i in range(w.B)]
+    assert np.array_equal(got["t_first_reject"], fr) and (np.array(fr) < n).any()
+    logp = np.array([O.teacher_logp(f["z_t"][t], int(f["ids"][t])) for t in range(w.T)])
+    assert np.allclose(got["t_logp_mean"], O.region_means(logp, w.offsets, n, n), rtol=1e-4, atol=1e-4)
 
 
 @pytest.mark.parametrize("name,reduction", [("tiny", O.RED_SUM), ("tiny_probe", O.RED_SEQ_MEAN),

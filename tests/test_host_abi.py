@@ -142,6 +142,13 @@ def test_workspace_bytes_and_argument_errors_without_gpu(B):
     assert B.adwin_opd_logits_workspace_bytes(lp) > 0
     lp.V = 4095
     assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_SHAPE
+    lp.V = 4096
+    lp.t_first_reject, lp.topk = 4096, 3
+    assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_NULL      # no t_rank
+    lp.t_rank, lp.topk = 4096, 0
+    assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_SHAPE
+    lp.topk, lp.t_logp_mean = 3, 4096
+    assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_NULL      # no t_logp
 
 
 def test_scheduler_functions_match_oracle(B):
