@@ -471,3 +471,34 @@ def test_minimal_and_odd_shapes(B, V, H_s, H_t, lens, win):
     refl = O.supervise_from_logits(fl["z_s"], fl["z_t"], fl["ids"], w.offsets, w.window, reduction=O.RED_SUM)
     Hp.assert_kl(out["kl"].cpu().numpy(), refl["kl"])
     Hp.assert_grad(out["dz"].float().cpu().numpy(), refl["dz"], "dz", Hp.BF16_ULP)
+
+
+def test_every_output_is_optional(B):
+    """NULL for an output means not wanted: each output alone equals the same output of a call
+    that asks for everything."""
+    w = synth.workload("ragged_small")
+    p = synth.hidden_problem(w)
+    d = {k: v.cuda() for k, v in p.items()}
+    cands = [16, 200]
+    everything = B.FusedCall.DEFAULT_OUTPUTS + ("t_logp", "t_entropy", "t_rank")
+
+    def run(want):
+        out = B.adwin_opd_fused(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window,
+                                mode=w.mode, want=want, candidates=cands)
+        torch.cuda.synchronize()
+        return {k: v.clone() for k, v in out.items()}
+    full = run(everything)
+    for k in everything:
+        alone = run((k,))
+        assert torch.equal(alone[k], full[k]), k
+    lo = synth.logits_problem(w)
+    dl = {k: v.cuda() for k, v in lo.items()}
+    all_l = ("kl", "c", "dz", "loss_prefix", "batch", "n_out", "n_adm_out", "status_dev")
+    full_l = B.adwin_opd_from_logits(dl["z_s"], dl["z_t"], dl["ids"], w.offsets, w.window, want=all_l)
+    torch.cuda.synchronize()
+    for k in all_l:
+        alone = B.adwin_opd_from_logits(dl["z_s"], dl["z_t"], dl["ids"], w.offsets, w.window, want=(k,))
+        torch.cuda.synchronize()
+        a, b = alone[k], full_l[k]
+        assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                           b.view(torch.int16) if b.dtype == torch.bfloat16 else b), k
