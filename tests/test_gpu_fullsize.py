@@ -41,6 +41,9 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name, estimator):
     want = B.FusedCall.DEFAULT_OUTPUTS
     if probe:       # the audit step also takes the teacher-side diagnostics and their summaries
         want += ("t_logp", "t_entropy", "t_rank", "t_first_reject", "t_logp_mean", "cand_loss_share")
+    head = estimator == 0 and name in ("strong_to_weak", "probe_alignment")
+    if head:        # the head-weight gradient(s) over all slabs, checked by identities below
+        want += ("dW_prefix", "dW_full") if probe else ("dW_prefix",)
     call = B.FusedCall(p["h_s"], p["h_t"], p["W_s"], p["W_t"], p["ids"], w.offsets, w.window,
                        mode=w.mode, reduction=B.ADWIN_RED_SUM, dh_dtype=B.ADWIN_DT_F32,
                        candidates=cands, estimator=estimator, want=want, topk=20)
@@ -76,6 +79,27 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name, estimator):
         assert not bool(out["dh_prefix"][oi].any())
         if not probe:
             assert not bool(out["kl"][oi].any()) and not bool(out["c"][oi].any())
+    if head:
+        # dW and dh contract the same dz: <dW, W_s> = sum_t <dh[t], h_s[t]> (both sides are
+        # sum_t w_t dz_t W_s h_s[t]); dh is compared with the oracle above, so this ties every
+        # slab and tile of the third contraction to it.  Every dz row sums to zero, so every
+        # column of dW does.
+        for kW, kh in (("dW_prefix", "dh_prefix"), ("dW_full", "dh_full")) if probe else (("dW_prefix", "dh_prefix"),):
+            dW = out[kW]
+            lhs = float((dW.double() * p["W_s"].double()).sum())
+            prod = out[kh].double() * p["h_s"].double()
+            rhs, scale = float(prod.sum()), float(prod.abs().sum())
+            del prod
+            assert abs(lhs - rhs) <= 1e-3 * abs(rhs) + 1e-6 * scale, (kW, lhs, rhs, scale)
+            assert abs(rhs) > 1e-3 * scale          # the identity is not a comparison of two noises
+            col = dW.double().sum(dim=0).abs().max()
+            assert float(col) <= 1e-3 * float(dW.double().abs().sum(dim=0).max()), kW
+            del dW
+        if probe:   # the two objectives' alignment in the head block, from the call's own gradients
+            a, b = out["dW_prefix"].double(), out["dW_full"].double()
+            cos = float((a * b).sum() / (a.norm() * b.norm()))
+            del a, b
+            assert abs(float(out["batch"][6]) - cos) <= 1e-5 and 0.0 < cos < 1.0
     # reduction parity: the oracle's window reduction applied to the GPU's per-row values
     kl_gpu = out["kl"].double().cpu().numpy()
     if probe:
