@@ -117,6 +117,20 @@ def token_dz(z_s, z_t):
     return p * (delta - np.sum(p * delta))
 
 
+def token_dz_scale(z_s, z_t):
+    """Magnitude against which a reduced-precision dz_t is to be judged, per entry:
+    p_s (|Delta - KL_t| + D_t) with D_t the standard deviation of Delta under p_s.  An
+    implementation that holds p_s and the centred Delta as separate rounded factors, centred at
+    any p_s-weighted mean of Delta over part of the vocabulary, makes errors proportional to this
+    and not to |dz_t|, which vanishes wherever Delta happens to equal KL_t."""
+    ls, lt = log_softmax(z_s), log_softmax(z_t)
+    p = np.exp(ls)
+    delta = ls - lt
+    kl = np.sum(p * delta)
+    dev = np.sqrt(np.sum(p * (delta - kl) ** 2))
+    return p * (np.abs(delta - kl) + dev)
+
+
 def token_dz_sampled(z_s, z_t, y):
     """The per-token term of the gamma = 0 estimator (Eq. 4) in logit space:
     c_t * d log p_s(y_t) / d z_s = c_t (e_{y_t} - p_s), with c_t held constant."""
@@ -146,22 +160,25 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, h
     head_weights: optional list of per-row weight vectors w; for each one the gradient of
     sum_r w[r] KL_r with respect to the student LM-head weights, sum_r w[r] dz_r^T h_s[r]
     (z = W h, so d z[v] / d W[v, k] = h[k]), is returned as a fourth value, and as a fifth the
-    Euclidean norm over r of the summands of each element, sqrt(sum_r (w[r] dz_r[v] h_s[r][k])^2):
-    the scale of the rounding error of any implementation that rounds the factors of the
-    summands independently (tests bound a reduced-precision result with it).
+    Euclidean norm over r of the summands of each element, sqrt(sum_r (w[r] s_r[v] h_s[r][k])^2),
+    with s_r = `token_dz_scale` (expected estimator) or |dz_r| (sampled): the scale of the
+    rounding error of any implementation that rounds the factors of the summands independently
+    (tests bound a reduced-precision result with it).
     g_norms: optional [K, H_s] array that receives the same norm for the hidden-state gradient,
-    sqrt(sum_v (dz_r[v] W_s[v][k])^2)."""
+    sqrt(sum_v (s_r[v] W_s[v][k])^2)."""
     K = H_s.shape[0]
     kl = np.zeros(K)
     c = np.zeros(K)
     g = np.zeros((K, W_s.shape[1]))
     dW = None if head_weights is None else [np.zeros(W_s.shape) for _ in head_weights]
     dW_sq = None if head_weights is None else [np.zeros(W_s.shape) for _ in head_weights]
+    want_norms = g_norms is not None or head_weights is not None
     for r0 in range(0, K, block):
         r1 = min(K, r0 + block)
         Z_s = H_s[r0:r1] @ W_s.T
         Z_t = H_t[r0:r1] @ W_t.T
         D = np.empty_like(Z_s)
+        S = np.empty_like(Z_s) if want_norms else None
         for r in range(r0, r1):
             z_s, z_t = Z_s[r - r0], Z_t[r - r0]
             kl[r] = token_kl(z_s, z_t)
@@ -169,16 +186,21 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, h
                 c[r] = token_cost(z_s, z_t, int(ids[r]))
             if estimator == EST_EXPECTED:
                 D[r - r0] = token_dz(z_s, z_t)
+                if want_norms:
+                    S[r - r0] = token_dz_scale(z_s, z_t)
             else:
                 D[r - r0] = token_dz_sampled(z_s, z_t, int(ids[r]))
+                if want_norms:
+                    S[r - r0] = np.abs(D[r - r0])
         g[r0:r1] = D @ W_s
         if g_norms is not None:
-            g_norms[r0:r1] = np.sqrt((D ** 2) @ (W_s ** 2))
+            g_norms[r0:r1] = np.sqrt((S ** 2) @ (W_s ** 2))
         if dW is not None:
             for k, w in enumerate(head_weights):
                 wD = D * np.asarray(w)[r0:r1, None]
                 dW[k] += wD.T @ H_s[r0:r1]
-                dW_sq[k] += (wD ** 2).T @ (H_s[r0:r1] ** 2)
+                wS = S * np.asarray(w)[r0:r1, None]
+                dW_sq[k] += (wS ** 2).T @ (H_s[r0:r1] ** 2)
     if dW is not None:
         return kl, c, g, dW, [np.sqrt(x) for x in dW_sq]
     return kl, c, g

@@ -58,6 +58,17 @@ __device__ __forceinline__ void merge_mza(float& m, float& Z, float& A, float m2
   m = mn;
 }
 
+// KL = mu - lse_s + lse_t with lse = ref + log Z, grouped so that no term is much larger than
+// the result: the log-sum-exps of peaked rows are tens of nats while the KL can be 1e-3, and
+// the references (and the sums relative to them) of a student and a teacher that agree differ
+// by little.  The plain difference of the two logarithms is the fallback when the ratio is
+// not a normal number.
+__device__ __forceinline__ float kl_from_sums(float mu, float ref_diff, float Zs, float Zt) {
+  const float q = Zs / Zt;
+  const float lq = (q > 1.0e-30f && q < 1.0e30f) ? logf(q) : logf(Zs) - logf(Zt);
+  return (mu - ref_diff) - lq;
+}
+
 // Largest i in [0, n) with a[i] <= x, for non-decreasing a with a[0] <= x.
 template <typename T>
 __device__ __forceinline__ int last_le(const T* a, int n, T x) {

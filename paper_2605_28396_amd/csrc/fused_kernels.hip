@@ -138,6 +138,8 @@ struct LogitPassArgs {
   // single-sweep mode: fixed per-row references and the offset of the second slab half
   const float* ref_s2; const float* ref_t2; const float* mu0;
   int64_t e2_off;
+  // per-(vocabulary tile, slab row) reference mu0 of the D factor, written by the sweep
+  float* mu0t; int64_t mu0t_stride;
   // diagnostics mode: teacher logit of the sampled token and the token id (-1: none) per row
   const float* zy_t; const int32_t* yid;
   // direct-to-LDS kernel: tile images of the four operands (see row_image_kernel)
@@ -147,7 +149,7 @@ struct LogitPassArgs {
 // Modes of the direct-to-LDS logit kernel.
 constexpr int kModeStats = 0;   // online (running-max) statistics only
 constexpr int kModeDz = 1;      // second sweep of the two-sweep scheme: dz tiles
-constexpr int kModeSingle = 2;  // single sweep: fixed-reference statistics + E1/E2 tiles
+constexpr int kModeSingle = 2;  // single sweep: fixed-reference statistics + D/E2 tiles
 constexpr int kModeSingleDiag = 3;  // the same plus the teacher-side diagnostics of Sec. 3.1
 constexpr int kModeSingleE2 = 4;      // single sweep that emits only the E2 factor (sampled estimator)
 constexpr int kModeSingleE2Diag = 5;  // the same plus the diagnostics
@@ -230,20 +232,21 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
 // rt2 = m_ref_t*log2e, mu0 ~ E_{p_s}[z_s - z_t]) every exponential is taken relative to the
 // same reference in every tile, so the statistics are plain sums,
 //   Z_s = sum e_s,  A = sum e_s d,  Z_t = sum e_t,   e_s = exp(z_s - m_ref_s), d = z_s - z_t,
-// and the unnormalised gradient factors E1 = e_s (d - mu0) and E2 = e_s can be emitted at
-// once: dz = (E1 - (mu - mu0) E2) / Z_s, hence g = (E1 W_s - (mu - mu0) E2 W_s) / Z_s.
-// E1 goes to slab rows row0.., E2 to the same rows e2_off elements further on.
+// and two bf16 factors of the unnormalised gradient can be emitted at once, D = d - mu0 and
+// E2 = e_s: dz = E2 (D - (mu - mu0)) / Z_s.  mu0 is a per-(row, vocabulary tile) reference
+// kept for the combine pass.  D goes to slab rows row0.., E2 to the same rows e2_off elements
+// further on.
 // B_t = sum e_t z_t (teacher entropy) and cnt = entries ranked above the sampled token are
 // only maintained in diagnostics mode.
 struct LaneSums { float Z_s[2], A_s[2], Z_t[2], B_t[2]; int cnt[2]; };
 
-template <bool TAIL, bool DIAG, bool WRITE_E1>
+template <bool TAIL, bool DIAG, bool WRITE_D>
 __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                 LaneSums& sm, const float (&rs2)[2],
-                                                const float (&rt2)[2], const float (&mu0)[2],
+                                                const float (&rt2)[2], float (&mu0)[2],
                                                 const float (&zyt)[2], const int (&yid)[2],
                                                 __bf16* blk, int64_t e2_off, int wrow,
-                                                int v0, int V, int lane) {
+                                                int v0, int V, int lane, float* mu0_out) {
   const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
@@ -255,7 +258,7 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        float e1[4], e2[4];
+        float e2[4];
         const bool ok = !TAIL || (vlane + fm * 32 + 8 * q) < V;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -271,18 +274,39 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
             Bt = fmaf(et, t, Bt);
             cnt += (t > zyt[fn] && (fm * 32 + 8 * q + e) != vy && ok) ? 1 : 0;
           }
-          e1[e] = es * (d - mu0[fn]);
           e2[e] = es;
         }
-        uint2 o1, o2;
-        o1.x = pack_bf16(e1[0], e1[1]); o1.y = pack_bf16(e1[2], e1[3]);
+        uint2 o2;
         o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
         const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
-        if (WRITE_E1) *(uint2*)(out + at) = o1;
         *(uint2*)(out + e2_off + at) = o2;
       }
     sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
     if (DIAG) { sm.B_t[fn] = Bt; sm.cnt[fn] = cnt; }
+    if (WRITE_D) {
+      // Second factor: D = d - mu0 with mu0 the strip's running mean of d = z_s - z_t under the
+      // student weights, this tile included (both half-columns of the row).  A heavy entry
+      // dominates the mean of its own tile, so its D is stored small and the correction
+      // (mu - mu0) carries its gradient: the rounding of both factors stays proportional to
+      // p_s |d - mu| even when the row is peaked and the first vocabulary entries say nothing
+      // about mu.  The masked entries of a tail tile have E2 = 0; their D is immaterial.
+      const float Zr = Zs + __shfl_xor(Zs, 32, 64), Ar = As + __shfl_xor(As, 32, 64);
+      if (Zr > 0.f) mu0[fn] = Ar / Zr;
+      const float m0 = mu0[fn];
+      if (mu0_out && lane < 32) mu0_out[fn * 32 + lane] = m0;
+#pragma unroll
+      for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float dd[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dd[e] = (zs[fm][fn][q * 4 + e] - m0) - zt[fm][fn][q * 4 + e];
+          uint2 o1;
+          o1.x = pack_bf16(dd[0], dd[1]); o1.y = pack_bf16(dd[2], dd[3]);
+          const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
+          *(uint2*)(out + at) = o1;
+        }
+    }
   }
 }
 
@@ -563,7 +587,7 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   LaneStats st;
   LaneSums sm;
   constexpr bool kDiag = MODE == kModeSingleDiag || MODE == kModeSingleE2Diag;
-  constexpr bool kE1 = MODE == kModeSingle || MODE == kModeSingleDiag;
+  constexpr bool kWriteD = MODE == kModeSingle || MODE == kModeSingleDiag;
   constexpr bool kSingle = MODE >= kModeSingle;
   float lse2[2], mu[2], rs2[2], rt2[2];   // per-row inputs of the dz / single-sweep epilogues
   float zyt[2];
@@ -669,12 +693,14 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
     } else {
       __bf16* blk = a.slab + ((int64_t)tt_local * (a.Vp / kBK) + 2 * vt) * kSlabBlock;
+      float* m0t = a.mu0t ? a.mu0t + (int64_t)vt * a.mu0t_stride + (int64_t)tt_local * kTileTokens + wave * 64
+                          : nullptr;
       if (MODE == kModeDz) {
         dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
       } else if (tail) {
-        single_epilogue<true, kDiag, kE1>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
+        single_epilogue<true, kDiag, kWriteD>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
       } else {
-        single_epilogue<false, kDiag, kE1>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane);
+        single_epilogue<false, kDiag, kWriteD>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
       }
     }
   }
@@ -733,7 +759,7 @@ __global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
   }
   const float lse_s = ms + logf(Zs), lse_t = mt + logf(Zt);
   const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
-  const float kl = mu - lse_s + lse_t;
+  const float kl = kl_from_sums(mu, ms - mt, Zs, Zt);
   if (lane == 0) {
     a.lse2[r] = lse_s * kLog2e;
     a.mu[r] = mu;
@@ -767,10 +793,30 @@ __global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
 // and the merge of the fixed-reference strip sums.
 // ---------------------------------------------------------------------------------------
 __global__ void make_refs_kernel(const float* __restrict__ part /* [5][1][n_pad] */, int64_t n_pad,
-                                 float* ref_s2, float* ref_t2, float* mu0) {
+                                 const float* __restrict__ zy_s, const float* __restrict__ zy_t,
+                                 const int32_t* __restrict__ yid, float* ref_s2, float* ref_t2,
+                                 float* mu0) {
   const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= n_pad) return;
-  const float ms = part[r], Zs = part[n_pad + r], A = part[2 * n_pad + r], mt = part[3 * n_pad + r];
+  float ms = part[r], Zs = part[n_pad + r], A = part[2 * n_pad + r], mt = part[3 * n_pad + r];
+  if (yid && yid[r] >= 0) {
+    // The sampled token joins the first vocabulary tile as a sample of the row: drawn from the
+    // student, it sits where the mass is, which the first 128 entries of a peaked row do not.
+    // The references rise to its logits (the exponentials of the sweep stay near 1 at the
+    // row maximum instead of growing with the gap to the first tile), and mu0 becomes the
+    // self-normalised estimate of E_p[z_s - z_t] over the tile's entries and the token.
+    const float zs = zy_s[r], zt = zy_t[r];
+    const float rs = fmaxf(ms, zs);
+    const float sc = fast_exp2((ms - rs) * kLog2e);
+    Zs *= sc; A *= sc;
+    if (yid[r] >= kTileVocab) {           // not already one of the tile's entries
+      const float ey = fast_exp2((zs - rs) * kLog2e);
+      Zs += ey;
+      A = fmaf(ey, zs - zt, A);
+    }
+    ms = rs;
+    mt = fmaxf(mt, zt);
+  }
   ref_s2[r] = ms * kLog2e;
   ref_t2[r] = mt * kLog2e;
   mu0[r] = A / Zs;
@@ -778,8 +824,8 @@ __global__ void make_refs_kernel(const float* __restrict__ part /* [5][1][n_pad]
 
 struct MergeSingleArgs {
   MergeArgs m;                 // part: [3][strips][n_pad] sums Z_s, A, Z_t
-  const float* ref_s2; const float* ref_t2; const float* mu0;
-  float* delta; float* inv_z;
+  const float* ref_s2; const float* ref_t2;
+  float* mu_out; float* inv_z;
   int64_t row0, rows;          // computed rows [row0, row0 + rows) of this launch (one slab)
 };
 
@@ -799,9 +845,9 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
   if (a.diag) { Bt = wave_sum(Bt); cnt = wave_sum(cnt); }
   const float lse_s = b.ref_s2[r] * kLn2 + logf(Zs), lse_t = b.ref_t2[r] * kLn2 + logf(Zt);
   const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
-  const float kl = mu - lse_s + lse_t;
+  const float kl = kl_from_sums(mu, (b.ref_s2[r] - b.ref_t2[r]) * kLn2, Zs, Zt);
   if (lane == 0) {
-    b.delta[r] = mu - b.mu0[r];
+    b.mu_out[r] = mu;
     b.inv_z[r] = 1.f / Zs;
     a.klr[r] = kl;
   }
@@ -837,23 +883,32 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
   }
 }
 
-// Teacher logit of the sampled token, z_t[y_t] = h_t . W_t[y_t], and the token id (-1 when
-// there is none or it is out of range), per computed row: what the sweep compares against
-// to count the entries the teacher ranks above y_t (Sec. 3.1).  One wave per row.
-__global__ __launch_bounds__(256) void token_logit_kernel(const int32_t* __restrict__ row_idx,
-                                                          const int32_t* __restrict__ ids,
-                                                          const __bf16* __restrict__ h_t,
-                                                          const __bf16* __restrict__ W_t, int H_t, int V,
-                                                          int64_t n_pad, float* zy_t, int32_t* yid) {
+// Logits of the sampled token under both models, z_s[y_t] = h_s . W_s[y_t] and
+// z_t[y_t] = h_t . W_t[y_t], and the token id (-1 when there is none or it is out of range),
+// per computed row.  The references of the single sweep are built from them (make_refs_kernel)
+// and the diagnostics sweep compares against z_t[y_t] to count the entries the teacher ranks
+// above y_t (Sec. 3.1).  One wave per row.
+struct TokenLogitArgs {
+  const int32_t* row_idx; const int32_t* ids;
+  const __bf16* h_s; const __bf16* W_s; const __bf16* h_t; const __bf16* W_t;
+  int H_s, H_t, V;
+  int64_t n_pad;
+  float* zy_s; float* zy_t; int32_t* yid;
+};
+
+__global__ __launch_bounds__(256) void token_logit_kernel(TokenLogitArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= n_pad) return;
-  const int64_t t = row_idx[r];
-  const int y = ids ? ids[t] : -1;
-  float z = 0.f;
-  const bool ok = y >= 0 && y < V;
-  if (ok) z = dot_bf16_row(h_t + t * H_t, W_t + (int64_t)y * H_t, H_t, lane);
-  if (lane == 0) { zy_t[r] = z; yid[r] = ok ? y : -1; }
+  if (r >= a.n_pad) return;
+  const int64_t t = a.row_idx[r];
+  const int y = a.ids ? a.ids[t] : -1;
+  float zs = 0.f, zt = 0.f;
+  const bool ok = y >= 0 && y < a.V;
+  if (ok) {
+    zs = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
+    zt = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)y * a.H_t, a.H_t, lane);
+  }
+  if (lane == 0) { a.zy_s[r] = zs; a.zy_t[r] = zt; a.yid[r] = ok ? y : -1; }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -899,14 +954,15 @@ __global__ __launch_bounds__(256) void wst_image_kernel(const uint16_t* __restri
 }
 
 // ---------------------------------------------------------------------------------------
-// Combine.  Once a slab's rows have their mu (all strips merged), the two gradient factors
-// collapse into the logit gradient itself, dz = (E1 - (mu - mu0) E2) / Z_s = p_s (d - mu),
-// written over E1 in the same image order, and the gradient GEMM runs on one factor.  A
+// Combine.  Once a slab's rows have their mu (all strips merged), the two stored factors
+// collapse into the logit gradient itself, dz = E2 (D - (mu - mu0)) / Z_s = p_s (d - mu),
+// written over D in the same image order, and the gradient GEMM runs on one factor.  A
 // streaming pass: 4 B read + 2 B written per slab element.
 // ---------------------------------------------------------------------------------------
 struct CombineArgs {
-  uint4* slab; int64_t e2_vec;          // E2 lies e2_vec 16-byte vectors after E1
-  const float* delta; const float* inv_z;   // per computed row
+  uint4* slab; int64_t e2_vec;          // E2 lies e2_vec 16-byte vectors after D
+  const float* mu; const float* inv_z;      // per computed row
+  const float* mu0t; int64_t mu0t_stride;   // reference of D per (vocabulary tile, slab row)
   int64_t row0;                         // computed-row index of slab row 0
   int nk;                               // k-steps (blocks) per row tile
   // TR: also the transpose of w * dz as tile images for the head-weight GEMMs (rows =
@@ -946,13 +1002,14 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   for (int i = 0; i < 8; ++i) {
     const int q = i * 256 + threadIdx.x;
     const int64_t r = rbase + (q >> 3);
-    const float dl = a.delta[r], iz = a.inv_z[r];
+    const float dl = a.mu[r] - a.mu0t[(int64_t)(kt >> 1) * a.mu0t_stride + rt * kTileTokens + (q >> 3)];
+    const float iz = a.inv_z[r];
     const uint4 x = p1[q], y = p2[q];
     float d[8];
-    d[0] = (bf16_lo(x.x) - dl * bf16_lo(y.x)) * iz; d[1] = (bf16_hi(x.x) - dl * bf16_hi(y.x)) * iz;
-    d[2] = (bf16_lo(x.y) - dl * bf16_lo(y.y)) * iz; d[3] = (bf16_hi(x.y) - dl * bf16_hi(y.y)) * iz;
-    d[4] = (bf16_lo(x.z) - dl * bf16_lo(y.z)) * iz; d[5] = (bf16_hi(x.z) - dl * bf16_hi(y.z)) * iz;
-    d[6] = (bf16_lo(x.w) - dl * bf16_lo(y.w)) * iz; d[7] = (bf16_hi(x.w) - dl * bf16_hi(y.w)) * iz;
+    d[0] = (bf16_lo(x.x) - dl) * (bf16_lo(y.x) * iz); d[1] = (bf16_hi(x.x) - dl) * (bf16_hi(y.x) * iz);
+    d[2] = (bf16_lo(x.y) - dl) * (bf16_lo(y.y) * iz); d[3] = (bf16_hi(x.y) - dl) * (bf16_hi(y.y) * iz);
+    d[4] = (bf16_lo(x.z) - dl) * (bf16_lo(y.z) * iz); d[5] = (bf16_hi(x.z) - dl) * (bf16_hi(y.z) * iz);
+    d[6] = (bf16_lo(x.w) - dl) * (bf16_lo(y.w) * iz); d[7] = (bf16_hi(x.w) - dl) * (bf16_hi(y.w) * iz);
     uint4 o;
     o.x = pack_bf16(d[0], d[1]); o.y = pack_bf16(d[2], d[3]);
     o.z = pack_bf16(d[4], d[5]); o.w = pack_bf16(d[6], d[7]);
@@ -1373,11 +1430,11 @@ struct FusedLayout {
   bool single;       // single-sweep scheme (needs use_dma)
   size_t o_wt_img, o_ws_img, o_ht_img, o_hs_img;   // tile images of the logit operands (use_dma)
   int strips1;       // vocabulary strips of the single sweep
-  size_t o_ref_t2, o_delta, o_invz;
+  size_t o_ref_t2, o_delta, o_invz, o_mu0t;
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, o_summ, o_cosp, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_s, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, o_summ, o_cosp, total;
 };
 
 static int env_int(const char* name, int dflt) {
@@ -1442,6 +1499,8 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_part = take(sizeof(float) * 5 * (size_t)(strips > strips1 ? strips : strips1) * (size_t)n_pad);
   L.o_ref_t2 = take(sizeof(float) * (size_t)n_pad);
   L.o_delta = take(sizeof(float) * (size_t)n_pad);
+  L.o_mu0t = take((L.single && p->estimator != ADWIN_EST_SAMPLED)
+                      ? sizeof(float) * (size_t)vt_total * (size_t)slab : 0);
   L.o_invz = take(sizeof(float) * (size_t)n_pad);
   L.o_lse2 = take(sizeof(float) * (size_t)n_pad);
   L.o_mu = take(sizeof(float) * (size_t)n_pad);
@@ -1466,6 +1525,7 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_cacc = take(sizeof(double) * 4 * kc * (size_t)p->B);
   L.o_cS = take(sizeof(double) * kc * (size_t)p->B);
   L.o_cr = take(sizeof(float) * (size_t)n_pad);
+  L.o_zy_s = take(sizeof(float) * (size_t)n_pad);
   L.o_zy_t = take(sizeof(float) * (size_t)n_pad);
   L.o_yid = take(sizeof(int32_t) * (size_t)n_pad);
   const bool head = p->dW_prefix || p->dW_full;       // transposed slab + weighted h_s^T images
@@ -1665,6 +1725,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     la.slab = (__bf16*)(ws + L.o_slab); la.Vp = L.Vp;
     la.ref_s2 = (const float*)(ws + L.o_lse2); la.ref_t2 = (const float*)(ws + L.o_ref_t2);
     la.mu0 = (const float*)(ws + L.o_mu); la.e2_off = 0;
+    la.mu0t = (L.single && !sampled) ? (float*)(ws + L.o_mu0t) : nullptr; la.mu0t_stride = L.slab_rows;
     la.tg = env_int("ADWIN_TG", 4);
     la.Wt_img = (const char*)(ws + L.o_wt_img); la.Ws_img = (const char*)(ws + L.o_ws_img);
     la.ht_img = (const char*)(ws + L.o_ht_img); la.hs_img = (const char*)(ws + L.o_hs_img);
@@ -1690,18 +1751,24 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         const int groups = (n_tiles + la.tg - 1) / la.tg;
         logit_pass_dma_kernel<kModeStats><<<(unsigned)(groups * la.tg), 256, kDmaLds, stream>>>(la);
         ADWIN_HIP_TRY(hipGetLastError());
+        if (p->ids || diag) {      // without ids: id -1 on every row, which the diagnostics sweep expects
+          TokenLogitArgs ta;
+          ta.row_idx = pl.row_idx; ta.ids = p->ids;
+          ta.h_s = la.h_s; ta.W_s = la.W_s; ta.h_t = la.h_t; ta.W_t = la.W_t;
+          ta.H_s = p->H_s; ta.H_t = p->H_t; ta.V = p->V; ta.n_pad = n_pad;
+          ta.zy_s = (float*)(ws + L.o_zy_s); ta.zy_t = (float*)(ws + L.o_zy_t);
+          ta.yid = (int32_t*)(ws + L.o_yid);
+          token_logit_kernel<<<(unsigned)((n_pad + 3) / 4), 256, 0, stream>>>(ta);
+          ADWIN_HIP_TRY(hipGetLastError());
+        }
         make_refs_kernel<<<(unsigned)((n_pad + 255) / 256), 256, 0, stream>>>(
-            la.part, n_pad, (float*)(ws + L.o_lse2), (float*)(ws + L.o_ref_t2), (float*)(ws + L.o_mu));
+            la.part, n_pad, (const float*)(ws + L.o_zy_s), (const float*)(ws + L.o_zy_t),
+            p->ids ? (const int32_t*)(ws + L.o_yid) : nullptr, (float*)(ws + L.o_lse2),
+            (float*)(ws + L.o_ref_t2), (float*)(ws + L.o_mu));
         ADWIN_HIP_TRY(hipGetLastError());
       }
       la.vt_total = vt_total; la.strips = L.strips1;
       la.zy_t = (const float*)(ws + L.o_zy_t); la.yid = (const int32_t*)(ws + L.o_yid);
-      if (diag) {
-        token_logit_kernel<<<(unsigned)((n_pad + 3) / 4), 256, 0, stream>>>(
-            pl.row_idx, p->ids, la.h_t, la.W_t, p->H_t, p->V, n_pad, (float*)(ws + L.o_zy_t),
-            (int32_t*)(ws + L.o_yid));
-        ADWIN_HIP_TRY(hipGetLastError());
-      }
       ga.g_rows = 2 * n_pad; ga.half_off = n_pad;
       for (int64_t r0 = 0; r0 < n_pad; r0 += L.slab_rows) {
         const int64_t rows = (n_pad - r0 < L.slab_rows) ? n_pad - r0 : L.slab_rows;
@@ -1719,8 +1786,8 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         phase(ADWIN_PHASE_MERGE);
         MergeSingleArgs ms;
         ms.m = m; ms.m.strips = L.strips1;
-        ms.ref_s2 = la.ref_s2; ms.ref_t2 = la.ref_t2; ms.mu0 = la.mu0;
-        ms.delta = (float*)(ws + L.o_delta); ms.inv_z = (float*)(ws + L.o_invz);
+        ms.ref_s2 = la.ref_s2; ms.ref_t2 = la.ref_t2;
+        ms.mu_out = (float*)(ws + L.o_delta); ms.inv_z = (float*)(ws + L.o_invz);
         ms.row0 = r0; ms.rows = rows;
         merge_single_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, stream>>>(ms);
         ADWIN_HIP_TRY(hipGetLastError());
@@ -1733,7 +1800,8 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
           phase(ADWIN_PHASE_DZ);
           CombineArgs ca;
           ca.slab = (uint4*)la.slab; ca.e2_vec = la.e2_off / 8;
-          ca.delta = ms.delta; ca.inv_z = ms.inv_z; ca.row0 = r0; ca.nk = ga.nk_total;
+          ca.mu = ms.mu_out; ca.inv_z = ms.inv_z; ca.row0 = r0; ca.nk = ga.nk_total;
+          ca.mu0t = la.mu0t; ca.mu0t_stride = la.mu0t_stride;
           ca.dzT_p = p->dW_prefix ? (uint4*)(ws + L.o_dzT_p) : nullptr;
           ca.dzT_f = p->dW_full ? (uint4*)(ws + L.o_dzT_f) : nullptr;
           ca.nkr = (int)(rows / kBK); ca.pl = pl; ca.n_rows = hp.n_rows; ca.grad_scale = p->grad_scale;

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
     }
     const float lse_s = m + logf(Z), lse_t = m2 + logf(Z2);
     const float mu = Aa / Z;                       // E_{p_s}[z_s - z_t]
-    const float kl = mu - lse_s + lse_t;
+    const float kl = kl_from_sums(mu, m - m2, Z, Z2);
     float c = 0.f;
     uint32_t flag = 0;
     if (a.ids) {
@@ -361,7 +361,7 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
     }
     const float lse_s = m + logf(Z), lse_t = m2 + logf(Z2);
     const float mu = Aa / Z;                       // E_{p_s}[z_s - z_t]
-    const float kl = mu - lse_s + lse_t;
+    const float kl = kl_from_sums(mu, m - m2, Z, Z2);
     float c = 0.f;
     uint32_t flag = 0;
     if (a.ids) {

@@ -28,10 +28,15 @@ def oracle_inputs(p: dict) -> dict:
     return {k: (v.cpu().numpy() if k == "ids" else synth.to_f64(v)) for k, v in p.items()}
 
 
-def assert_kl(got, want, what="kl"):
+def assert_kl(got, want, what="kl", logit_scale=None):
+    """logit_scale: per-row magnitude of the logits (e.g. the larger |log-sum-exp|).  fp32
+    logits of magnitude |z| carry an absolute rounding error of about 2^-24 |z| each, and the
+    KL is a difference of such quantities: where the logits are tens of nats the absolute floor
+    grows to 8 * 2^-24 * |z| (it is KL_ABS for |z| up to ~2)."""
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
     err = np.abs(got - want)
-    tol = KL_REL * np.abs(want) + KL_ABS
+    floor = KL_ABS if logit_scale is None else np.maximum(KL_ABS, 8 * 2.0 ** -24 * np.asarray(logit_scale))
+    tol = KL_REL * np.abs(want) + floor
     bad = np.where(err > tol)[0]
     assert len(bad) == 0, f"{what}: {len(bad)} rows off, worst {err.max():.3e} at {bad[:5]}"
 
@@ -43,11 +48,14 @@ def assert_cost(got, want):
     assert np.all(err <= tol), f"c: worst {err.max():.3e}"
 
 
-def assert_grad(got, want, what="dh", storage_ulp=0.0):
+def assert_grad(got, want, what="dh", storage_ulp=0.0, abs_cap=True):
+    """abs_cap: also hold the absolute bound DH_ABS, which is the binding one only while the
+    gradients themselves are below 1 (the benchmark's random-initialisation regime); peaked
+    cases with gradients of order 1..10 are held to the relative bound alone."""
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
     scale = np.abs(want).max() if want.size else 0.0
     err = np.abs(got - want)
-    tol = np.minimum(DH_ABS, DH_REL * scale) + storage_ulp * np.abs(want)
+    tol = (np.minimum(DH_ABS, DH_REL * scale) if abs_cap else DH_REL * scale) + storage_ulp * np.abs(want)
     worst = (err - tol).max() if err.size else -1.0
     assert worst <= 0, (f"{what}: max err {err.max():.3e} vs tol {DH_REL * scale:.3e} "
                         f"(max|ref| {scale:.3e})")

@@ -38,17 +38,17 @@ def _run_fused(B, w, p, dev, **kw):
             for k, v in out.items()}
 
 
-def _check_fused(w, got, ref, reduction, dh_bf16=False):
+def _check_fused(w, got, ref, reduction, dh_bf16=False, logit_scale=None, abs_cap=True):
     assert np.array_equal(got["n_out"], ref["n"]) and int(got["n_adm_out"][0]) == ref["n_adm"]
     assert int(got["status_dev"][0]) == 0
-    Hp.assert_kl(got["kl"], ref["kl"])
+    Hp.assert_kl(got["kl"], ref["kl"], logit_scale=logit_scale)
     Hp.assert_cost(got["c"], ref["c"])
     ulp = Hp.BF16_ULP if dh_bf16 else 0.0
-    Hp.assert_grad(got["dh_prefix"], ref["dh_prefix"], "dh_prefix", ulp)
+    Hp.assert_grad(got["dh_prefix"], ref["dh_prefix"], "dh_prefix", ulp, abs_cap)
     Hp.assert_close_rel(got["loss_prefix"], ref["loss_prefix"], Hp.LOSS_REL, "loss_prefix")
     Hp.assert_close_rel(got["batch"][:2], ref["batch"][:2], Hp.LOSS_REL, "batch losses")
     if w.mode == synth.MODE_PREFIX_AND_FULL:
-        Hp.assert_grad(got["dh_full"], ref["dh_full"], "dh_full", ulp)
+        Hp.assert_grad(got["dh_full"], ref["dh_full"], "dh_full", ulp, abs_cap)
         Hp.assert_close_rel(got["loss_full"], ref["loss_full"], Hp.LOSS_REL, "loss_full")
         for k in ("rho_pooled", "rho_field"):
             assert np.all(np.abs(got[k] - ref[k]) <= Hp.RHO_ABS), (k, got[k], ref[k])
@@ -502,3 +502,54 @@ def test_every_output_is_optional(B):
         a, b = alone[k], full_l[k]
         assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
                            b.view(torch.int16) if b.dtype == torch.bfloat16 else b), k
+
+
+def _peaked_workload():
+    return synth.Workload("peaked", 8000, 256, 256, synth._offsets([150, 0, 300, 70]),
+                          np.array([100, 5, 300, 20], np.int32), synth.MODE_PREFIX_AND_FULL)
+
+
+@pytest.mark.parametrize("on_policy", [True, False])
+@pytest.mark.parametrize("estimator", [O.EST_EXPECTED, O.EST_SAMPLED])
+def test_peaked_distributions(B, estimator, on_policy):
+    """Logits with a spread of 4 nats (half the mass on one entry, row maximum 14 nats on average
+    and up to 25 above the largest of the first 128 entries) and a teacher that is a perturbed
+    copy of the student: the regime of trained models, where the fixed references of the
+    single sweep sit far below the row maximum."""
+    w = _peaked_workload()
+    p = synth.peaked_problem(w)
+    if on_policy:                       # y_t ~ p_s, as in the method; else uniform over the vocabulary
+        p["ids"] = _sample_ids_from_student(w, p)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SUM, mode=w.mode, estimator=estimator,
+                      head_gradient=estimator == O.EST_EXPECTED, summand_norms=True)
+    assert 0.5 < ref["kl"].mean() < 3.0
+    want = B.FusedCall.DEFAULT_OUTPUTS + ("t_logp", "t_entropy", "t_rank")
+    if estimator == O.EST_EXPECTED:
+        want += ("dW_prefix", "dW_full")
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32, estimator=estimator,
+                     want=want)
+    z_t = f["h_t"] @ f["W_t"].T
+    lse_t = np.array([np.log(np.exp(z - z.max()).sum()) + z.max() for z in z_t])
+    if estimator == O.EST_EXPECTED:
+        # A gradient row is carried by a handful of vocabulary entries here, so the rounding of
+        # dz to bf16 does not average out: even with the exact mu known in advance (the two-sweep
+        # scheme) the error is 0.4 % of the largest gradient element.  Every element is held to
+        # the bound of its own summands instead; the per-tile references of the sweep keep the
+        # rounding of the two stored factors proportional to p_s |d - mu|, which this checks.
+        adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
+        for k, mask in (("dh_prefix", adm), ("dh_full", np.ones(w.T, bool))):
+            tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask[:, None] + 1e-6 * np.abs(ref[k]).max()
+            err = np.abs(got[k] - ref[k])
+            assert (err <= tol).all(), (k, err.max(), np.abs(ref[k]).max(), (err / tol).max())
+            assert err.max() <= 3 * Hp.DH_REL * np.abs(ref[k]).max(), (k, err.max(), np.abs(ref[k]).max())
+            got[k] = ref[k]
+    _check_fused(w, got, ref, O.RED_SUM, logit_scale=np.abs(lse_t), abs_cap=False)
+    if estimator == O.EST_EXPECTED:
+        _check_head_gradient(got, ref, True)
+    ent, logp, lo, hi = _teacher_reference(z_t, f["ids"], list(ref["rows"]), 1e-3)
+    for t in ref["rows"]:
+        assert abs(got["t_entropy"][t] - ent[t]) <= 2e-3, (t, got["t_entropy"][t], ent[t])
+        assert abs(got["t_logp"][t] - logp[t]) <= 1e-3 * max(1.0, abs(logp[t]))
+        assert lo[t] <= got["t_rank"][t] <= hi[t]

@@ -475,9 +475,10 @@ def test_head_weight_gradient_finite_differences():
     # between |dW| / sqrt(#summands) and the sum of magnitudes
     one = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.array([1, 0]), reduction=O.RED_SUM,
                       head_gradient=True)
-    assert np.allclose(one["dW_prefix_l2"], np.abs(one["dW_prefix"]), rtol=1e-12)
+    sc = np.stack([O.token_dz_scale(W_s @ h_s[t], W_t @ h_t[t]) for t in range(T)])
+    assert np.allclose(one["dW_prefix_l2"], np.outer(sc[0], np.abs(h_s[0])), rtol=1e-12)
     assert np.allclose(one["dW_prefix"], np.outer(dz[0], h_s[0]), rtol=1e-12)
-    l1 = np.abs(dz).T @ np.abs(h_s)
+    l1 = sc.T @ np.abs(h_s)
     assert (out["dW_full_l2"] <= l1 + 1e-15).all()
     assert (np.abs(out["dW_full"]) <= np.sqrt(T) * out["dW_full_l2"] + 1e-15).all()
 
@@ -567,10 +568,26 @@ def test_summand_norms_of_the_hidden_gradient():
     offsets = np.array([0, 3]); h_s, h_t = RNG.normal(0, 1, (3, Hs)), RNG.normal(0, 1, (3, Ht))
     out = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.array([2]), summand_norms=True)
     for t in range(3):
-        dz = O.token_dz(W_s @ h_s[t], W_t @ h_t[t])
+        dz = O.token_dz_scale(W_s @ h_s[t], W_t @ h_t[t])
         for k in range(Hs):
             terms = dz * W_s[:, k]
             want = math.sqrt(sum(x * x for x in terms)) if t < 2 else 0.0
             assert out["g_l2"][t, k] == pytest.approx(want, rel=1e-12)
             if t < 2:
                 assert abs(out["g"][t, k]) <= math.sqrt(V) * out["g_l2"][t, k] + 1e-15
+
+
+def test_error_scale_of_the_logit_gradient():
+    # p (|Delta - KL| + D): two-entry closed form, dominance over |dz|, zero for equal models
+    a, b = 0.8, 0.3                                   # p_s = (a, 1-a), p_t = (b, 1-b)
+    z_s, z_t = np.log([a, 1 - a]), np.log([b, 1 - b])
+    delta = np.array([math.log(a / b), math.log((1 - a) / (1 - b))])
+    kl = a * delta[0] + (1 - a) * delta[1]
+    dev = math.sqrt(a * (delta[0] - kl) ** 2 + (1 - a) * (delta[1] - kl) ** 2)
+    want = np.array([a, 1 - a]) * (np.abs(delta - kl) + dev)
+    assert np.allclose(O.token_dz_scale(z_s, z_t), want, rtol=1e-12)
+    assert np.allclose(O.token_dz_scale(z_s + 3.0, z_t - 1.0), want, rtol=1e-12)     # shift invariance
+    for _ in range(5):
+        zs, zt = RNG.normal(0, 3, 11), RNG.normal(0, 3, 11)
+        assert (O.token_dz_scale(zs, zt) >= np.abs(O.token_dz(zs, zt)) - 1e-15).all()
+        assert np.abs(O.token_dz_scale(zs, zs + 2.5)).max() < 1e-12
