@@ -553,3 +553,38 @@ def test_peaked_distributions(B, estimator, on_policy):
         assert abs(got["t_entropy"][t] - ent[t]) <= 2e-3, (t, got["t_entropy"][t], ent[t])
         assert abs(got["t_logp"][t] - logp[t]) <= 1e-3 * max(1.0, abs(logp[t]))
         assert lo[t] <= got["t_rank"][t] <= hi[t]
+
+
+def test_peaked_distributions_other_paths(B, monkeypatch):
+    """The same peaked pair through the logits-given kernels (both) and through the two-sweep
+    fallback of the fused path."""
+    w = _peaked_workload()
+    p = synth.peaked_problem(w)
+    p["ids"] = _sample_ids_from_student(w, p)
+    f = Hp.oracle_inputs(p)
+    z_s = torch.from_numpy(f["h_s"] @ f["W_s"].T).to(torch.bfloat16)
+    z_t = torch.from_numpy(f["h_t"] @ f["W_t"].T).to(torch.bfloat16)
+    fz_s, fz_t = synth.to_f64(z_s), synth.to_f64(z_t)
+    refl = O.supervise_from_logits(fz_s, fz_t, f["ids"], w.offsets, w.window, reduction=O.RED_SUM)
+    lse = np.array([np.log(np.exp(z - z.max()).sum()) + z.max() for z in fz_t])
+    for env in ({}, {"ADWIN_LOGITS_STREAMING": "1"}):
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        out = B.adwin_opd_from_logits(z_s.cuda(), z_t.cuda(), p["ids"].cuda(), w.offsets, w.window,
+                                      reduction=O.RED_SUM)
+        torch.cuda.synchronize()
+        Hp.assert_kl(out["kl"].cpu().numpy(), refl["kl"], logit_scale=np.abs(lse))
+        Hp.assert_cost(out["c"].cpu().numpy(), refl["c"])
+        Hp.assert_grad(out["dz"].float().cpu().numpy(), refl["dz"], "dz", Hp.BF16_ULP, abs_cap=False)
+    monkeypatch.delenv("ADWIN_LOGITS_STREAMING")
+    monkeypatch.setenv("ADWIN_TWO_SWEEP", "1")
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SUM, mode=w.mode, summand_norms=True)
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32)
+    lse_t = np.array([np.log(np.exp(z - z.max()).sum()) + z.max() for z in f["h_t"] @ f["W_t"].T])
+    for k in ("dh_prefix", "dh_full"):
+        mask = (np.abs(ref[k]).sum(axis=1) > 0)[:, None]
+        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask + 1e-6 * np.abs(ref[k]).max()
+        assert (np.abs(got[k] - ref[k]) <= tol).all(), k
+        got[k] = ref[k]
+    _check_fused(w, got, ref, O.RED_SUM, logit_scale=np.abs(lse_t), abs_cap=False)
