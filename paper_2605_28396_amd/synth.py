@@ -170,21 +170,21 @@ def hidden_problem(w: Workload, device="cpu") -> dict:
 def peaked_problem(w: Workload, device="cpu", logit_std: float = 4.0, teacher_noise: float = 0.3) -> dict:
     """A same-family pair with peaked distributions, the regime of trained language models
     rather than of random initialisation: student logits ~N(0, logit_std^2) (a handful of
-    entries carry most of the mass), the teacher a perturbed copy of the student (h_t = h_s +
-    noise, W_t = W_s + noise; needs H_t == H_s), so that the KL is of order one and z_s - z_t is
-    small against the spread of the logits.  A further third of the rows gets its largest
-    student logits late in the vocabulary by construction of W (rows of W grow with the entry
-    index), so references taken from the first vocabulary entries sit far below the row maximum."""
-    assert w.H_s == w.H_t
+    entries carry most of the mass), the teacher a perturbed copy of the student (its first H_s
+    hidden columns are h_s + noise and W_s + noise, any further columns small noise; needs
+    H_t >= H_s), so that the KL is of order one and z_s - z_t is small against the spread of the
+    logits.  The rows of W grow with the entry index, so the largest logits tend to sit late in
+    the vocabulary and references taken from its first entries lie far below the row maximum."""
+    assert w.H_t >= w.H_s
     sd = logit_std / float(w.H_s) ** 0.5
     h_s = normal_bf16((w.T, w.H_s), 1.0, (w.name, "pk_h_s"), device)
     W_s = normal_bf16((w.V, w.H_s), sd, (w.name, "pk_W_s"), device)
-    ramp = torch.linspace(0.5, 1.5, w.V, device=device, dtype=torch.float32)[:, None]
-    W_s = (W_s.float() * ramp).to(torch.bfloat16)
-    h_t = (h_s.float() + teacher_noise * normal_bf16((w.T, w.H_s), 1.0, (w.name, "pk_nh"), device).float()
-           ).to(torch.bfloat16)
-    W_t = (W_s.float() + teacher_noise * sd * normal_bf16((w.V, w.H_s), 1.0, (w.name, "pk_nW"), device).float()
-           ).to(torch.bfloat16)
+    W_s.mul_(torch.linspace(0.5, 1.5, w.V, device=device, dtype=torch.float32)[:, None].to(torch.bfloat16))
+    h_t = normal_bf16((w.T, w.H_t), 1.0, (w.name, "pk_nh"), device)
+    h_t.mul_(teacher_noise)
+    h_t[:, :w.H_s] += h_s
+    W_t = normal_bf16((w.V, w.H_t), teacher_noise * sd, (w.name, "pk_nW"), device)
+    W_t[:, :w.H_s] += W_s
     return {"h_s": h_s, "h_t": h_t, "W_s": W_s, "W_t": W_t,
             "ids": uniform_ids(w.T, w.V, (w.name, "ids"), device)}
 

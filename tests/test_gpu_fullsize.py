@@ -157,6 +157,40 @@ def test_fused_full_size_sampled_rows_and_reductions(B, name, estimator):
     _free()
 
 
+def test_fused_full_size_peaked_rows(B):
+    """The benchmark shape with a peaked same-family pair instead of random-initialisation
+    tensors (half the mass of a row on one entry, row maximum far above the first vocabulary
+    entries, ids uniform, i.e. the references get no help from the sampled token): sampled
+    rows against the oracle, gradient elements bounded by their own summands."""
+    print("[case] fused full size, peaked rows", flush=True)
+    w = synth.workload("strong_to_weak")
+    dev = torch.device("cuda:0")
+    p = synth.peaked_problem(w, dev)
+    call = B.FusedCall(p["h_s"], p["h_t"], p["W_s"], p["W_t"], p["ids"], w.offsets, w.window,
+                       mode=w.mode, reduction=B.ADWIN_RED_SUM, dh_dtype=B.ADWIN_DT_F32)
+    assert call.run() == 0
+    torch.cuda.synchronize()
+    out = call.out
+    assert int(out["status_dev"][0]) == 0
+    rows = synth.sample_rows(w, K_ROWS)
+    idx = torch.from_numpy(rows).to(dev)
+    Ws, Wt = synth.to_f64(p["W_s"]), synth.to_f64(p["W_t"])
+    hs, ht = synth.to_f64(p["h_s"][idx]), synth.to_f64(p["h_t"][idx])
+    gn = np.zeros((len(rows), w.H_s))
+    kl, c, g = O.rows_terms(hs, ht, Ws, Wt, p["ids"][idx].cpu().numpy(), g_norms=gn)
+    assert 0.3 < kl.mean() < 5.0
+    lse_t = np.array([np.log(np.exp(z - z.max()).sum()) + z.max() for z in ht[::16] @ Wt.T])
+    del Ws, Wt
+    Hp.assert_kl(out["kl"][idx].cpu().numpy(), kl, logit_scale=np.abs(lse_t).max())
+    Hp.assert_cost(out["c"][idx].cpu().numpy(), c)
+    err = np.abs(out["dh_prefix"][idx].double().cpu().numpy() - g)
+    tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * gn + 1e-6 * np.abs(g).max()
+    assert (err <= tol).all(), (err.max(), np.abs(g).max(), (err / tol).max())
+    assert err.max() <= 3 * Hp.DH_REL * np.abs(g).max(), (err.max(), np.abs(g).max())
+    del call, out, p
+    _free()
+
+
 def test_head_weight_gradient_full_vocabulary(B):
     """dW_s at the benchmark's vocabulary size (all 594 vocabulary tiles; 4 hidden tiles) over a
     batch and hidden sizes small enough for the oracle: every row feeds every element, so rows
