@@ -139,8 +139,9 @@ typedef struct adwin_opd_problem {
   /* Gradients of the batch objectives with respect to the student LM-head weights (z = W h):
    * sum_t grad_scale * alpha_i * dz_t^T h_s[t], the third contraction of the LM-head backward.
    * NULL = not wanted; each costs one more 2 V H_s FLOP per token.  Device, 16-byte aligned
-   * (else ADWIN_E_ALIGN), overwritten in full (zeros when no row is computed).  Estimator
-   * EXPECTED only, and dW_full only in mode PREFIX_AND_FULL (else ADWIN_E_MODE).  Each element
+   * (else ADWIN_E_ALIGN), overwritten in full (zeros when no row is computed).  dz is the
+   * logit gradient of the selected estimator.  dW_full only in mode PREFIX_AND_FULL, and
+   * neither with the two-sweep fallback scheme (else ADWIN_E_MODE).  Each element
    * is a sum over rows of products whose dz factor is rounded to bf16.  With both requested,
    * batch[6] = cos(dW_prefix, dW_full): Sec. 4.2's alignment taken in the LM-head parameter
    * block (0 if either is zero). */

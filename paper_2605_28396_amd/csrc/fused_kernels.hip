@@ -972,9 +972,13 @@ struct CombineArgs {
   // before the one rounding to bf16.  Either image may be NULL.
   uint4* dzT_p; uint4* dzT_f; int nkr;  // k-steps (of 64 slab rows) per vocabulary tile
   DevicePlan pl; int64_t n_rows; float grad_scale;
+  // SAMPLED (with TR): the slab holds only E2 and is left as it is; the transposed images take
+  // Eq. 4's logit gradient c_t (e_{y_t} - p_s) = c_t (1[v = y_t] - E2 / Z_s), the one-hot term
+  // entering before the rounding.  c_t and y_t per computed row (y_t = -1: none).
+  const float* cr; const int32_t* yid;
 };
 
-template <bool TR>
+template <bool TR, bool SAMPLED = false>
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   // one workgroup per block (row tile rt = blockIdx.y, kt = blockIdx.x): 2048 vectors of 8
   // entries; vector q holds row q / 8, chunk position q % 8
@@ -1002,18 +1006,30 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   for (int i = 0; i < 8; ++i) {
     const int q = i * 256 + threadIdx.x;
     const int64_t r = rbase + (q >> 3);
-    const float dl = a.mu[r] - a.mu0t[(int64_t)(kt >> 1) * a.mu0t_stride + rt * kTileTokens + (q >> 3)];
     const float iz = a.inv_z[r];
-    const uint4 x = p1[q], y = p2[q];
+    const uint4 y = p2[q];
     float d[8];
-    d[0] = (bf16_lo(x.x) - dl) * (bf16_lo(y.x) * iz); d[1] = (bf16_hi(x.x) - dl) * (bf16_hi(y.x) * iz);
-    d[2] = (bf16_lo(x.y) - dl) * (bf16_lo(y.y) * iz); d[3] = (bf16_hi(x.y) - dl) * (bf16_hi(y.y) * iz);
-    d[4] = (bf16_lo(x.z) - dl) * (bf16_lo(y.z) * iz); d[5] = (bf16_hi(x.z) - dl) * (bf16_hi(y.z) * iz);
-    d[6] = (bf16_lo(x.w) - dl) * (bf16_lo(y.w) * iz); d[7] = (bf16_hi(x.w) - dl) * (bf16_hi(y.w) * iz);
-    uint4 o;
-    o.x = pack_bf16(d[0], d[1]); o.y = pack_bf16(d[2], d[3]);
-    o.z = pack_bf16(d[4], d[5]); o.w = pack_bf16(d[6], d[7]);
-    p1[q] = o;
+    if (SAMPLED) {
+      const float c = a.cr[r], ciz = -c * iz;
+      d[0] = bf16_lo(y.x) * ciz; d[1] = bf16_hi(y.x) * ciz; d[2] = bf16_lo(y.y) * ciz; d[3] = bf16_hi(y.y) * ciz;
+      d[4] = bf16_lo(y.z) * ciz; d[5] = bf16_hi(y.z) * ciz; d[6] = bf16_lo(y.w) * ciz; d[7] = bf16_hi(y.w) * ciz;
+      // entries of this vector: 64 kt + 8 (logical chunk) + e
+      const int rl = q >> 3, v0 = kt * kBK + (((q & 7) ^ ((rl >> 1) & 7)) << 3);
+      const int e_y = a.yid[r] - v0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] += (e == e_y) ? c : 0.f;
+    } else {
+      const float dl = a.mu[r] - a.mu0t[(int64_t)(kt >> 1) * a.mu0t_stride + rt * kTileTokens + (q >> 3)];
+      const uint4 x = p1[q];
+      d[0] = (bf16_lo(x.x) - dl) * (bf16_lo(y.x) * iz); d[1] = (bf16_hi(x.x) - dl) * (bf16_hi(y.x) * iz);
+      d[2] = (bf16_lo(x.y) - dl) * (bf16_lo(y.y) * iz); d[3] = (bf16_hi(x.y) - dl) * (bf16_hi(y.y) * iz);
+      d[4] = (bf16_lo(x.z) - dl) * (bf16_lo(y.z) * iz); d[5] = (bf16_hi(x.z) - dl) * (bf16_hi(y.z) * iz);
+      d[6] = (bf16_lo(x.w) - dl) * (bf16_lo(y.w) * iz); d[7] = (bf16_hi(x.w) - dl) * (bf16_hi(y.w) * iz);
+      uint4 o;
+      o.x = pack_bf16(d[0], d[1]); o.y = pack_bf16(d[2], d[3]);
+      o.z = pack_bf16(d[4], d[5]); o.w = pack_bf16(d[6], d[7]);
+      p1[q] = o;
+    }
     if (TR) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) dz[i][e] = d[e];
@@ -1652,7 +1668,6 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   const bool head = p->dW_prefix || p->dW_full;
   if ((diag || p->t_logp || sampled || head) && !L.single) return ADWIN_E_MODE;
   if (sampled && !p->ids) return ADWIN_E_NULL;
-  if (head && sampled) return ADWIN_E_MODE;
   if (p->dW_full && p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
   if (((uintptr_t)p->dW_prefix | (uintptr_t)p->dW_full) & 15) return ADWIN_E_ALIGN;
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -1793,19 +1808,25 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         ADWIN_HIP_TRY(hipGetLastError());
         ga.slab_row0 = r0;
         ga.row_tiles = (int)(rows / kGradTile);
+        CombineArgs ca;
+        ca.slab = (uint4*)la.slab; ca.e2_vec = la.e2_off / 8;
+        ca.mu = ms.mu_out; ca.inv_z = ms.inv_z; ca.row0 = r0; ca.nk = ga.nk_total;
+        ca.mu0t = la.mu0t; ca.mu0t_stride = la.mu0t_stride;
+        ca.dzT_p = p->dW_prefix ? (uint4*)(ws + L.o_dzT_p) : nullptr;
+        ca.dzT_f = p->dW_full ? (uint4*)(ws + L.o_dzT_f) : nullptr;
+        ca.nkr = (int)(rows / kBK); ca.pl = pl; ca.n_rows = hp.n_rows; ca.grad_scale = p->grad_scale;
+        ca.cr = (const float*)(ws + L.o_cr); ca.yid = (const int32_t*)(ws + L.o_yid);
+        const dim3 cgrid((unsigned)ga.nk_total, (unsigned)ga.row_tiles);
         if (sampled) {       // contract the E2 factor; c_t and W_s[y_t] enter in finalize_kernel
           ga.slab = la.slab + la.e2_off;
           ga.half_tiles = 0;                       // output rows in the second half of g
+          if (head) {        // the transposed operand of the head-weight GEMMs; the slab stays as it is
+            phase(ADWIN_PHASE_DZ);
+            combine_kernel<true, true><<<cgrid, 256, 0, stream>>>(ca);
+            ADWIN_HIP_TRY(hipGetLastError());
+          }
         } else {
           phase(ADWIN_PHASE_DZ);
-          CombineArgs ca;
-          ca.slab = (uint4*)la.slab; ca.e2_vec = la.e2_off / 8;
-          ca.mu = ms.mu_out; ca.inv_z = ms.inv_z; ca.row0 = r0; ca.nk = ga.nk_total;
-          ca.mu0t = la.mu0t; ca.mu0t_stride = la.mu0t_stride;
-          ca.dzT_p = p->dW_prefix ? (uint4*)(ws + L.o_dzT_p) : nullptr;
-          ca.dzT_f = p->dW_full ? (uint4*)(ws + L.o_dzT_f) : nullptr;
-          ca.nkr = (int)(rows / kBK); ca.pl = pl; ca.n_rows = hp.n_rows; ca.grad_scale = p->grad_scale;
-          const dim3 cgrid((unsigned)ga.nk_total, (unsigned)ga.row_tiles);
           if (head) combine_kernel<true><<<cgrid, 256, 0, stream>>>(ca);
           else combine_kernel<false><<<cgrid, 256, 0, stream>>>(ca);
           ADWIN_HIP_TRY(hipGetLastError());

@@ -370,6 +370,21 @@ def test_head_weight_gradient(B, name, reduction):
     _check_head_gradient(got, ref, probe)
 
 
+@pytest.mark.parametrize("name", ["tiny_probe", "ragged_small", "ragged_mid"])
+def test_head_weight_gradient_sampled_estimator(B, name):
+    """dW_s under Eq. 4's estimator: sum_t w_t c_t (e_{y_t} - p_s)^T h_s[t]."""
+    w = synth.workload(name)
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SEQ_MEAN, grad_scale=2.0, mode=w.mode, estimator=O.EST_SAMPLED,
+                      head_gradient=True)
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SEQ_MEAN, grad_scale=2.0, want=WANT_HEAD,
+                     estimator=B.ADWIN_EST_SAMPLED)
+    _check_fused(w, got, ref, O.RED_SEQ_MEAN)
+    _check_head_gradient(got, ref, True)
+
+
 def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
     """Rows split over several slabs: every slab adds its product to dW."""
     monkeypatch.setenv("ADWIN_SLAB_ROWS", "512")

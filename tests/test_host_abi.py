@@ -121,11 +121,10 @@ def test_workspace_bytes_and_argument_errors_without_gpu(B):
     assert st(_problem(B), 4096 + 8, n) == B.ADWIN_E_WORKSPACE     # misaligned
     assert st(_problem(B), 4096, n - 256) == B.ADWIN_E_WORKSPACE   # too small
     assert B.lib.adwin_opd_fused(None, 0, 0, None) == B.ADWIN_E_NULL
-    # head-weight gradient: expected-KL estimator only, dW_full only with the full-rollout pass
+    # head-weight gradient: dW_full only with the full-rollout pass
     # (all rejected before anything is enqueued; the fake workspace is never touched)
     def st_ws(p):
         return st(p, 4096, B.adwin_opd_workspace_bytes(p))
-    assert st_ws(_problem(B, dW_prefix=8192, estimator=B.ADWIN_EST_SAMPLED, ids=4096)) == B.ADWIN_E_MODE
     assert st_ws(_problem(B, mode=0, dW_full=8192)) == B.ADWIN_E_MODE
     assert st_ws(_problem(B, dW_prefix=8200)) == B.ADWIN_E_ALIGN
     # rollout summaries need the per-row outputs they reduce
