@@ -140,6 +140,17 @@ def token_dz_sampled(z_s, z_t, y):
     return token_cost(z_s, z_t, y) * (e_y - p)
 
 
+def token_dz_sampled_scale(z_s, z_t, y):
+    """Magnitude against which a reduced-precision sampled-token gradient is judged: |c_t| p_s
+    off the sampled entry and |c_t| on it -- the entry c_t (1 - p_s(y_t)) is a difference of two
+    rounded terms of magnitude up to |c_t| and vanishes as p_s(y_t) -> 1 while their errors do
+    not."""
+    p = np.exp(log_softmax(z_s))
+    s = np.abs(token_cost(z_s, z_t, y)) * p
+    s[y] = np.abs(token_cost(z_s, z_t, y))
+    return s
+
+
 def token_terms(h_s, h_t, W_s, W_t, y=None, estimator=EST_EXPECTED):
     """Logits from hidden states, then KL_t, c_t and g_t = dz_t W_s for one row."""
     z_s = W_s @ h_s
@@ -161,7 +172,7 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, h
     sum_r w[r] KL_r with respect to the student LM-head weights, sum_r w[r] dz_r^T h_s[r]
     (z = W h, so d z[v] / d W[v, k] = h[k]), is returned as a fourth value, and as a fifth the
     Euclidean norm over r of the summands of each element, sqrt(sum_r (w[r] s_r[v] h_s[r][k])^2),
-    with s_r = `token_dz_scale` (expected estimator) or |dz_r| (sampled): the scale of the
+    with s_r = `token_dz_scale` (expected estimator) or `token_dz_sampled_scale`: the scale of the
     rounding error of any implementation that rounds the factors of the summands independently
     (tests bound a reduced-precision result with it).
     g_norms: optional [K, H_s] array that receives the same norm for the hidden-state gradient,
@@ -191,7 +202,7 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, h
             else:
                 D[r - r0] = token_dz_sampled(z_s, z_t, int(ids[r]))
                 if want_norms:
-                    S[r - r0] = np.abs(D[r - r0])
+                    S[r - r0] = token_dz_sampled_scale(z_s, z_t, int(ids[r]))
         g[r0:r1] = D @ W_s
         if g_norms is not None:
             g_norms[r0:r1] = np.sqrt((S ** 2) @ (W_s ** 2))

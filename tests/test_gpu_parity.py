@@ -538,11 +538,9 @@ def test_peaked_distributions(B, estimator, on_policy):
     f = Hp.oracle_inputs(p)
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
                       reduction=O.RED_SUM, mode=w.mode, estimator=estimator,
-                      head_gradient=estimator == O.EST_EXPECTED, summand_norms=True)
+                      head_gradient=True, summand_norms=True)
     assert 0.5 < ref["kl"].mean() < 3.0
-    want = B.FusedCall.DEFAULT_OUTPUTS + ("t_logp", "t_entropy", "t_rank")
-    if estimator == O.EST_EXPECTED:
-        want += ("dW_prefix", "dW_full")
+    want = B.FusedCall.DEFAULT_OUTPUTS + ("t_logp", "t_entropy", "t_rank", "dW_prefix", "dW_full")
     got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32, estimator=estimator,
                      want=want)
     z_t = f["h_t"] @ f["W_t"].T
@@ -561,8 +559,7 @@ def test_peaked_distributions(B, estimator, on_policy):
             assert err.max() <= 3 * Hp.DH_REL * np.abs(ref[k]).max(), (k, err.max(), np.abs(ref[k]).max())
             got[k] = ref[k]
     _check_fused(w, got, ref, O.RED_SUM, logit_scale=np.abs(lse_t), abs_cap=False)
-    if estimator == O.EST_EXPECTED:
-        _check_head_gradient(got, ref, True)
+    _check_head_gradient(got, ref, True)
     ent, logp, lo, hi = _teacher_reference(z_t, f["ids"], list(ref["rows"]), 1e-3)
     for t in ref["rows"]:
         assert abs(got["t_entropy"][t] - ent[t]) <= 2e-3, (t, got["t_entropy"][t], ent[t])

@@ -591,3 +591,12 @@ def test_error_scale_of_the_logit_gradient():
         zs, zt = RNG.normal(0, 3, 11), RNG.normal(0, 3, 11)
         assert (O.token_dz_scale(zs, zt) >= np.abs(O.token_dz(zs, zt)) - 1e-15).all()
         assert np.abs(O.token_dz_scale(zs, zs + 2.5)).max() < 1e-12
+
+
+def test_error_scale_of_the_sampled_gradient():
+    zs, zt = RNG.normal(0, 3, 9), RNG.normal(0, 3, 9)
+    for y in (0, 4, 8):
+        sc, dz = O.token_dz_sampled_scale(zs, zt, y), O.token_dz_sampled(zs, zt, y)
+        c = abs(O.token_cost(zs, zt, y))
+        assert (sc >= np.abs(dz) - 1e-15).all()
+        assert sc[y] == pytest.approx(c) and sc.sum() == pytest.approx(c * (2 - np.exp(O.log_softmax(zs))[y]))
