@@ -87,6 +87,11 @@ extern "C" {
  * Problem description for the fused path (hidden states in, Sec. 4.1 / 4.2).
  * Limits: 1 <= B; 0 <= T < 2^31; V a positive multiple of 8; H_s and H_t positive
  * multiples of 64 (the k-extent of one staged MFMA tile).
+ * Outputs are optional (NULL = not wanted).  When none of the requested outputs depends on
+ * the gradients -- only kl, c, the window losses, n_out / n_adm_out / status_dev, the
+ * diagnostics and their summaries, and batch in mode PREFIX_ONLY -- the call is a forward-only
+ * statistics pass: no gradient factor is stored or contracted, and the workspace is smaller
+ * accordingly (adwin_opd_workspace_bytes looks at the same pointers).
  */
 typedef struct adwin_opd_problem {
   size_t  struct_bytes;      /* sizeof(adwin_opd_problem), checked                            */

@@ -214,7 +214,8 @@ class FusedCall:
 
     def __init__(self, h_s, h_t, W_s, W_t, ids, offsets, window, mode=ADWIN_PREFIX_ONLY,
                  reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0, dh_dtype=ADWIN_DT_F32,
-                 want=DEFAULT_OUTPUTS, topk=0, device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED):
+                 want=DEFAULT_OUTPUTS, topk=0, device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED,
+                 cand_outputs=True):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.candidates = None if candidates is None else _host_i32(candidates)
         self.inputs = (h_s, h_t, W_s, W_t, ids)
@@ -260,7 +261,7 @@ class FusedCall:
                 shp, dt = shapes[k]
                 self.out[k] = torch.empty(shp, dtype=dt, device=dev)
                 setattr(p, k, _ptr(self.out[k]))
-            if K:
+            if K and cand_outputs:     # the audit's alignment outputs; cand_loss_share goes through `want`
                 for k, shp in (("cand_rho_pooled", (K, B)), ("cand_rho_field", (K, B)),
                                ("cand_batch", (K, 4))):
                     self.out[k] = torch.empty(shp, dtype=torch.float32, device=dev)

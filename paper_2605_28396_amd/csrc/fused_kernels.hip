@@ -153,6 +153,8 @@ constexpr int kModeSingle = 2;  // single sweep: fixed-reference statistics + D/
 constexpr int kModeSingleDiag = 3;  // the same plus the teacher-side diagnostics of Sec. 3.1
 constexpr int kModeSingleE2 = 4;      // single sweep that emits only the E2 factor (sampled estimator)
 constexpr int kModeSingleE2Diag = 5;  // the same plus the diagnostics
+constexpr int kModeSingleFwd = 6;     // single sweep, statistics only: nothing is written to the slab
+constexpr int kModeSingleFwdDiag = 7; // the same plus the diagnostics
 
 // Running per-token statistics held by one lane for its two token columns.
 struct LaneStats { float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2]; };
@@ -240,7 +242,7 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
 // only maintained in diagnostics mode.
 struct LaneSums { float Z_s[2], A_s[2], Z_t[2], B_t[2]; int cnt[2]; };
 
-template <bool TAIL, bool DIAG, bool WRITE_D>
+template <bool TAIL, bool DIAG, bool WRITE_D, bool WRITE_E2>
 __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                 LaneSums& sm, const float (&rs2)[2],
                                                 const float (&rt2)[2], float (&mu0)[2],
@@ -279,7 +281,7 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
         uint2 o2;
         o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
         const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
-        *(uint2*)(out + e2_off + at) = o2;
+        if (WRITE_E2) *(uint2*)(out + e2_off + at) = o2;
       }
     sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
     if (DIAG) { sm.B_t[fn] = Bt; sm.cnt[fn] = cnt; }
@@ -586,7 +588,8 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 
   LaneStats st;
   LaneSums sm;
-  constexpr bool kDiag = MODE == kModeSingleDiag || MODE == kModeSingleE2Diag;
+  constexpr bool kDiag = MODE == kModeSingleDiag || MODE == kModeSingleE2Diag || MODE == kModeSingleFwdDiag;
+  constexpr bool kWriteE2 = MODE < kModeSingleFwd;
   constexpr bool kWriteD = MODE == kModeSingle || MODE == kModeSingleDiag;
   constexpr bool kSingle = MODE >= kModeSingle;
   float lse2[2], mu[2], rs2[2], rt2[2];   // per-row inputs of the dz / single-sweep epilogues
@@ -698,9 +701,9 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       if (MODE == kModeDz) {
         dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
       } else if (tail) {
-        single_epilogue<true, kDiag, kWriteD>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
+        single_epilogue<true, kDiag, kWriteD, kWriteE2>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
       } else {
-        single_epilogue<false, kDiag, kWriteD>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
+        single_epilogue<false, kDiag, kWriteD, kWriteE2>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
       }
     }
   }
@@ -1460,6 +1463,16 @@ static int env_int(const char* name, int dflt) {
   return v > 0 ? v : dflt;
 }
 
+// Whether any requested output depends on the per-row gradients.  Without one the single
+// sweep runs in its statistics-only mode (KL, c, losses, the diagnostics and their summaries):
+// no gradient factors are stored, combined or contracted.
+static bool needs_gradient(const adwin_opd_problem* p) {
+  const bool probe = p->mode == ADWIN_PREFIX_AND_FULL;
+  return p->dh_prefix || p->dh_full || p->rho_pooled || p->rho_field || p->dW_prefix || p->dW_full ||
+         (probe && (p->batch || (p->candidates && p->n_candidates > 0 &&
+                                 (p->cand_rho_pooled || p->cand_rho_field || p->cand_batch))));
+}
+
 static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) {
   FusedLayout L;
   const int64_t n_pad = hp.n_pad > 0 ? hp.n_pad : kTileTokens;
@@ -1527,8 +1540,10 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_ws_img = take(L.use_dma ? 2 * (size_t)L.Vp * (size_t)p->H_s : 0);
   L.o_ht_img = take(L.use_dma ? 2 * (size_t)n_pad * (size_t)p->H_t : 0);
   L.o_hs_img = take(L.use_dma ? 2 * (size_t)n_pad * (size_t)p->H_s : 0);
-  L.o_slab = take(2 * (size_t)halves * (size_t)slab * (size_t)L.Vp);
-  L.o_g = take(sizeof(float) * (size_t)ks * (size_t)halves * (size_t)n_pad * (size_t)p->H_s);
+  // statistics-only calls (no output depends on the gradients) need neither the slab nor g
+  const bool need_g = needs_gradient(p) || !L.single;
+  L.o_slab = take(need_g ? 2 * (size_t)halves * (size_t)slab * (size_t)L.Vp : 0);
+  L.o_g = take(need_g ? sizeof(float) * (size_t)ks * (size_t)halves * (size_t)n_pad * (size_t)p->H_s : 0);
   const size_t nch = (size_t)(hp.n_chunks > 0 ? hp.n_chunks : 1);
   L.o_pp = take(sizeof(float) * nch * (size_t)p->H_s);
   L.o_pf = take(sizeof(float) * nch * (size_t)p->H_s);
@@ -1613,6 +1628,12 @@ static hipError_t ensure_lds_opt_in() {
   e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingleE2Diag>,
                           hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
   if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingleFwd>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute((const void*)logit_pass_dma_kernel<kModeSingleFwdDiag>,
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDmaLds);
+  if (e != hipSuccess) return e;
   e = hipFuncSetAttribute((const void*)grad_gemm_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                           kGradLds);
   if (e != hipSuccess) return e;
@@ -1666,6 +1687,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   const bool sampled = p->estimator == ADWIN_EST_SAMPLED;
   // the diagnostics and the sampled estimator ride on the single-sweep kernels
   const bool head = p->dW_prefix || p->dW_full;
+  const bool need_g = needs_gradient(p) || !L.single;   // the statistics-only mode is a single-sweep mode
   if ((diag || p->t_logp || sampled || head) && !L.single) return ADWIN_E_MODE;
   if (sampled && !p->ids) return ADWIN_E_NULL;
   if (p->dW_full && p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
@@ -1703,7 +1725,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     const int n_tiles = (int)(n_pad / kTileTokens);
     // tile images of W_s^T for the gradient GEMM
     const int h_tiles = (p->H_s + kGradTile - 1) / kGradTile;
-    {
+    if (need_g) {
       dim3 g((unsigned)(L.Vp / kBK), (unsigned)h_tiles);
       wst_image_kernel<<<g, 256, 0, stream>>>((const uint16_t*)p->W_s, (uint16_t*)(ws + L.o_WsT), p->V,
                                               p->H_s, (int)(L.Vp / kBK));
@@ -1740,7 +1762,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     la.slab = (__bf16*)(ws + L.o_slab); la.Vp = L.Vp;
     la.ref_s2 = (const float*)(ws + L.o_lse2); la.ref_t2 = (const float*)(ws + L.o_ref_t2);
     la.mu0 = (const float*)(ws + L.o_mu); la.e2_off = 0;
-    la.mu0t = (L.single && !sampled) ? (float*)(ws + L.o_mu0t) : nullptr; la.mu0t_stride = L.slab_rows;
+    la.mu0t = (L.single && !sampled && need_g) ? (float*)(ws + L.o_mu0t) : nullptr; la.mu0t_stride = L.slab_rows;
     la.tg = env_int("ADWIN_TG", 4);
     la.Wt_img = (const char*)(ws + L.o_wt_img); la.Ws_img = (const char*)(ws + L.o_ws_img);
     la.ht_img = (const char*)(ws + L.o_ht_img); la.hs_img = (const char*)(ws + L.o_hs_img);
@@ -1792,7 +1814,9 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         const int groups = (la.n_tiles + la.tg - 1) / la.tg;
         phase(ADWIN_PHASE_STATS);
         const unsigned sweep_grid = (unsigned)(groups * la.tg * L.strips1);
-        if (sampled && diag) logit_pass_dma_kernel<kModeSingleE2Diag><<<sweep_grid, 256, kDmaLds, stream>>>(la);
+        if (!need_g && diag) logit_pass_dma_kernel<kModeSingleFwdDiag><<<sweep_grid, 256, kDmaLds, stream>>>(la);
+        else if (!need_g) logit_pass_dma_kernel<kModeSingleFwd><<<sweep_grid, 256, kDmaLds, stream>>>(la);
+        else if (sampled && diag) logit_pass_dma_kernel<kModeSingleE2Diag><<<sweep_grid, 256, kDmaLds, stream>>>(la);
         else if (sampled) logit_pass_dma_kernel<kModeSingleE2><<<sweep_grid, 256, kDmaLds, stream>>>(la);
         else if (diag) logit_pass_dma_kernel<kModeSingleDiag><<<sweep_grid, 256, kDmaLds, stream>>>(la);
         else logit_pass_dma_kernel<kModeSingle><<<sweep_grid, 256, kDmaLds, stream>>>(la);
@@ -1806,6 +1830,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         ms.row0 = r0; ms.rows = rows;
         merge_single_kernel<<<(unsigned)((rows + 3) / 4), 256, 0, stream>>>(ms);
         ADWIN_HIP_TRY(hipGetLastError());
+        if (!need_g) continue;
         ga.slab_row0 = r0;
         ga.row_tiles = (int)(rows / kGradTile);
         CombineArgs ca;
@@ -1902,7 +1927,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   }
   // finalize over every packed row (also zero-fills rows outside the windows)
   phase(ADWIN_PHASE_REDUCE);
-  if (p->T > 0) {
+  if (p->T > 0 && need_g) {
     FinalizeArgs f;
     f.pl = pl; f.B = p->B; f.T = p->T; f.probe = probe;
     f.g = gws; f.ksplit = L.ksplit; f.n_pad = n_pad; f.H = p->H_s;
@@ -1915,13 +1940,13 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     finalize_kernel<<<(unsigned)((p->T + 3) / 4), 256, 0, stream>>>(f);
     ADWIN_HIP_TRY(hipGetLastError());
   }
-  ADWIN_HIP_TRY(launch_segment_sums(pl, p->B, probe, klr, rownorm, seg, p->loss_prefix,
+  ADWIN_HIP_TRY(launch_segment_sums(pl, p->B, probe, klr, need_g ? rownorm : nullptr, seg, p->loss_prefix,
                                     p->loss_full, stream));
   PoolArgs pa;
   pa.pl = pl; pa.B = p->B; pa.probe = probe; pa.H = p->H_s; pa.g = gws;
   pa.pp = (float*)(ws + L.o_pp); pa.pf = (float*)(ws + L.o_pf);
   pa.up = (float*)(ws + L.o_up); pa.uf = (float*)(ws + L.o_uf);
-  if (probe) {
+  if (probe && need_g) {
     const unsigned hy = (unsigned)((p->H_s + 255) / 256);
     if (hp.n_chunks > 0) {
       pool_partial_kernel<<<dim3((unsigned)hp.n_chunks, hy), 256, 0, stream>>>(pa);
@@ -1931,12 +1956,13 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     ADWIN_HIP_TRY(hipGetLastError());
   }
   BatchArgs b{};
-  b.pl = pl; b.B = p->B; b.H = p->H_s; b.probe = probe; b.zero_grad = (p->grad_scale == 0.f);
+  b.pl = pl; b.B = p->B; b.H = need_g ? p->H_s : 0; b.probe = probe;
+  b.zero_grad = (p->grad_scale == 0.f) || !need_g;
   b.seg = seg; b.up = pa.up; b.uf = pa.uf; b.racc = (double*)(ws + L.o_racc);
   b.rho_pooled = p->rho_pooled; b.rho_field = p->rho_field; b.batch = p->batch;
   b.n_out = p->n_out; b.n_adm_out = p->n_adm_out; b.n_adm = hp.n_adm;
   ADWIN_HIP_TRY(launch_alignment_and_batch(b, stream));
-  if (probe && p->candidates && p->n_candidates > 0) {
+  if (probe && need_g && p->candidates && p->n_candidates > 0) {
     CandArgs ca{};
     ca.pl = pl; ca.B = p->B; ca.H = p->H_s; ca.K = p->n_candidates;
     ca.reduction = p->reduction; ca.zero_grad = (p->grad_scale == 0.f);

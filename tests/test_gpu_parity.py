@@ -600,3 +600,33 @@ def test_peaked_distributions_other_paths(B, monkeypatch):
         assert (np.abs(got[k] - ref[k]) <= tol).all(), k
         got[k] = ref[k]
     _check_fused(w, got, ref, O.RED_SUM, logit_scale=np.abs(lse_t), abs_cap=False)
+
+
+@pytest.mark.parametrize("name", ["ragged_small", "ragged_mid", "tiny"])
+def test_statistics_only_call(B, name):
+    """No requested output depends on the gradients: the call runs the sweep without storing or
+    contracting gradient factors, needs a smaller workspace, and returns the same values."""
+    w = synth.workload(name)
+    p = synth.hidden_problem(w)
+    d = {k: v.cuda() for k, v in p.items()}
+    probe = w.mode == synth.MODE_PREFIX_AND_FULL
+    fwd = ("kl", "c", "loss_prefix", "loss_full", "n_out", "n_adm_out", "status_dev",
+           "t_logp", "t_entropy", "t_rank", "t_first_reject", "t_logp_mean")
+    if probe:
+        fwd += ("cand_loss_share",)
+    else:
+        fwd += ("batch",)
+    cands = [5, 64, 300] if probe else None
+    full = B.FusedCall(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window, mode=w.mode,
+                       want=fwd + ("dh_prefix",), topk=50, candidates=cands)
+    only = B.FusedCall(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window, mode=w.mode,
+                       want=fwd, topk=50, candidates=cands, cand_outputs=False)
+    assert only.workspace_bytes < full.workspace_bytes
+    assert full.run() == 0 and only.run() == 0
+    torch.cuda.synchronize()
+    for k in fwd:
+        assert torch.equal(only.out[k], full.out[k]), k
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window, mode=w.mode)
+    Hp.assert_kl(only.out["kl"].cpu().numpy(), ref["kl"])
+    Hp.assert_close_rel(only.out["loss_prefix"].cpu().numpy(), ref["loss_prefix"], Hp.LOSS_REL, "loss_prefix")
