@@ -199,3 +199,12 @@ def test_candidate_argument_errors_without_gpu(B):
     assert st(_problem(B, mode=1, candidates=c.ctypes.data, n_candidates=17)) == B.ADWIN_E_SHAPE
     with_c = B.adwin_opd_workspace_bytes(_problem(B, mode=1, candidates=c.ctypes.data, n_candidates=2))
     assert with_c > B.adwin_opd_workspace_bytes(_problem(B, mode=1))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One process, one GPU: the benchmark says so instead of starting a multi-GPU run."""
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
