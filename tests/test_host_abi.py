@@ -208,3 +208,20 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_launch_info_without_gpu(B, monkeypatch):
+    """Rows, padding and slabs of a call as the library will launch it (pure host)."""
+    info = B.adwin_opd_fused_launch_info(_problem(B, mode=1))
+    assert info == {"rows": 100, "padded_rows": 256, "slab_rows": 256, "slabs": 1}
+    info = B.adwin_opd_fused_launch_info(_problem(B, mode=0))          # windows 16 and 100 on lengths 40, 60
+    assert info["rows"] == 16 + 60 and info["padded_rows"] == 256 and info["slabs"] == 1
+    big = _problem(B, mode=1)
+    off = np.array([0, 30000, 50000], np.int64); win = np.array([1, 1], np.int32)
+    big.T, big.offsets, big.window = 50000, off.ctypes.data, win.ctypes.data
+    info = B.adwin_opd_fused_launch_info(big)
+    assert info["rows"] == 50000 and info["padded_rows"] == 50176
+    assert info["slabs"] * info["slab_rows"] >= info["padded_rows"] > (info["slabs"] - 1) * info["slab_rows"]
+    assert info["slab_rows"] % 256 == 0 and 4096 <= info["slab_rows"] <= 16384
+    monkeypatch.setenv("ADWIN_SLAB_ROWS", "1000")                      # rounded up to whole token tiles
+    assert B.adwin_opd_fused_launch_info(big)["slab_rows"] == 1024
