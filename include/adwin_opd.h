@@ -50,7 +50,8 @@ extern "C" {
 #define ADWIN_E_WINDOW     -4  /* a window is negative                                         */
 #define ADWIN_E_ALIGN      -5  /* a device pointer is not 16-byte aligned                      */
 #define ADWIN_E_WORKSPACE  -6  /* workspace NULL, misaligned (256 B) or too small              */
-#define ADWIN_E_MODE       -7  /* unknown mode / reduction / dh_dtype, or struct_bytes mismatch */
+#define ADWIN_E_MODE       -7  /* unknown mode / reduction / dh_dtype / estimator, struct_bytes  */
+                               /* mismatch, or an option the selected scheme does not offer     */
 #define ADWIN_E_HIP        -8  /* a HIP call or kernel launch failed                           */
 
 /* mode */
@@ -87,6 +88,10 @@ extern "C" {
  * Problem description for the fused path (hidden states in, Sec. 4.1 / 4.2).
  * Limits: 1 <= B; 0 <= T < 2^31; V a positive multiple of 8; H_s and H_t positive
  * multiples of 64 (the k-extent of one staged MFMA tile).
+ * The sampled estimator, the diagnostics (t_*) and the head-weight gradients (dW_*) ride on
+ * the single-sweep kernels, which need H_s >= 128 and H_t >= 128; with a smaller hidden size, or
+ * with the two-sweep scheme forced through the environment (ADWIN_TWO_SWEEP, ADWIN_NO_DMA), a
+ * call that asks for them returns ADWIN_E_MODE.
  * Outputs are optional (NULL = not wanted).  When none of the requested outputs depends on
  * the gradients -- only kl, c, the window losses, n_out / n_adm_out / status_dev, the
  * diagnostics and their summaries, and batch in mode PREFIX_ONLY -- the call is a forward-only
