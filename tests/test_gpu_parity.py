@@ -630,3 +630,39 @@ def test_statistics_only_call(B, name):
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window, mode=w.mode)
     Hp.assert_kl(only.out["kl"].cpu().numpy(), ref["kl"])
     Hp.assert_close_rel(only.out["loss_prefix"].cpu().numpy(), ref["loss_prefix"], Hp.LOSS_REL, "loss_prefix")
+
+
+def test_many_short_rollouts(B):
+    """1,500 rollouts of 0..30 tokens (many empty, many with window 0 or beyond the end): the
+    per-rollout kernels, the chunked pooled sums and the candidate audit at a large B."""
+    g = np.random.default_rng(20260528)
+    nb = 1500
+    lens = g.integers(0, 30, size=nb, endpoint=True)
+    win = g.integers(0, 40, size=nb, endpoint=True).astype(np.int32)
+    w = synth.Workload("many_short", 264, 128, 128, synth._offsets(lens), win, synth.MODE_PREFIX_AND_FULL)
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    cands = [1, 3, 8, 20, 64]
+    for reduction in (O.RED_SEQ_MEAN, O.RED_TOKEN_MEAN):
+        ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                          reduction=reduction, mode=w.mode, summand_norms=True)
+        got = _run_fused(B, w, p, "cuda", reduction=reduction, dh_dtype=B.ADWIN_DT_F32, candidates=cands,
+                         want=B.FusedCall.DEFAULT_OUTPUTS + ("t_rank", "t_logp", "t_first_reject", "t_logp_mean",
+                                                            "cand_loss_share"), topk=100)
+        # gradient elements: V = 264 is a tiny vocabulary (see test_minimal_and_odd_shapes)
+        a_p, a_f = O.row_weights(lens, np.minimum(win, lens), reduction)
+        seq = np.repeat(np.arange(nb), lens)
+        adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
+        for k, wt in (("dh_prefix", a_p[seq] * adm), ("dh_full", a_f[seq])):
+            tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * np.abs(wt)[:, None] + 1e-6 * np.abs(ref[k]).max()
+            assert (np.abs(got[k] - ref[k]) <= tol).all(), k
+            got[k] = ref[k]
+        _check_fused(w, got, ref, reduction)
+        aud = O.audit_candidates(ref["g"], w.offsets, cands, reduction)
+        assert np.all(np.abs(got["cand_rho_pooled"] - aud["rho_pooled"]) <= Hp.RHO_ABS)
+        assert np.all(np.abs(got["cand_rho_field"] - aud["rho_field"]) <= Hp.RHO_ABS)
+        comp = lens
+        ranks = [got["t_rank"][w.offsets[i]:w.offsets[i + 1]] for i in range(nb)]
+        assert np.array_equal(got["t_first_reject"], [O.first_rejection(r, 100) for r in ranks])
+        assert np.allclose(got["cand_loss_share"], O.loss_share(got["kl"].astype(np.float64), w.offsets, comp, cands),
+                           rtol=1e-6, atol=1e-7)
