@@ -666,3 +666,28 @@ def test_many_short_rollouts(B):
         assert np.array_equal(got["t_first_reject"], [O.first_rejection(r, 100) for r in ranks])
         assert np.allclose(got["cand_loss_share"], O.loss_share(got["kl"].astype(np.float64), w.offsets, comp, cands),
                            rtol=1e-6, atol=1e-7)
+
+
+def test_one_long_rollout(B):
+    """A single rollout of 70,000 tokens (several slabs at the forced slab size, hundreds of
+    reduction chunks): windows and candidates far inside, at and beyond its end."""
+    w = synth.Workload("one_long", 264, 128, 128, synth._offsets([70000]), np.array([33333], np.int32),
+                       synth.MODE_PREFIX_AND_FULL)
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    cands = [1, 1000, 33333, 65536, 100000]
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SEQ_MEAN, mode=w.mode, summand_norms=True, block=256)
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SEQ_MEAN, dh_dtype=B.ADWIN_DT_F32, candidates=cands)
+    a_p, a_f = O.row_weights(np.array([70000]), np.array([33333]), O.RED_SEQ_MEAN)
+    adm = np.arange(w.T) < 33333
+    for k, wt in (("dh_prefix", a_p[0] * adm), ("dh_full", np.full(w.T, a_f[0]))):
+        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * np.abs(wt)[:, None] + 1e-6 * np.abs(ref[k]).max()
+        assert (np.abs(got[k] - ref[k]) <= tol).all(), k
+        got[k] = ref[k]
+    _check_fused(w, got, ref, O.RED_SEQ_MEAN)
+    aud = O.audit_candidates(ref["g"], w.offsets, cands, O.RED_SEQ_MEAN)
+    assert np.all(np.abs(got["cand_rho_pooled"] - aud["rho_pooled"]) <= Hp.RHO_ABS)
+    assert np.all(np.abs(got["cand_rho_field"] - aud["rho_field"]) <= Hp.RHO_ABS)
+    assert abs(got["cand_rho_pooled"][2, 0] - got["rho_pooled"][0]) <= 1e-6       # the call's own window
+    assert got["cand_rho_field"][3, 0] < 1.0 and got["cand_rho_field"][4, 0] == pytest.approx(1.0, abs=1e-6)
