@@ -1114,13 +1114,13 @@ __global__ __launch_bounds__(256) void hst_image_kernel(HstImageArgs a) {
 // ---------------------------------------------------------------------------------------
 // Pass 3: g[r][h] = sum_v dz[r][v] W_s[v][h].  256 x 256 output tile, 2 x 2 waves of
 // 128 x 128.  A = slab rows (i = row), B = rows of W_s^T (j = hidden column, contiguous in
-// g).  The k-steps (one block of each operand, 64 KiB together) go through two LDS stages
-// by direct global->LDS loads.  Per k-step a wave issues its 16 wave-loads of the next
-// k-step in the shadow of the first MFMAs, so that they have the rest of the step (about
-// 1500 matrix-pipe cycles) to land.  The one barrier per k-step sits before the last of
-// the four k16 sub-steps: by then every fragment of the current stage is in registers, so
-// the last sub-step's MFMAs cover the LDS reads of the next stage's first fragments and the
-// matrix pipe never waits for LDS after a barrier.
+// g).  The k-steps (one 32 KiB block of each operand) go through five block buffers in the
+// LDS, three for A and two for B, by direct global->LDS loads.  Per k-step a wave issues
+// its 16 wave-loads of the k-step after next in the shadow of MFMAs (see grad_kstep), so
+// that they have a k-step or more (upwards of 2000 matrix-pipe cycles) to land.  The one
+// barrier per k-step sits before the last of the four k16 sub-steps: by then every fragment
+// of the current blocks is in registers, so the last sub-step's MFMAs cover the LDS reads of
+// the next blocks' first fragments and the matrix pipe never waits for LDS after a barrier.
 // ---------------------------------------------------------------------------------------
 struct GradArgs {
   const __bf16* slab; const __bf16* WsT;   // tile images
@@ -1135,18 +1135,23 @@ struct GradArgs {
   int accumulate;           // add to g instead of overwriting it
 };
 
-constexpr int kGradStage = 2 * kImgBytes;     // 64 KiB
-constexpr int kGradLds = 2 * kGradStage;      // 128 KiB
+constexpr int kGradABufs = 3;                                 // A blocks in flight or in use
+constexpr int kGradBOff = kGradABufs * kImgBytes;             // the two B buffers follow
+constexpr int kGradLds = (kGradABufs + 2) * kImgBytes;        // 160 KiB
 
-// HEAD: the B block of the next k-step is loaded in sub-step 0 (into the other stage);
-// TAIL: the A block of the k-step after next in sub-step 3 (into this stage, which no wave
-// reads any more once it has passed this step's barrier).  Every block thus has a whole
-// k-step between its first wave-load and the barrier that publishes it.
-template <bool HEAD, bool TAIL, bool LAST>
+// LOADS: in k-step s the A block of k-step s + 2 is loaded in sub-step 1 (into the third A
+// buffer, which no wave reads any more once it has passed the previous step's barrier) and
+// the B block of k-step s + 2 in sub-step 3, after this step's barrier, into the B buffer
+// this step has just finished reading.  The A blocks are the stream that comes from HBM (a
+// slab block is used by the h tiles of one row tile and never again) and get a lead of a
+// k-step and a half, the B blocks, shared by every row tile and mostly found in the L2, one
+// k-step.  Loads return in order: the wait before the barrier leaves the youngest eight,
+// this step's A loads, in flight.
+template <bool LOADS, bool LAST>
 __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][4],
                                            const char* curA, const char* curB, const char* nxtA,
-                                           const char* nxtB, int lane, uint32_t lds_cur, uint32_t lds_nxt,
-                                           uint32_t voff, const char* sB1, const char* sA2) {
+                                           const char* nxtB, int lane, uint32_t lds_a2, uint32_t lds_b2,
+                                           uint32_t voff, const char* sB2, const char* sA2) {
   const int key = (lane >> 1) & 7, half = lane >> 5;
   const int rowoff = (lane & 31) * kRowBytes;
   int sw[4];
@@ -1158,7 +1163,7 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
                                                       acc[I][J], 0, 0, 0);                    \
   ADWIN_FENCE
   // side operation M (0..15) in the shadow of MFMA M of sub-step KK: fragment reads of the
-  // next sub-step, then (sub-steps 0 and 1) the 16 wave-loads of the next k-step: 8 KiB
+  // next sub-step, then (sub-steps 1 and 3) the wave-loads of the k-step after next: 4 KiB
   // groups d = 0..7 of the A block, then of the B block, each offset by this wave's 1 KiB
 #define ADWIN_SIDE(KK, M)                                                                           \
   if constexpr ((KK) < 3 && (M) < 8) {                                                              \
@@ -1167,17 +1172,17 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
     else                                                                                            \
       fb[((KK) + 1) & 1][(M) >> 1] = *(const bf16x8*)(curB + ((M) >> 1) * 32 * kRowBytes + sw[(KK) + 1]); \
     ADWIN_FENCE                                                                                     \
-  } else if constexpr ((KK) == 0 && (M) >= 8 && HEAD) {                                             \
-    dma16(lds_nxt + (uint32_t)kImgBytes + (uint32_t)((M) - 8) * 4096u, voff, sB1 + ((M) - 8) * 4096); \
+  } else if constexpr ((KK) == 1 && (M) >= 8 && LOADS) {                                            \
+    dma16(lds_a2 + (uint32_t)((M) - 8) * 4096u, voff, sA2 + ((M) - 8) * 4096);                      \
+    ADWIN_FENCE                                                                                     \
+  } else if constexpr ((KK) == 3 && (M) >= 8 && LOADS) {                                            \
+    dma16(lds_b2 + (uint32_t)((M) - 8) * 4096u, voff, sB2 + ((M) - 8) * 4096);                      \
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 3 && (M) < 8 && !LAST) {                                             \
     if constexpr (((M) & 1) == 0)                                                                   \
       fa[0][(M) >> 1] = *(const bf16x8*)(nxtA + ((M) >> 1) * 32 * kRowBytes + sw[0]);               \
     else                                                                                            \
       fb[0][(M) >> 1] = *(const bf16x8*)(nxtB + ((M) >> 1) * 32 * kRowBytes + sw[0]);               \
-    ADWIN_FENCE                                                                                     \
-  } else if constexpr ((KK) == 3 && (M) >= 8 && TAIL) {                                             \
-    dma16(lds_cur + (uint32_t)((M) - 8) * 4096u, voff, sA2 + ((M) - 8) * 4096);                     \
     ADWIN_FENCE                                                                                     \
   }
 #define ADWIN_ROW(KK, I, M0)                                                    \
@@ -1191,7 +1196,8 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
   // every fragment of this stage is in registers; the next stage's loads must have landed
   // before its first fragments are read in the shadow of the last sub-step
   if constexpr (!LAST) {
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if constexpr (LOADS) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
   }
   ADWIN_FENCE
@@ -1234,16 +1240,16 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       for (int e = 0; e < 16; ++e) acc[fm][fn][e] = 0.f;
 
   if (nk > 0) {
-    // stage 0 of the first k-step, then its first fragments
+    // blocks of the first k-step, then its first fragments
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
       dma16(ldsw + (uint32_t)d * 4096u, voff, sA + d * 4096);
-      dma16(ldsw + (uint32_t)kImgBytes + (uint32_t)d * 4096u, voff, sB + d * 4096);
+      dma16(ldsw + (uint32_t)kGradBOff + (uint32_t)d * 4096u, voff, sB + d * 4096);
     }
     wait_vm<0>();
     __syncthreads();
     bf16x8 fa[2][4], fb[2][4];
-    const int waveA = wm * 128 * kRowBytes, waveB = kImgBytes + wn * 128 * kRowBytes;
+    const int waveA = wm * 128 * kRowBytes, waveB = kGradBOff + wn * 128 * kRowBytes;
     {
       const int key = (lane >> 1) & 7, half = lane >> 5;
       const int sw0 = (lane & 31) * kRowBytes + ((half ^ key) << 4);
@@ -1253,31 +1259,37 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
         fb[0][i] = *(const bf16x8*)(lds + waveB + i * 32 * kRowBytes + sw0);
       }
     }
-    // A block of k-step 1 (the loop loads B of s + 1 and A of s + 2 in k-step s)
+    // blocks of k-step 1 (k-step s of the loop loads those of k-step s + 2)
     if (nk > 1) {
 #pragma unroll
-      for (int d = 0; d < 8; ++d) dma16(ldsw + kGradStage + (uint32_t)d * 4096u, voff, sA + kImgBytes + d * 4096);
+      for (int d = 0; d < 8; ++d) dma16(ldsw + kImgBytes + (uint32_t)d * 4096u, voff, sA + kImgBytes + d * 4096);
+#pragma unroll
+      for (int d = 0; d < 8; ++d)
+        dma16(ldsw + kGradBOff + kImgBytes + (uint32_t)d * 4096u, voff, sB + kImgBytes + d * 4096);
     }
-    int s = 0;
+    // k-step s reads A buffer s % 3 and B buffer s % 2
+    int s = 0, ia = 0;
     for (; s + 2 < nk; ++s) {
-      const char* cur = lds + (s & 1) * kGradStage;
-      const char* nxt = lds + ((s + 1) & 1) * kGradStage;
-      grad_kstep<true, true, false>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
-                                    ldsw + (s & 1) * kGradStage, ldsw + ((s + 1) & 1) * kGradStage, voff,
-                                    sB + (int64_t)(s + 1) * kImgBytes, sA + (int64_t)(s + 2) * kImgBytes);
+      const int ia1 = ia == kGradABufs - 1 ? 0 : ia + 1, ia2 = ia1 == kGradABufs - 1 ? 0 : ia1 + 1;
+      const int ib = (s & 1) * kImgBytes, ib1 = kImgBytes - ib;
+      grad_kstep<true, false>(acc, fa, fb, lds + ia * kImgBytes + waveA, lds + ib + waveB,
+                              lds + ia1 * kImgBytes + waveA, lds + ib1 + waveB, lane,
+                              ldsw + ia2 * kImgBytes, ldsw + kGradBOff + ib, voff,
+                              sB + (int64_t)(s + 2) * kImgBytes, sA + (int64_t)(s + 2) * kImgBytes);
+      ia = ia1;
     }
     if (s + 1 < nk) {
-      const char* cur = lds + (s & 1) * kGradStage;
-      const char* nxt = lds + ((s + 1) & 1) * kGradStage;
-      grad_kstep<true, false, false>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
-                                     ldsw + (s & 1) * kGradStage, ldsw + ((s + 1) & 1) * kGradStage, voff,
-                                     sB + (int64_t)(s + 1) * kImgBytes, sA);
+      const int ia1 = ia == kGradABufs - 1 ? 0 : ia + 1;
+      const int ib = (s & 1) * kImgBytes, ib1 = kImgBytes - ib;
+      grad_kstep<false, false>(acc, fa, fb, lds + ia * kImgBytes + waveA, lds + ib + waveB,
+                               lds + ia1 * kImgBytes + waveA, lds + ib1 + waveB, lane, ldsw, ldsw, voff, sB, sA);
+      ia = ia1;
       ++s;
     }
     {
-      const char* cur = lds + (s & 1) * kGradStage;
-      grad_kstep<false, false, true>(acc, fa, fb, cur + waveA, cur + waveB, cur, cur, lane, ldsw, ldsw, voff,
-                                     sB, sA);
+      const int ib = (s & 1) * kImgBytes;
+      grad_kstep<false, true>(acc, fa, fb, lds + ia * kImgBytes + waveA, lds + ib + waveB, lds, lds, lane,
+                              ldsw, ldsw, voff, sB, sA);
     }
   }
   float* g = a.g + (int64_t)split * a.g_rows * a.H;
