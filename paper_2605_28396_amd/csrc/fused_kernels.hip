@@ -1168,9 +1168,9 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
 #define ADWIN_SIDE(KK, M)                                                                           \
   if constexpr ((KK) < 3 && (M) < 8) {                                                              \
     if constexpr (((M) & 1) == 0)                                                                   \
-      fa[((KK) + 1) & 1][(M) >> 1] = *(const bf16x8*)(curA + ((M) >> 1) * 32 * kRowBytes + sw[(KK) + 1]); \
+      fa[((KK) + 1) & 1][((M) >> 1) & 3] = *(const bf16x8*)(curA + (((M) >> 1) & 3) * 32 * kRowBytes + sw[(KK) + 1]); \
     else                                                                                            \
-      fb[((KK) + 1) & 1][(M) >> 1] = *(const bf16x8*)(curB + ((M) >> 1) * 32 * kRowBytes + sw[(KK) + 1]); \
+      fb[((KK) + 1) & 1][((M) >> 1) & 3] = *(const bf16x8*)(curB + (((M) >> 1) & 3) * 32 * kRowBytes + sw[(KK) + 1]); \
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 1 && (M) >= 8 && LOADS) {                                            \
     dma16(lds_a2 + (uint32_t)((M) - 8) * 4096u, voff, sA2 + ((M) - 8) * 4096);                      \
@@ -1180,9 +1180,9 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 3 && (M) < 8 && !LAST) {                                             \
     if constexpr (((M) & 1) == 0)                                                                   \
-      fa[0][(M) >> 1] = *(const bf16x8*)(nxtA + ((M) >> 1) * 32 * kRowBytes + sw[0]);               \
+      fa[0][((M) >> 1) & 3] = *(const bf16x8*)(nxtA + (((M) >> 1) & 3) * 32 * kRowBytes + sw[0]);               \
     else                                                                                            \
-      fb[0][(M) >> 1] = *(const bf16x8*)(nxtB + ((M) >> 1) * 32 * kRowBytes + sw[0]);               \
+      fb[0][((M) >> 1) & 3] = *(const bf16x8*)(nxtB + (((M) >> 1) & 3) * 32 * kRowBytes + sw[0]);               \
     ADWIN_FENCE                                                                                     \
   }
 #define ADWIN_ROW(KK, I, M0)                                                    \

@@ -111,13 +111,16 @@ class PhaseTimer {
  public:
   explicit PhaseTimer(hipStream_t st) : st_(st) {}
   ~PhaseTimer();
-  hipError_t begin(int phase);
-  hipError_t end();
+  // begin/end keep the first error they meet; collect returns it instead of times
+  void begin(int phase);
+  void end();
   hipError_t collect(float* phase_ms, int n_phases);
  private:
   struct Span { int phase; hipEvent_t a, b; };
   hipStream_t st_;
   std::vector<Span> spans_;
+  hipError_t err_ = hipSuccess;
+  bool open_ = false;
 };
 
 // RAII helper: no-op when the timer is null.

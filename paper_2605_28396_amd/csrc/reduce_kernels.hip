@@ -569,20 +569,25 @@ PhaseTimer::~PhaseTimer() {
     if (s.b) (void)hipEventDestroy(s.b);
   }
 }
-hipError_t PhaseTimer::begin(int phase) {
+void PhaseTimer::begin(int phase) {
+  open_ = false;
+  if (err_ != hipSuccess) return;
   Span s{phase, nullptr, nullptr};
-  hipError_t e = hipEventCreate(&s.a);
-  if (e != hipSuccess) return e;
-  e = hipEventCreate(&s.b);
-  if (e != hipSuccess) { (void)hipEventDestroy(s.a); return e; }
+  err_ = hipEventCreate(&s.a);
+  if (err_ != hipSuccess) return;
+  err_ = hipEventCreate(&s.b);
+  if (err_ != hipSuccess) { (void)hipEventDestroy(s.a); return; }
   spans_.push_back(s);
-  return hipEventRecord(s.a, st_);
+  err_ = hipEventRecord(s.a, st_);
+  open_ = err_ == hipSuccess;
 }
-hipError_t PhaseTimer::end() {
-  if (spans_.empty()) return hipSuccess;
-  return hipEventRecord(spans_.back().b, st_);
+void PhaseTimer::end() {
+  if (!open_) return;
+  open_ = false;
+  err_ = hipEventRecord(spans_.back().b, st_);
 }
 hipError_t PhaseTimer::collect(float* phase_ms, int n_phases) {
+  if (err_ != hipSuccess) return err_;
   hipError_t e = hipStreamSynchronize(st_);
   if (e != hipSuccess) return e;
   for (int k = 0; k < n_phases; ++k) phase_ms[k] = 0.f;
