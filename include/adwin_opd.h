@@ -19,18 +19,26 @@
  *   - extern "C"; every function returns an int status: 0 = ADWIN_OK, negative =
  *     error.  Nothing throws, aborts or exits.  On an argument error no output
  *     buffer is touched and nothing is enqueued.
- *   - "host" pointers are ordinary CPU memory read synchronously during the call;
+ *   - "host" pointers are ordinary CPU memory (pageable is fine) read synchronously
+ *     during the call and free to be reused once it returns: what the device needs
+ *     of them travels in kernel arguments, not in asynchronous copies;
  *     "device" pointers are HIP device memory on the current device, owned by the
  *     caller, row-major and contiguous, 16-byte aligned.
  *   - The library allocates no device memory and keeps no state between calls.  All
  *     scratch comes from the caller's workspace (size from *_workspace_bytes).
  *   - Work is enqueued on the caller's HIP stream (`hip_stream` is a hipStream_t, NULL
  *     = default stream) and the call returns without synchronising.  Outputs are
- *     defined once the stream has drained and the status was ADWIN_OK.
+ *     defined once the stream has drained and the status was ADWIN_OK.  After a first
+ *     call on the device (which sets kernel attributes) a call is nothing but kernel
+ *     launches, so it may be captured in a HIP graph; the host arrays are read at
+ *     capture, the device buffers at every replay.
  *   - Row t of the packed [T, .] arrays holds the hidden state (or logits) of the
  *     context (x, y_<t) and ids[t] = y_t: the caller has already applied the
  *     next-token shift and dropped prompt positions.
- *   - Results are deterministic: no floating-point atomics are used.
+ *   - Results are deterministic, bit for bit from call to call: every sum is taken in
+ *     a fixed order (where the head-weight gradient adds one slab's contribution to
+ *     the previous ones with the hardware's floating-point add, each element is added
+ *     to by exactly one lane per launch and the launches are ordered on the stream).
  */
 #ifndef ADWIN_OPD_H
 #define ADWIN_OPD_H

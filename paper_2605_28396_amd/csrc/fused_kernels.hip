@@ -1711,7 +1711,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   PhaseScope* scope = new PhaseScope(timer, ADWIN_PHASE_SETUP);
   struct ScopeGuard { PhaseScope*& s; ~ScopeGuard() { delete s; } } guard{scope};
   auto phase = [&](int ph) { delete scope; scope = new PhaseScope(timer, ph); };
-  ADWIN_HIP_TRY(hipMemcpyAsync(ws + L.o_plan, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
+  ADWIN_HIP_TRY(launch_upload(ws + L.o_plan, blob.data(), blob.size(), stream));
   DevicePlan pl = device_plan_at(ws + L.o_plan, p->B, (int32_t*)(ws + L.o_row_idx),
                                  (int32_t*)(ws + L.o_row_seq));
   float* klr = (float*)(ws + L.o_klr);

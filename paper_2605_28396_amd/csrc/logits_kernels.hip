@@ -472,7 +472,7 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
 
   std::vector<unsigned char> blob;
   HostPlan hp = make_host_plan(p->T, p->B, p->offsets, p->window, /*probe=*/0, p->reduction, &blob);
-  ADWIN_HIP_TRY(hipMemcpyAsync(ws + L.o_plan, blob.data(), blob.size(), hipMemcpyHostToDevice, stream));
+  ADWIN_HIP_TRY(launch_upload(ws + L.o_plan, blob.data(), blob.size(), stream));
   DevicePlan pl = device_plan_at(ws + L.o_plan, p->B, nullptr, nullptr);
   float* klr = (float*)(ws + L.o_klr);
   double* seg = (double*)(ws + L.o_seg);

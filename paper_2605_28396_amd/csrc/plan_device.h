@@ -33,6 +33,9 @@ DevicePlan device_plan_at(unsigned char* ws_plan, int32_t B, int32_t* row_idx, i
 // --- launchers (all asynchronous on `st`) ---------------------------------------------
 hipError_t launch_build_rows(const DevicePlan& pl, int32_t B, int64_t n_rows, int64_t n_pad,
                              hipStream_t st);
+// copies `bytes` (a multiple of 16) of host memory to `dst`; the host bytes are taken
+// before the call returns
+hipError_t launch_upload(void* dst, const void* src_host, size_t bytes, hipStream_t st);
 hipError_t launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st);
 

@@ -545,6 +545,33 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t st) {
   fill_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p, n, v);
   return hipGetLastError();
 }
+
+// Host -> device upload of a small blob through kernel arguments: the launch takes its copy
+// of the bytes before it returns, so the host buffer may be pageable and may be freed or
+// reused at once, whatever the stream still has to do, and the launch is an ordinary kernel
+// node for a caller who captures the stream.
+constexpr int kUploadChunk = 3072;   // bytes per launch (the argument block stays below 4 KiB)
+struct UploadArgs { uint4* dst; int n16; uint4 data[kUploadChunk / 16]; };
+__global__ __launch_bounds__(256) void upload_kernel(const UploadArgs a) {
+  const int q = threadIdx.x;
+  if (q < a.n16) a.dst[q] = a.data[q];
+}
+hipError_t launch_upload(void* dst, const void* src_host, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return hipSuccess;
+  if (!dst || !src_host || (bytes & 15) || ((uintptr_t)dst & 15)) return hipErrorInvalidValue;
+  static_assert(kUploadChunk / 16 <= 256, "one thread per 16 bytes");
+  UploadArgs a;
+  for (size_t at = 0; at < bytes; at += kUploadChunk) {
+    const size_t nb = bytes - at < (size_t)kUploadChunk ? bytes - at : (size_t)kUploadChunk;
+    a.dst = (uint4*)((unsigned char*)dst + at);
+    a.n16 = (int)(nb / 16);
+    memcpy(a.data, (const unsigned char*)src_host + at, nb);
+    upload_kernel<<<1, 256, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
 hipError_t launch_segment_sums(const DevicePlan& pl, int32_t B, int probe, const float* klr,
                                const float* rownorm, double* seg, float* loss_prefix,
                                float* loss_full, hipStream_t st) {
