@@ -1,0 +1,218 @@
+// Shared between the translation units of the fused path: tile geometry, the argument
+// blocks of its kernels and the host-side launchers.  The kernels live in
+// sweep_kernels.hip (LM-head projections, row statistics, gradient factors) and
+// grad_kernels.hip (combine pass, gradient contractions, scale + scatter); fused_host.hip
+// lays out the workspace and strings the launches together.
+#ifndef ADWIN_FUSED_SHARED_H
+#define ADWIN_FUSED_SHARED_H
+
+#include "device_utils.h"
+#include "plan_device.h"
+
+namespace adwin {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kRowBytes = kBK * 2;   // 128 B of k per staged row
+
+// Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
+// virtual ids so that the tiles sharing operands also share an L2.
+__device__ __forceinline__ int xcd_contiguous_id(int bid, int nb) {
+  const int xcd = bid & 7, loc = bid >> 3;
+  const int base = nb >> 3, rem = nb & 7;
+  return xcd * base + (xcd < rem ? xcd : rem) + loc;
+}
+
+// One wave instruction of a direct global->LDS load: lane l moves the 16 bytes at
+// sbase + voff(l) to LDS address lds_dst + 16 l (M0 = LDS destination of the wave, scalar
+// base + 32-bit lane offset).  Such loads return in order and are waited for with an
+// explicit s_waitcnt vmcnt(N).
+__device__ __forceinline__ void dma16(uint32_t lds_dst, uint32_t voff, const char* sbase) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_dst), "v"(voff), "s"(sbase) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
+// Slab layout (the A operand of the gradient GEMM, see "Tile images" below): block
+// (row tile, k-step) of 256 rows x 64 vocabulary entries, row r at r * 64 elements, its
+// 8-entry chunk c at chunk position c ^ ((r >> 1) & 7).  A 256 x 128 logit tile covers the
+// two consecutive blocks 2 vt and 2 vt + 1 of its row tile; `blk` points at the first.
+constexpr int kSlabBlock = kTileTokens * kBK;   // elements per block
+constexpr int kImgBytesSlab = kSlabBlock * 2;   // 32 KiB
+
+// Blocks of the gradient GEMM's operand images: 256 rows x 64 k-entries (see grad_kernels.hip).
+constexpr int kImgElems = kGradTile * kBK;            // bf16 elements per block
+constexpr int kImgBytes = kImgElems * 2;              // 32 KiB
+
+// ---------------------------------------------------------------------------------------
+// Argument blocks
+// ---------------------------------------------------------------------------------------
+struct LogitPassArgs {
+  const __bf16* h_s; const __bf16* h_t; const __bf16* W_s; const __bf16* W_t;
+  int H_s, H_t, V;
+  const int32_t* row_idx;      // [n_pad]
+  int64_t n_pad;
+  int tile0;                   // first token tile of this launch
+  int n_tiles;                 // token tiles in this launch
+  int strips;                  // vocabulary strips
+  int tg;                      // token tiles per workgroup group (share W tiles in one L2)
+  int vt_total;                // vocabulary tiles (of 128)
+  // pass 1 out: [5][strips][n_pad]
+  float* part;
+  // pass 2 in / out
+  const float* lse2; const float* mu;
+  __bf16* slab; int64_t Vp;    // slab blocks of the launch's token tiles, tile0 first
+  // single-sweep mode: fixed per-row references and the offset of the second slab half
+  const float* ref_s2; const float* ref_t2; const float* mu0;
+  int64_t e2_off;
+  // per-(vocabulary tile, slab row) reference mu0 of the D factor, written by the sweep
+  float* mu0t; int64_t mu0t_stride;
+  // diagnostics mode: teacher logit of the sampled token and the token id (-1: none) per row
+  const float* zy_t; const int32_t* yid;
+  // direct-to-LDS kernel: tile images of the four operands (see row_image_kernel)
+  const char* Wt_img; const char* Ws_img; const char* ht_img; const char* hs_img;
+};
+
+// Modes of the direct-to-LDS logit kernel.
+constexpr int kModeStats = 0;   // online (running-max) statistics only
+constexpr int kModeDz = 1;      // second sweep of the two-sweep scheme: dz tiles
+constexpr int kModeSingle = 2;  // single sweep: fixed-reference statistics + D/E2 tiles
+constexpr int kModeSingleDiag = 3;  // the same plus the teacher-side diagnostics of Sec. 3.1
+constexpr int kModeSingleE2 = 4;      // single sweep that emits only the E2 factor (sampled estimator)
+constexpr int kModeSingleE2Diag = 5;  // the same plus the diagnostics
+constexpr int kModeSingleFwd = 6;     // single sweep, statistics only: nothing is written to the slab
+constexpr int kModeSingleFwdDiag = 7; // the same plus the diagnostics
+
+// Tile images of a row-major [rows, H] operand (see row_image_kernel).
+struct RowImageArgs {
+  const uint4* src; uint4* img; const int32_t* row_idx;
+  int64_t n_rows; int H, nk, th;
+};
+
+// Merge of the strip partials into lse, mu, KL_t and c_t.
+struct MergeArgs {
+  const float* part; int strips; int64_t n_pad; int64_t n_rows;
+  const int32_t* row_idx;
+  const __bf16* h_s; const __bf16* h_t; const __bf16* W_s; const __bf16* W_t;
+  int H_s, H_t, V;
+  const int32_t* ids;
+  float* lse2; float* mu; float* klr;
+  float* kl; float* c;
+  uint32_t* status;
+  // teacher-side diagnostics (single-sweep merge only); part planes 3 and 4 hold
+  // sum e_t z_t and the rank count when `diag` is set
+  int diag;
+  float* t_logp; float* t_entropy; int32_t* t_rank;
+  float* cr;     // [n_pad] c_t per computed row, for the sampled estimator (else NULL)
+};
+
+struct MergeSingleArgs {
+  MergeArgs m;                 // part: [3][strips][n_pad] sums Z_s, A, Z_t
+  const float* ref_s2; const float* ref_t2;
+  float* mu_out; float* inv_z;
+  int64_t row0, rows;          // computed rows [row0, row0 + rows) of this launch (one slab)
+};
+
+// Logits of the sampled token under both models (see token_logit_kernel).
+struct TokenLogitArgs {
+  const int32_t* row_idx; const int32_t* ids;
+  const __bf16* h_s; const __bf16* W_s; const __bf16* h_t; const __bf16* W_t;
+  int H_s, H_t, V;
+  int64_t n_pad;
+  float* zy_s; float* zy_t; int32_t* yid;
+};
+
+// Combine pass over one slab (see combine_kernel).
+struct CombineArgs {
+  uint4* slab; int64_t e2_vec;          // E2 lies e2_vec 16-byte vectors after D
+  const float* mu; const float* inv_z;      // per computed row
+  const float* mu0t; int64_t mu0t_stride;   // reference of D per (vocabulary tile, slab row)
+  int64_t row0;                         // computed-row index of slab row 0
+  int nk;                               // k-steps (blocks) per row tile
+  // TR: also the transpose of w * dz as tile images for the head-weight GEMMs (rows =
+  // vocabulary entries in tiles of 256, k = slab rows): block (vt, kr) with kr = 4 rt + j,
+  // j = 0..3.  w = grad_scale * alpha of the row under the prefix objective (dzT_p; 0 outside
+  // the window) and under the full-rollout objective (dzT_f); the weight is applied in fp32
+  // before the one rounding to bf16.  Either image may be NULL.
+  uint4* dzT_p; uint4* dzT_f; int nkr;  // k-steps (of 64 slab rows) per vocabulary tile
+  DevicePlan pl; int64_t n_rows; float grad_scale;
+  // SAMPLED (with TR): the slab holds only E2 and is left as it is; the transposed images take
+  // Eq. 4's logit gradient c_t (e_{y_t} - p_s) = c_t (1[v = y_t] - E2 / Z_s), the one-hot term
+  // entering before the rounding.  c_t and y_t per computed row (y_t = -1: none).
+  const float* cr; const int32_t* yid;
+};
+
+// Transposed h_s images of one slab (see hst_image_kernel).
+struct HstImageArgs {
+  const uint16_t* h_s; const int32_t* row_idx;
+  int64_t row0;
+  int H, nkr;
+  uint16_t* img;
+};
+
+// Gradient GEMM over tile images (see grad_gemm_kernel).
+struct GradArgs {
+  const __bf16* slab; const __bf16* WsT;   // tile images
+  int nk_total;             // k-steps (blocks) per tile
+  float* g;                 // [ksplit][g_rows][H]
+  int64_t g_rows; int H;
+  int64_t slab_row0;        // computed-row index of slab row 0
+  int row_tiles, h_tiles, ksplit;
+  int half_tiles;           // slab row tiles >= half_tiles hold the E2 factor: output rows
+  int64_t half_off;         // half_off + slab_row0 + ... (single-sweep mode; else half_tiles = row_tiles)
+  int64_t out_rows;         // rows of g that exist (rows at or beyond are not stored)
+  int accumulate;           // add to g instead of overwriting it
+};
+
+// Scale + scatter of the row gradients (see finalize_kernel).
+struct FinalizeArgs {
+  DevicePlan pl; int B; int64_t T; int probe;
+  float* g; int ksplit; int64_t n_pad; int H;
+  int64_t g_rows;                          // rows per k-split plane of g
+  const float* inv_z;                      // 1 / Z_s per computed row (sampled estimator)
+  // sampled estimator (Eq. 4): g = c_t (W_s[y_t] - G2 inv_z), G2 = E2 W_s in the second half of
+  // g; cr NULL: g is the contraction of the logit gradient itself, in the first half
+  const float* cr; const int32_t* ids; const __bf16* W_s; int V;
+  float grad_scale; int dh_bf16;
+  void* dh_prefix; void* dh_full;
+  float* rownorm;
+};
+
+// Pooled gradients per rollout (see pool_partial_kernel, pool_final_kernel).
+struct PoolArgs {
+  DevicePlan pl; int B; int probe; int H;
+  const float* g; float* pp; float* pf;   // partials [n_chunks][H]
+  float* up; float* uf;                   // [B][H]
+};
+
+// ---------------------------------------------------------------------------------------
+// Launchers (asynchronous on `st`; the return value is that of the launch)
+// ---------------------------------------------------------------------------------------
+// sweep_kernels.hip
+hipError_t sweep_kernels_opt_in();       // large dynamic LDS of the logit kernels, once per device
+hipError_t launch_row_image(const RowImageArgs& a, unsigned tiles, hipStream_t st);
+// mode: one of kMode*; dma false selects the register-staged kernel (kModeStats, kModeDz only)
+hipError_t launch_logit_pass(int mode, bool dma, const LogitPassArgs& a, unsigned grid, hipStream_t st);
+hipError_t launch_token_logit(const TokenLogitArgs& a, hipStream_t st);
+hipError_t launch_make_refs(const float* part, int64_t n_pad, const float* zy_s, const float* zy_t,
+                            const int32_t* yid, float* ref_s2, float* ref_t2, float* mu0, hipStream_t st);
+hipError_t launch_merge_stats(const MergeArgs& a, hipStream_t st);
+hipError_t launch_merge_single(const MergeSingleArgs& a, hipStream_t st);
+// grad_kernels.hip
+hipError_t grad_kernels_opt_in();
+hipError_t launch_wst_image(const void* W_s, void* img, int V, int H, int nk, int h_tiles, hipStream_t st);
+hipError_t launch_hst_image(const HstImageArgs& a, int h_tiles, hipStream_t st);
+hipError_t launch_combine(bool transposed, bool sampled, const CombineArgs& a, int row_tiles, hipStream_t st);
+hipError_t launch_grad_gemm(const GradArgs& a, hipStream_t st);
+hipError_t launch_finalize(const FinalizeArgs& a, hipStream_t st);
+hipError_t launch_pool_partial(const PoolArgs& a, int n_chunks, hipStream_t st);
+hipError_t launch_pool_final(const PoolArgs& a, hipStream_t st);
+
+}  // namespace adwin
+
+#endif  // ADWIN_FUSED_SHARED_H

@@ -1,0 +1,887 @@
+// Fused path, first half: LM-head projections on bf16 MFMA and everything that is taken
+// from the logits while they sit in registers -- full-vocabulary log-sum-exp, per-token
+// reverse KL (Eq. 2 at token level) and the factors of the logit gradient (Eq. 4 in
+// expectation, App. A.1).  The logits themselves are never written anywhere.
+//
+// Single sweep (the default): per-row references are fixed in advance (online statistics
+// of vocabulary tile 0 and the sampled token's logits), so one pass over the vocabulary
+// yields the sums Z_s, A = sum e_s (z_s - z_t), Z_t and two bf16 gradient factors
+// D = (z_s - z_t) - mu0 and E2 = e_s per logit, written as tile images into a bounded row
+// slab; the merge gives lse, mu, KL_t, c_t per row, and the combine pass (grad_kernels.hip)
+// turns the factors into dz = p_s ((z_s - z_t) - mu).
+// Two sweeps (fallback): running-max statistics, merge, then the logits again for dz.
+//
+// For a 256-token tile a workgroup walks vocabulary tiles of 128; per tile two MFMA GEMMs
+// (teacher, then student) into fp32 accumulators, then the epilogue on the registers.
+// MFMA operand roles: v_mfma_f32_32x32x16_bf16 computes D[i][j] += sum_k A[i][k] B[k][j]
+// with i in registers and j = lane % 32.  A = W tile (i = vocabulary) and B = h tile
+// (j = token), so each lane owns one token column and the reduction over the vocabulary
+// runs down its own registers with no cross-lane traffic.
+#include "fused_shared.h"
+
+namespace adwin {
+
+// ---------------------------------------------------------------------------------------
+// Staging of [ROWS x 64] bf16 tiles: global -> registers -> LDS.  Thread t moves the
+// 16-byte chunk (t & 7) of rows (t >> 3) + 32 i.  Chunk c of row r is stored at chunk
+// position c ^ ((r >> 1) & 7): two 128-byte rows span all 64 LDS banks, so the 16 rows
+// that 16 consecutive lanes of an MFMA fragment read touch land on 16 distinct
+// (row parity, position) pairs, i.e. on distinct banks.
+// ---------------------------------------------------------------------------------------
+template <int ROWS>
+struct RowStager {
+  static constexpr int N = ROWS / 32;
+  const uint4* p[N];
+  uint4 v[N];
+  __device__ __forceinline__ void issue(int kt) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = p[i][kt * 8];
+  }
+  __device__ __forceinline__ void commit(char* tile, int thread_off) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) *(uint4*)(tile + thread_off + i * 32 * kRowBytes) = v[i];
+  }
+};
+
+__device__ __forceinline__ int stage_thread_off(int tid) {
+  const int r = tid >> 3, c = tid & 7;
+  return r * kRowBytes + ((c ^ ((r >> 1) & 7)) << 4);
+}
+
+// acc[FM][FN] += A_tile(wave rows) * B_tile(wave rows)^T for one staged k-step of 64.
+template <int FM, int FN>
+__device__ __forceinline__ void mma_stage(f32x16 (&acc)[FM][FN], const char* tA, const char* tB,
+                                          int lane) {
+  const int row_off = (lane & 31) * kRowBytes;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int sw = ((kk * 2 + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4;
+    bf16x8 a[FM], b[FN];
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm)
+      a[fm] = *(const bf16x8*)(tA + fm * 32 * kRowBytes + row_off + sw);
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+      b[fn] = *(const bf16x8*)(tB + fn * 32 * kRowBytes + row_off + sw);
+#pragma unroll
+    for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn)
+        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[fm], b[fn], acc[fm][fn], 0, 0, 0);
+  }
+}
+
+// Double-buffered k loop.  ldsA/ldsB: stage 0 tiles; stage 1 follows at `stage_bytes`.
+// waveA/waveB: byte offset of this wave's rows inside the A/B tile.
+template <int RA, int RB, int FM, int FN>
+__device__ __forceinline__ void gemm_kloop(f32x16 (&acc)[FM][FN], RowStager<RA>& sa,
+                                           RowStager<RB>& sb, int kt0, int nk, char* lds,
+                                           int stage_bytes, int waveA, int waveB, int tid) {
+  constexpr int kOffB = RA * kRowBytes;
+  const int toff = stage_thread_off(tid);
+  const int lane = tid & 63;
+  sa.issue(kt0);
+  sb.issue(kt0);
+  sa.commit(lds, toff);
+  sb.commit(lds + kOffB, toff);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    char* cur = lds + (kt & 1) * stage_bytes;
+    char* nxt = lds + ((kt + 1) & 1) * stage_bytes;
+    const bool more = kt + 1 < nk;
+    if (more) {
+      sa.issue(kt0 + kt + 1);
+      sb.issue(kt0 + kt + 1);
+    }
+    mma_stage<FM, FN>(acc, cur + waveA, cur + kOffB + waveB, lane);
+    if (more) {
+      sa.commit(nxt, toff);
+      sb.commit(nxt + kOffB, toff);
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Logit passes
+// ---------------------------------------------------------------------------------------
+
+// Running per-token statistics held by one lane for its two token columns.
+struct LaneStats { float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2]; };
+
+// Element e of block fm sits at vocabulary row v0 + fm*32 + 8*(e/4) + 4*(lane/32) + e%4.
+// Online update of (m_s, Z_s, A, m_t, Z_t) with one 128 x 64 logit tile per wave.
+__device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
+                                               LaneStats& st, int v0, int V, bool tail, int lane) {
+  const int vlane = v0 + 4 * (lane >> 5);
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    float mxs = st.m_s[fn], mxt = st.m_t[fn];
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < V;
+        if (ok) { mxs = fmaxf(mxs, zs[fm][fn][e]); mxt = fmaxf(mxt, zt[fm][fn][e]); }
+      }
+    const float scs = fast_exp2((st.m_s[fn] - mxs) * kLog2e);
+    const float sct = fast_exp2((st.m_t[fn] - mxt) * kLog2e);
+    float Zs = st.Z_s[fn] * scs, As = st.A_s[fn] * scs, Zt = st.Z_t[fn] * sct;
+    const float ms2 = mxs * kLog2e, mt2 = mxt * kLog2e;
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < V;
+        const float s = zs[fm][fn][e], t = zt[fm][fn][e];
+        float es = fast_exp2(fmaf(s, kLog2e, -ms2));
+        float et = fast_exp2(fmaf(t, kLog2e, -mt2));
+        float d = s - t;
+        if (!ok) { es = 0.f; et = 0.f; d = 0.f; }
+        Zs += es;
+        As = fmaf(es, d, As);
+        Zt += et;
+      }
+    st.m_s[fn] = mxs; st.m_t[fn] = mxt; st.Z_s[fn] = Zs; st.A_s[fn] = As; st.Z_t[fn] = Zt;
+  }
+}
+
+// dz = p_s ((z_s - z_t) - mu), rounded to bf16, into rows wrow + fn*32 + lane%32 of the tile.
+__device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
+                                            const float (&lse2)[2], const float (&mu)[2], __bf16* blk,
+                                            int wrow, int v0, int V, bool tail, int lane) {
+  const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK + 4 * half;
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float d[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
+          d[e] = fast_exp2(fmaf(s, kLog2e, -lse2[fn])) * ((s - t) - mu[fn]);
+        }
+        if (tail && vlane + fm * 32 + 8 * q >= V) { d[0] = d[1] = d[2] = d[3] = 0.f; }
+        uint2 o;
+        o.x = pack_bf16(d[0], d[1]);
+        o.y = pack_bf16(d[2], d[3]);
+        *(uint2*)(out + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3)) = o;
+      }
+  }
+}
+
+// Single-sweep epilogue.  With per-row references fixed in advance (rs2 = m_ref_s*log2e,
+// rt2 = m_ref_t*log2e, mu0 ~ E_{p_s}[z_s - z_t]) every exponential is taken relative to the
+// same reference in every tile, so the statistics are plain sums,
+//   Z_s = sum e_s,  A = sum e_s d,  Z_t = sum e_t,   e_s = exp(z_s - m_ref_s), d = z_s - z_t,
+// and two bf16 factors of the unnormalised gradient can be emitted at once, D = d - mu0 and
+// E2 = e_s: dz = E2 (D - (mu - mu0)) / Z_s.  mu0 is a per-(row, vocabulary tile) reference
+// kept for the combine pass.  D goes to slab rows row0.., E2 to the same rows e2_off elements
+// further on.
+// B_t = sum e_t z_t (teacher entropy) and cnt = entries ranked above the sampled token are
+// only maintained in diagnostics mode.
+struct LaneSums { float Z_s[2], A_s[2], Z_t[2], B_t[2]; int cnt[2]; };
+
+template <bool TAIL, bool DIAG, bool WRITE_D, bool WRITE_E2>
+__device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
+                                                LaneSums& sm, const float (&rs2)[2],
+                                                const float (&rt2)[2], float (&mu0)[2],
+                                                const float (&zyt)[2], const int (&yid)[2],
+                                                __bf16* blk, int64_t e2_off, int wrow,
+                                                int v0, int V, int lane, float* mu0_out) {
+  const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK + 4 * half;
+    float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn], Bt = sm.B_t[fn];
+    int cnt = sm.cnt[fn];
+    const int vy = yid[fn] - vlane;        // position of the sampled token among this lane's entries
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float e2[4];
+        const bool ok = !TAIL || (vlane + fm * 32 + 8 * q) < V;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
+          float es = fast_exp2(fmaf(s, kLog2e, -rs2[fn]));
+          float et = fast_exp2(fmaf(t, kLog2e, -rt2[fn]));
+          float d = s - t;
+          if (TAIL && !ok) { es = 0.f; et = 0.f; d = 0.f; }
+          Zs += es;
+          As = fmaf(es, d, As);
+          Zt += et;
+          if (DIAG) {
+            Bt = fmaf(et, t, Bt);
+            cnt += (t > zyt[fn] && (fm * 32 + 8 * q + e) != vy && ok) ? 1 : 0;
+          }
+          e2[e] = es;
+        }
+        uint2 o2;
+        o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
+        const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
+        if (WRITE_E2) *(uint2*)(out + e2_off + at) = o2;
+      }
+    sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
+    if (DIAG) { sm.B_t[fn] = Bt; sm.cnt[fn] = cnt; }
+    if (WRITE_D) {
+      // Second factor: D = d - mu0 with mu0 the strip's running mean of d = z_s - z_t under the
+      // student weights, this tile included (both half-columns of the row).  A heavy entry
+      // dominates the mean of its own tile, so its D is stored small and the correction
+      // (mu - mu0) carries its gradient: the rounding of both factors stays proportional to
+      // p_s |d - mu| even when the row is peaked and the first vocabulary entries say nothing
+      // about mu.  The masked entries of a tail tile have E2 = 0; their D is immaterial.
+      const float Zr = Zs + __shfl_xor(Zs, 32, 64), Ar = As + __shfl_xor(As, 32, 64);
+      if (Zr > 0.f) mu0[fn] = Ar / Zr;
+      const float m0 = mu0[fn];
+      if (mu0_out && lane < 32) mu0_out[fn * 32 + lane] = m0;
+#pragma unroll
+      for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float dd[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dd[e] = (zs[fm][fn][q * 4 + e] - m0) - zt[fm][fn][q * 4 + e];
+          uint2 o1;
+          o1.x = pack_bf16(dd[0], dd[1]); o1.y = pack_bf16(dd[2], dd[3]);
+          const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
+          *(uint2*)(out + at) = o1;
+        }
+    }
+  }
+}
+
+template <bool DIAG>
+__device__ __forceinline__ void write_sums(LaneSums& sm, float* part, int strips, int strip,
+                                           int64_t n_pad, int64_t row0, int lane) {
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    const float Zs = sm.Z_s[fn] + __shfl_xor(sm.Z_s[fn], 32, 64);
+    const float As = sm.A_s[fn] + __shfl_xor(sm.A_s[fn], 32, 64);
+    const float Zt = sm.Z_t[fn] + __shfl_xor(sm.Z_t[fn], 32, 64);
+    const float Bt = DIAG ? sm.B_t[fn] + __shfl_xor(sm.B_t[fn], 32, 64) : 0.f;
+    const int cnt = DIAG ? sm.cnt[fn] + __shfl_xor(sm.cnt[fn], 32, 64) : 0;
+    if (lane < 32) {
+      const int64_t plane = (int64_t)strips * n_pad;
+      float* o = part + (int64_t)strip * n_pad + row0 + fn * 32 + lane;
+      o[0 * plane] = Zs;
+      o[1 * plane] = As;
+      o[2 * plane] = Zt;
+      if (DIAG) {
+        o[3 * plane] = Bt;
+        o[4 * plane] = (float)cnt;     // at most V < 2^24: exact
+      }
+    }
+  }
+}
+
+// Merge the two half-columns held by lanes l and l^32 and write one strip's partials.
+__device__ __forceinline__ void write_partials(LaneStats& st, float* part, int strips, int strip,
+                                               int64_t n_pad, int64_t row0, int lane) {
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    merge_mza(st.m_s[fn], st.Z_s[fn], st.A_s[fn], __shfl_xor(st.m_s[fn], 32, 64),
+              __shfl_xor(st.Z_s[fn], 32, 64), __shfl_xor(st.A_s[fn], 32, 64));
+    merge_mz(st.m_t[fn], st.Z_t[fn], __shfl_xor(st.m_t[fn], 32, 64), __shfl_xor(st.Z_t[fn], 32, 64));
+    if (lane < 32) {
+      const int64_t plane = (int64_t)strips * n_pad;
+      float* o = part + (int64_t)strip * n_pad + row0 + fn * 32 + lane;
+      o[0 * plane] = st.m_s[fn];
+      o[1 * plane] = st.Z_s[fn];
+      o[2 * plane] = st.A_s[fn];
+      o[3 * plane] = st.m_t[fn];
+      o[4 * plane] = st.Z_t[fn];
+    }
+  }
+}
+
+constexpr int kLogitStage = (kTileVocab + kTileTokens) * kRowBytes;   // 48 KiB
+constexpr int kLogitLds = 2 * kLogitStage;
+
+template <bool PASS2>
+__global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // virtual id -> (group of 4 token tiles, strip, tile in group)
+  const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int per_group = a.tg * a.strips;
+  const int tg = vid / per_group, within = vid % per_group;
+  const int strip = within / a.tg, tt_local = tg * a.tg + (within % a.tg);
+  if (tt_local >= a.n_tiles) return;
+  const int tt = a.tile0 + tt_local;
+  const int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
+  const int vt_end = (int)((int64_t)a.vt_total * (strip + 1) / a.strips);
+
+  // token-row stagers (rows fixed for the whole vocabulary walk)
+  RowStager<kTileTokens> hs, ht;
+  RowStager<kTileVocab> ws, wt;
+  {
+    const int r = tid >> 3, c = tid & 7;
+#pragma unroll
+    for (int i = 0; i < kTileTokens / 32; ++i) {
+      const int64_t row = a.row_idx[(int64_t)tt * kTileTokens + r + 32 * i];
+      hs.p[i] = (const uint4*)(a.h_s + row * a.H_s) + c;
+      ht.p[i] = (const uint4*)(a.h_t + row * a.H_t) + c;
+    }
+  }
+  const int waveB = wave * 64 * kRowBytes;   // this wave's 64 token rows in the B tile
+
+  LaneStats st;
+  float lse2[2], mu[2];
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    st.m_s[fn] = kNegBig; st.Z_s[fn] = 0.f; st.A_s[fn] = 0.f; st.m_t[fn] = kNegBig; st.Z_t[fn] = 0.f;
+    lse2[fn] = 0.f; mu[fn] = 0.f;
+    if (PASS2) {
+      const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
+      lse2[fn] = a.lse2[r];
+      mu[fn] = a.mu[r];
+    }
+  }
+
+  for (int vt = vt_begin; vt < vt_end; ++vt) {
+    const int v0 = vt * kTileVocab;
+    {
+      const int r = tid >> 3, c = tid & 7;
+#pragma unroll
+      for (int i = 0; i < kTileVocab / 32; ++i) {
+        int v = v0 + r + 32 * i;
+        v = v < a.V ? v : a.V - 1;               // tail rows: load a valid row, masked below
+        ws.p[i] = (const uint4*)(a.W_s + (int64_t)v * a.H_s) + c;
+        wt.p[i] = (const uint4*)(a.W_t + (int64_t)v * a.H_t) + c;
+      }
+    }
+    f32x16 zt[4][2], zs[4][2];
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { zt[fm][fn][e] = 0.f; zs[fm][fn][e] = 0.f; }
+    gemm_kloop<kTileVocab, kTileTokens, 4, 2>(zt, wt, ht, 0, a.H_t / kBK, lds, kLogitStage, 0, waveB, tid);
+    gemm_kloop<kTileVocab, kTileTokens, 4, 2>(zs, ws, hs, 0, a.H_s / kBK, lds, kLogitStage, 0, waveB, tid);
+
+    const bool tail = v0 + kTileVocab > a.V;
+    if (!PASS2) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
+    else dz_epilogue(zs, zt, lse2, mu, a.slab + ((int64_t)tt_local * (a.Vp / kBK) + 2 * vt) * kSlabBlock,
+                     wave * 64, v0, a.V, tail, lane);
+  }
+  if (!PASS2)
+    write_partials(st, a.part, a.strips, strip, a.n_pad, (int64_t)tt * kTileTokens + wave * 64, lane);
+}
+
+// ---------------------------------------------------------------------------------------
+// Logit passes, direct global->LDS staging.
+//
+// Same tile, MFMA roles and epilogues as logit_pass_kernel, but the k-tiles are moved by
+// global_load_lds_dwordx4 (no register staging) into a three-stage LDS ring, two k-steps
+// ahead of the MFMAs.  One wave instruction moves 8 rows x 128 B: lane l lands at
+// base + 16 l, i.e. row l/8, chunk position l%8, and therefore fetches global chunk
+// (l%8) ^ swizzle(row).  The teacher and student k-loops form one pipeline of
+// H_t/64 + H_s/64 steps per vocabulary tile.
+//
+// The loads are written as inline assembly (M0 = LDS destination of the wave, scalar base
+// + 32-bit lane offset) and waited for with explicit s_waitcnt vmcnt(N): the loads return
+// in order, so "at most the 12 loads of the next stage outstanding" means this stage has
+// landed.  Compiler-issued loads in between only make the count larger, i.e. the wait
+// longer.  Requires rows * H * 2 bytes < 4 GiB per operand (32-bit lane offsets).
+// ---------------------------------------------------------------------------------------
+constexpr int kDmaStages = 3;
+constexpr int kDmaLds = kDmaStages * kLogitStage;           // 144 KiB
+constexpr int kDmaPerWave = (kTileVocab + kTileTokens) / 8 / 4;   // 12 wave-loads per stage
+
+// Row images.  The direct-to-LDS logit kernel reads all four operands as LDS images of its
+// k-steps: [rows, H] row-major (optionally gathered through row_idx) is re-laid as tiles of
+// `th` consecutive rows; block (tile, kt) holds their k-entries 64 kt .. 64 kt + 63, row r at
+// r * 128 B, its 16-byte chunk c at chunk position c ^ ((r >> 1) & 7); rows >= n_rows are
+// zero.  Blocks of one tile are consecutive in kt.  Every wave-load then moves 1 KiB of
+// consecutive bytes and no operand needs 32-bit lane offsets from its base.
+
+__global__ __launch_bounds__(256) void row_image_kernel(RowImageArgs a) {
+  const int kt = blockIdx.x;
+  const int64_t tile = blockIdx.y;
+  uint4* blk = a.img + ((tile * a.nk + kt) * a.th) * 8;
+  for (int q = threadIdx.x; q < a.th * 8; q += 256) {
+    const int r = q >> 3, pos = q & 7, c = pos ^ ((r >> 1) & 7);
+    const int64_t row = tile * a.th + r;
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (row < a.n_rows) {
+      const int64_t src_row = a.row_idx ? (int64_t)a.row_idx[row] : row;
+      v = a.src[src_row * (a.H >> 3) + kt * 8 + c];
+    }
+    blk[q] = v;
+  }
+}
+
+constexpr int kImgABytes = kTileVocab * kRowBytes;    // 16 KiB: one W block
+constexpr int kImgBBytes = kTileTokens * kRowBytes;   // 32 KiB: one h block
+
+// Wave-load I (0..11) of this wave for one stage: KiB (wave + 4 I) of the A block, then of
+// the B block; lane l moves bytes 16 l .. 16 l + 15 of that KiB.
+template <int I>
+__device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, uint32_t voff, const char* sA,
+                                        const char* sB) {
+  if constexpr (I < kTileVocab / 32)
+    dma16(lds_stage + (uint32_t)(wave + 4 * I) * 1024u, voff, sA + (wave + 4 * I) * 1024);
+  else
+    dma16(lds_stage + (uint32_t)(kTileVocab / 8 + wave + 4 * (I - kTileVocab / 32)) * 1024u, voff,
+          sB + (wave + 4 * (I - kTileVocab / 32)) * 1024);
+}
+
+// One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  On entry fa[0],
+// fb[0] hold the fragments of sub-step 0.  The instruction order is pinned: after each MFMA
+// one or two side operations are issued in its shadow -- an LDS read of a fragment of the
+// next sub-step (fragments are double-buffered) and, when ISSUE, one of the 12 global->LDS
+// loads of the stage two k-steps ahead -- so that neither the LDS latency nor the
+// vector-memory issue holds up the matrix pipe.  The one barrier of the k-step sits before
+// the last sub-step: by then every fragment of this stage is in registers, and the last
+// sub-step's MFMAs cover the reads of the next stage's first fragments (stage `nxt`, whose
+// loads were issued one k-step earlier and are waited for here).  LAST: no next stage in
+// this vocabulary tile; no barrier and no fragment reads.
+template <bool ISSUE, bool LAST>
+__device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
+                                            const char* curA, const char* curB, const char* nxtA,
+                                            const char* nxtB, int lane, uint32_t lds_stage, int wave,
+                                            uint32_t voff, const char* sA, const char* sB) {
+  const int key = (lane >> 1) & 7, half = lane >> 5;
+  const int rowoff = (lane & 31) * kRowBytes;
+  int sw[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) sw[kk] = rowoff + (((kk * 2 + half) ^ key) << 4);
+#define ADWIN_FENCE __builtin_amdgcn_sched_barrier(0);
+#define ADWIN_RA(TA, KK, I) fa[((KK) + 1) & 1][I] = *(const bf16x8*)((TA) + (I) * 32 * kRowBytes + sw[((KK) + 1) & 3]); ADWIN_FENCE
+#define ADWIN_RB(TB, KK, I) fb[((KK) + 1) & 1][I] = *(const bf16x8*)((TB) + (I) * 32 * kRowBytes + sw[((KK) + 1) & 3]); ADWIN_FENCE
+#define ADWIN_MM(KK, FMI, FNI)                                                                  \
+  acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
+                                                          acc[FMI][FNI], 0, 0, 0);              \
+  ADWIN_FENCE
+#define ADWIN_DMA(I) if constexpr (ISSUE) { dma_one<I>(lds_stage, wave, voff, sA, sB); ADWIN_FENCE }
+  // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from (TA, TB) when READ
+#define ADWIN_SUB(KK, READ, TA, TB, D0, D1, D2)                         \
+  ADWIN_MM(KK, 0, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 0) }        \
+  ADWIN_MM(KK, 0, 1) if constexpr (READ) { ADWIN_RB(TB, KK, 0) }        \
+  ADWIN_MM(KK, 1, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 1) }        \
+  ADWIN_MM(KK, 1, 1) if constexpr (READ) { ADWIN_RB(TB, KK, 1) }        \
+  ADWIN_MM(KK, 2, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 2) }        \
+  ADWIN_MM(KK, 2, 1) if constexpr (READ) { ADWIN_RA(TA, KK, 3) } ADWIN_DMA(D0) \
+  ADWIN_MM(KK, 3, 0) ADWIN_DMA(D1)                                      \
+  ADWIN_MM(KK, 3, 1) ADWIN_DMA(D2)
+  ADWIN_FENCE
+  ADWIN_SUB(0, true, curA, curB, 0, 1, 2)
+  ADWIN_SUB(1, true, curA, curB, 3, 4, 5)
+  ADWIN_SUB(2, true, curA, curB, 6, 7, 8)
+  if constexpr (!LAST) {
+    // loads issued after those of the next stage: the 9 above (none when !ISSUE)
+    if constexpr (ISSUE) asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+  ADWIN_FENCE
+  ADWIN_SUB(3, !LAST, nxtA, nxtB, 9, 10, 11)
+#undef ADWIN_SUB
+#undef ADWIN_DMA
+#undef ADWIN_MM
+#undef ADWIN_RB
+#undef ADWIN_RA
+#undef ADWIN_FENCE
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int per_group = a.tg * a.strips;
+  const int tg = vid / per_group, within = vid % per_group;
+  const int strip = within / a.tg, tt_local = tg * a.tg + (within % a.tg);
+  if (tt_local >= a.n_tiles) return;
+  const int tt = a.tile0 + tt_local;
+  const int vt_begin = (int)((int64_t)a.vt_total * strip / a.strips);
+  const int vt_end = (int)((int64_t)a.vt_total * (strip + 1) / a.strips);
+  if (vt_begin >= vt_end) return;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+
+  const uint32_t voff = (uint32_t)lane * 16u;
+  const int waveA = 0, waveB = kTileVocab * kRowBytes + wave * 64 * kRowBytes;
+  const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;   // each >= 2 on this path
+  // blocks of this token tile (fixed) and of vocabulary tile vt, teacher and student
+  const char* sHt = a.ht_img + (int64_t)tt * nk_t * kImgBBytes;
+  const char* sHs = a.hs_img + (int64_t)tt * nk_s * kImgBBytes;
+  auto blocks_wt = [&](int vt) { return a.Wt_img + (int64_t)vt * nk_t * kImgABytes; };
+  auto blocks_ws = [&](int vt) { return a.Ws_img + (int64_t)vt * nk_s * kImgABytes; };
+
+  LaneStats st;
+  LaneSums sm;
+  constexpr bool kDiag = MODE == kModeSingleDiag || MODE == kModeSingleE2Diag || MODE == kModeSingleFwdDiag;
+  constexpr bool kWriteE2 = MODE < kModeSingleFwd;
+  constexpr bool kWriteD = MODE == kModeSingle || MODE == kModeSingleDiag;
+  constexpr bool kSingle = MODE >= kModeSingle;
+  float lse2[2], mu[2], rs2[2], rt2[2];   // per-row inputs of the dz / single-sweep epilogues
+  float zyt[2];
+  int yid[2];
+#pragma unroll
+  for (int fn = 0; fn < 2; ++fn) {
+    st.m_s[fn] = kNegBig; st.Z_s[fn] = 0.f; st.A_s[fn] = 0.f; st.m_t[fn] = kNegBig; st.Z_t[fn] = 0.f;
+    sm.Z_s[fn] = 0.f; sm.A_s[fn] = 0.f; sm.Z_t[fn] = 0.f; sm.B_t[fn] = 0.f; sm.cnt[fn] = 0;
+    lse2[fn] = 0.f; mu[fn] = 0.f; rs2[fn] = 0.f; rt2[fn] = 0.f; zyt[fn] = 0.f; yid[fn] = -1;
+    const int64_t r = (int64_t)tt * kTileTokens + wave * 64 + fn * 32 + (lane & 31);
+    if (MODE == kModeDz) {
+      lse2[fn] = a.lse2[r];
+      mu[fn] = a.mu[r];
+    } else if (kSingle) {
+      rs2[fn] = a.ref_s2[r];
+      rt2[fn] = a.ref_t2[r];
+      mu[fn] = a.mu0[r];
+      if (kDiag) { zyt[fn] = a.zy_t[r]; yid[fn] = a.yid[r]; }
+    }
+  }
+
+  // The k-steps of all vocabulary tiles of the strip form one pipeline: per tile nk_t
+  // teacher steps, then nk_s student steps; step g is staged into ring slot g % 3 two steps
+  // before it is consumed, also across the tile boundary (the next tile's first two steps
+  // are loaded during this tile's last two, i.e. before and under the epilogue).
+  uint32_t wr = 0, rd = 0;     // ring slots of the next step to load / to consume
+  auto slot_inc = [](uint32_t x) { return x + 1 == kDmaStages ? 0u : x + 1; };
+  {
+    const char* sWt = blocks_wt(vt_begin);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t dst = lds0 + wr * kLogitStage;
+      const char* sA = sWt + i * kImgABytes;
+      const char* sB = sHt + i * kImgBBytes;
+      dma_one<0>(dst, wave, voff, sA, sB); dma_one<1>(dst, wave, voff, sA, sB);
+      dma_one<2>(dst, wave, voff, sA, sB); dma_one<3>(dst, wave, voff, sA, sB);
+      dma_one<4>(dst, wave, voff, sA, sB); dma_one<5>(dst, wave, voff, sA, sB);
+      dma_one<6>(dst, wave, voff, sA, sB); dma_one<7>(dst, wave, voff, sA, sB);
+      dma_one<8>(dst, wave, voff, sA, sB); dma_one<9>(dst, wave, voff, sA, sB);
+      dma_one<10>(dst, wave, voff, sA, sB); dma_one<11>(dst, wave, voff, sA, sB);
+      wr = slot_inc(wr);
+    }
+  }
+  for (int vt = vt_begin; vt < vt_end; ++vt) {
+    const int v0 = vt * kTileVocab;
+    const char* sWt = blocks_wt(vt);
+    const char* sWs = blocks_ws(vt);
+    f32x16 zt[4][2], zs[4][2];
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { zt[fm][fn][e] = 0.f; zs[fm][fn][e] = 0.f; }
+
+    // step 0 of this tile has landed once at most the 12 loads of step 1 are outstanding
+    wait_vm<kDmaPerWave>();
+    __syncthreads();
+    bf16x8 fa[2][4], fb[2][2];
+    {
+      const char* cur = lds + rd * kLogitStage;
+      const int key = (lane >> 1) & 7, half = lane >> 5;
+      const int sw0 = (lane & 31) * kRowBytes + ((half ^ key) << 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[0][i] = *(const bf16x8*)(cur + waveA + i * 32 * kRowBytes + sw0);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fb[0][i] = *(const bf16x8*)(cur + waveB + i * 32 * kRowBytes + sw0);
+    }
+    // one k-step: consume slot rd, prefetch fragments from the following slot, load into wr
+    auto step = [&](auto issue_c, auto last_c, f32x16 (&acc)[4][2], const char* sA, const char* sB) {
+      constexpr bool kIssue = decltype(issue_c)::value, kLast = decltype(last_c)::value;
+      const char* cur = lds + rd * kLogitStage;
+      const uint32_t rn = slot_inc(rd);
+      const char* nxt = lds + rn * kLogitStage;
+      sweep_kstep<kIssue, kLast>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
+                                 lds0 + wr * kLogitStage, wave, voff, sA, sB);
+      if (kIssue) wr = slot_inc(wr);
+      rd = rn;
+    };
+    const std::true_type yes{};
+    const std::false_type no{};
+    int s = 0;
+    for (; s + 2 < nk_t; ++s)                  // teacher k-steps loading teacher k-steps
+      step(yes, no, zt, sWt + (s + 2) * kImgABytes, sHt + (s + 2) * kImgBBytes);
+    for (; s < nk_t; ++s) {                    // last two teacher k-steps load student k-steps 0, 1
+      const int n = s + 2 - nk_t;
+      step(yes, no, zt, sWs + n * kImgABytes, sHs + n * kImgBBytes);
+    }
+    for (; s + 2 < nk; ++s) {                  // student k-steps loading student k-steps
+      const int n = s + 2 - nk_t;
+      step(yes, no, zs, sWs + n * kImgABytes, sHs + n * kImgBBytes);
+    }
+    if (vt + 1 < vt_end) {                     // last two: load the next tile's teacher k-steps 0, 1
+      const char* sWn = blocks_wt(vt + 1);
+      step(yes, no, zs, sWn, sHt);
+      step(yes, yes, zs, sWn + kImgABytes, sHt + kImgBBytes);
+    } else {
+      step(no, no, zs, sWs, sHs);
+      step(no, yes, zs, sWs, sHs);
+    }
+    const bool tail = v0 + kTileVocab > a.V;
+    if (MODE == kModeStats) {
+      stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
+    } else {
+      __bf16* blk = a.slab + ((int64_t)tt_local * (a.Vp / kBK) + 2 * vt) * kSlabBlock;
+      float* m0t = a.mu0t ? a.mu0t + (int64_t)vt * a.mu0t_stride + (int64_t)tt_local * kTileTokens + wave * 64
+                          : nullptr;
+      if (MODE == kModeDz) {
+        dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
+      } else if (tail) {
+        single_epilogue<true, kDiag, kWriteD, kWriteE2>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
+      } else {
+        single_epilogue<false, kDiag, kWriteD, kWriteE2>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
+      }
+    }
+  }
+  const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
+  if (MODE == kModeStats) write_partials(st, a.part, a.strips, strip, a.n_pad, row0, lane);
+  else if (kSingle) write_sums<kDiag>(sm, a.part, a.strips, strip, a.n_pad, row0, lane);
+}
+
+// ---------------------------------------------------------------------------------------
+// Merge of the strip partials, KL_t and c_t.  One wave per computed row.
+// ---------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float dot_bf16_row(const __bf16* x, const __bf16* y, int H, int lane) {
+  float acc = 0.f;
+  const uint4* px = (const uint4*)x;
+  const uint4* py = (const uint4*)y;
+  for (int q = lane; q < (H >> 3); q += 64) {
+    const uint4 a = px[q], b = py[q];
+    acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+    acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+    acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+    acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+  }
+  return wave_sum(acc);
+}
+
+__global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.n_pad) return;
+  const int64_t plane = (int64_t)a.strips * a.n_pad;
+  float ms = kNegBig, Zs = 0.f, A = 0.f, mt = kNegBig, Zt = 0.f;
+  if (lane < a.strips) {
+    const float* p = a.part + (int64_t)lane * a.n_pad + r;
+    ms = p[0]; Zs = p[plane]; A = p[2 * plane]; mt = p[3 * plane]; Zt = p[4 * plane];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    merge_mza(ms, Zs, A, __shfl_xor(ms, o, 64), __shfl_xor(Zs, o, 64), __shfl_xor(A, o, 64));
+    merge_mz(mt, Zt, __shfl_xor(mt, o, 64), __shfl_xor(Zt, o, 64));
+  }
+  const float lse_s = ms + logf(Zs), lse_t = mt + logf(Zt);
+  const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
+  const float kl = kl_from_sums(mu, ms - mt, Zs, Zt);
+  if (lane == 0) {
+    a.lse2[r] = lse_s * kLog2e;
+    a.mu[r] = mu;
+    a.klr[r] = kl;
+  }
+  if (r >= a.n_rows) return;                // padding rows feed pass 2 only
+  const int64_t t = a.row_idx[r];
+  float c = 0.f;
+  uint32_t flag = 0;
+  if (a.ids && a.c) {
+    const int y = a.ids[t];
+    if (y >= 0 && y < a.V) {
+      const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
+      const float zy_t = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)y * a.H_t, a.H_t, lane);
+      c = (zy_s - lse_s) - (zy_t - lse_t);
+    } else {
+      flag |= ADWIN_DEV_BAD_ID;
+    }
+  }
+  if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f))
+    flag |= ADWIN_DEV_NONFINITE;
+  if (lane == 0) {
+    if (flag && a.status) atomicOr(a.status, flag);
+    if (a.kl) a.kl[t] = kl;
+    if (a.c) a.c[t] = c;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Single-sweep mode: per-row references from the online statistics of vocabulary tile 0,
+// and the merge of the fixed-reference strip sums.
+// ---------------------------------------------------------------------------------------
+__global__ void make_refs_kernel(const float* __restrict__ part /* [5][1][n_pad] */, int64_t n_pad,
+                                 const float* __restrict__ zy_s, const float* __restrict__ zy_t,
+                                 const int32_t* __restrict__ yid, float* ref_s2, float* ref_t2,
+                                 float* mu0) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_pad) return;
+  float ms = part[r], Zs = part[n_pad + r], A = part[2 * n_pad + r], mt = part[3 * n_pad + r];
+  if (yid && yid[r] >= 0) {
+    // The sampled token joins the first vocabulary tile as a sample of the row: drawn from the
+    // student, it sits where the mass is, which the first 128 entries of a peaked row do not.
+    // The references rise to its logits (the exponentials of the sweep stay near 1 at the
+    // row maximum instead of growing with the gap to the first tile), and mu0 becomes the
+    // self-normalised estimate of E_p[z_s - z_t] over the tile's entries and the token.
+    const float zs = zy_s[r], zt = zy_t[r];
+    const float rs = fmaxf(ms, zs);
+    const float sc = fast_exp2((ms - rs) * kLog2e);
+    Zs *= sc; A *= sc;
+    if (yid[r] >= kTileVocab) {           // not already one of the tile's entries
+      const float ey = fast_exp2((zs - rs) * kLog2e);
+      Zs += ey;
+      A = fmaf(ey, zs - zt, A);
+    }
+    ms = rs;
+    mt = fmaxf(mt, zt);
+  }
+  ref_s2[r] = ms * kLog2e;
+  ref_t2[r] = mt * kLog2e;
+  mu0[r] = A / Zs;
+}
+
+__global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
+  const MergeArgs& a = b.m;
+  const int lane = threadIdx.x & 63;
+  const int64_t r = b.row0 + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= b.row0 + b.rows) return;
+  const int64_t plane = (int64_t)a.strips * a.n_pad;
+  float Zs = 0.f, A = 0.f, Zt = 0.f, Bt = 0.f, cnt = 0.f;
+  if (lane < a.strips) {
+    const float* p = a.part + (int64_t)lane * a.n_pad + r;
+    Zs = p[0]; A = p[plane]; Zt = p[2 * plane];
+    if (a.diag) { Bt = p[3 * plane]; cnt = p[4 * plane]; }
+  }
+  Zs = wave_sum(Zs); A = wave_sum(A); Zt = wave_sum(Zt);
+  if (a.diag) { Bt = wave_sum(Bt); cnt = wave_sum(cnt); }
+  const float lse_s = b.ref_s2[r] * kLn2 + logf(Zs), lse_t = b.ref_t2[r] * kLn2 + logf(Zt);
+  const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
+  const float kl = kl_from_sums(mu, (b.ref_s2[r] - b.ref_t2[r]) * kLn2, Zs, Zt);
+  if (lane == 0) {
+    b.mu_out[r] = mu;
+    b.inv_z[r] = 1.f / Zs;
+    a.klr[r] = kl;
+  }
+  if (r >= a.n_rows) return;
+  const int64_t t = a.row_idx[r];
+  float c = 0.f, logp_t = 0.f;
+  bool have_y = false;
+  uint32_t flag = 0;
+  if (a.ids && (a.c || a.t_logp || a.t_rank || a.cr)) {
+    const int y = a.ids[t];
+    if (y >= 0 && y < a.V) {
+      const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
+      const float zy_t = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)y * a.H_t, a.H_t, lane);
+      c = (zy_s - lse_s) - (zy_t - lse_t);
+      logp_t = zy_t - lse_t;
+      have_y = true;
+    } else {
+      flag |= ADWIN_DEV_BAD_ID;
+    }
+  }
+  if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f) ||
+      !(fabsf(A) < 3.0e38f))
+    flag |= ADWIN_DEV_NONFINITE;
+  if (lane == 0) {
+    if (flag && a.status) atomicOr(a.status, flag);
+    if (a.kl) a.kl[t] = kl;
+    if (a.c) a.c[t] = c;
+    if (a.t_logp) a.t_logp[t] = logp_t;
+    // H[p_t] = lse_t - E_{p_t}[z_t]; both sums are relative to the same reference
+    if (a.t_entropy) a.t_entropy[t] = lse_t - Bt / Zt;
+    if (a.t_rank) a.t_rank[t] = have_y ? (int32_t)cnt + 1 : 0;
+    if (a.cr) a.cr[r] = c;
+  }
+}
+
+// Logits of the sampled token under both models, z_s[y_t] = h_s . W_s[y_t] and
+// z_t[y_t] = h_t . W_t[y_t], and the token id (-1 when there is none or it is out of range),
+// per computed row.  The references of the single sweep are built from them (make_refs_kernel)
+// and the diagnostics sweep compares against z_t[y_t] to count the entries the teacher ranks
+// above y_t (Sec. 3.1).  One wave per row.
+
+__global__ __launch_bounds__(256) void token_logit_kernel(TokenLogitArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= a.n_pad) return;
+  const int64_t t = a.row_idx[r];
+  const int y = a.ids ? a.ids[t] : -1;
+  float zs = 0.f, zt = 0.f;
+  const bool ok = y >= 0 && y < a.V;
+  if (ok) {
+    zs = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
+    zt = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)y * a.H_t, a.H_t, lane);
+  }
+  if (lane == 0) { a.zy_s[r] = zs; a.zy_t[r] = zt; a.yid[r] = ok ? y : -1; }
+}
+
+// ---------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------
+hipError_t sweep_kernels_opt_in() {
+  hipError_t e;
+#define ADWIN_OPT_IN(KERNEL, BYTES)                                                              \
+  e = hipFuncSetAttribute((const void*)KERNEL, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES); \
+  if (e != hipSuccess) return e;
+  ADWIN_OPT_IN(logit_pass_kernel<false>, kLogitLds)
+  ADWIN_OPT_IN(logit_pass_kernel<true>, kLogitLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeStats>, kDmaLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeDz>, kDmaLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeSingle>, kDmaLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeSingleDiag>, kDmaLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeSingleE2>, kDmaLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeSingleE2Diag>, kDmaLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeSingleFwd>, kDmaLds)
+  ADWIN_OPT_IN(logit_pass_dma_kernel<kModeSingleFwdDiag>, kDmaLds)
+#undef ADWIN_OPT_IN
+  return hipSuccess;
+}
+
+hipError_t launch_row_image(const RowImageArgs& a, unsigned tiles, hipStream_t st) {
+  row_image_kernel<<<dim3((unsigned)a.nk, tiles), 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_logit_pass(int mode, bool dma, const LogitPassArgs& a, unsigned grid, hipStream_t st) {
+  if (!dma) {
+    if (mode == kModeStats) logit_pass_kernel<false><<<grid, 256, kLogitLds, st>>>(a);
+    else if (mode == kModeDz) logit_pass_kernel<true><<<grid, 256, kLogitLds, st>>>(a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
+  switch (mode) {
+    case kModeStats: logit_pass_dma_kernel<kModeStats><<<grid, 256, kDmaLds, st>>>(a); break;
+    case kModeDz: logit_pass_dma_kernel<kModeDz><<<grid, 256, kDmaLds, st>>>(a); break;
+    case kModeSingle: logit_pass_dma_kernel<kModeSingle><<<grid, 256, kDmaLds, st>>>(a); break;
+    case kModeSingleDiag: logit_pass_dma_kernel<kModeSingleDiag><<<grid, 256, kDmaLds, st>>>(a); break;
+    case kModeSingleE2: logit_pass_dma_kernel<kModeSingleE2><<<grid, 256, kDmaLds, st>>>(a); break;
+    case kModeSingleE2Diag: logit_pass_dma_kernel<kModeSingleE2Diag><<<grid, 256, kDmaLds, st>>>(a); break;
+    case kModeSingleFwd: logit_pass_dma_kernel<kModeSingleFwd><<<grid, 256, kDmaLds, st>>>(a); break;
+    case kModeSingleFwdDiag: logit_pass_dma_kernel<kModeSingleFwdDiag><<<grid, 256, kDmaLds, st>>>(a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_token_logit(const TokenLogitArgs& a, hipStream_t st) {
+  token_logit_kernel<<<(unsigned)((a.n_pad + 3) / 4), 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_make_refs(const float* part, int64_t n_pad, const float* zy_s, const float* zy_t,
+                            const int32_t* yid, float* ref_s2, float* ref_t2, float* mu0, hipStream_t st) {
+  make_refs_kernel<<<(unsigned)((n_pad + 255) / 256), 256, 0, st>>>(part, n_pad, zy_s, zy_t, yid, ref_s2,
+                                                                    ref_t2, mu0);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_stats(const MergeArgs& a, hipStream_t st) {
+  merge_stats_kernel<<<(unsigned)((a.n_pad + 3) / 4), 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_single(const MergeSingleArgs& a, hipStream_t st) {
+  merge_single_kernel<<<(unsigned)((a.rows + 3) / 4), 256, 0, st>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace adwin
