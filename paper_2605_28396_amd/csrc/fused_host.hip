@@ -2,6 +2,7 @@
 // that makes one call (Sec. 4.1: supervision on the admitted prefix; Sec. 4.2: the probe
 // audit against the full-rollout gradient).  The kernels are in sweep_kernels.hip,
 // grad_kernels.hip and reduce_kernels.hip; nothing here touches device memory itself.
+#include <optional>
 #include <utility>
 #include <vector>
 
@@ -228,9 +229,10 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
   unsigned char* ws = (unsigned char*)workspace;
   ADWIN_HIP_TRY(ensure_lds_opt_in());
 
-  PhaseScope* scope = new PhaseScope(timer, ADWIN_PHASE_SETUP);
-  struct ScopeGuard { PhaseScope*& s; ~ScopeGuard() { delete s; } } guard{scope};
-  auto phase = [&](int ph) { delete scope; scope = new PhaseScope(timer, ph); };
+  // one timed span at a time: starting a phase ends the previous one (no-ops without a timer)
+  std::optional<PhaseScope> scope;
+  auto phase = [&](int ph) { scope.reset(); scope.emplace(timer, ph); };
+  phase(ADWIN_PHASE_SETUP);
   ADWIN_HIP_TRY(launch_upload(ws + L.o_plan, blob.data(), blob.size(), stream));
   DevicePlan pl = device_plan_at(ws + L.o_plan, p->B, (int32_t*)(ws + L.o_row_idx),
                                  (int32_t*)(ws + L.o_row_seq));
