@@ -488,6 +488,43 @@ def test_minimal_and_odd_shapes(B, V, H_s, H_t, lens, win):
     Hp.assert_grad(out["dz"].float().cpu().numpy(), refl["dz"], "dz", Hp.BF16_ULP)
 
 
+def _random_shapes(n_cases, seed):
+    g = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n_cases):
+        V = 8 * int(g.integers(1, 150, endpoint=True))
+        H_s, H_t = (64 * int(g.integers(1, 7, endpoint=True)) for _ in range(2))
+        nb = int(g.integers(1, 6, endpoint=True))
+        lens = [int(g.integers(0, 400, endpoint=True)) if g.random() > 0.15 else 0 for _ in range(nb)]
+        if sum(lens) == 0:
+            lens[0] = 1
+        win = [int(g.integers(0, l + 50, endpoint=True)) for l in lens]
+        cases.append((V, H_s, H_t, lens, win, int(g.integers(0, 1, endpoint=True))))
+    return cases
+
+
+@pytest.mark.parametrize("V,H_s,H_t,lens,win,mode", _random_shapes(12, 20260528))
+def test_random_small_shapes(B, V, H_s, H_t, lens, win, mode):
+    """Seeded random shapes between the hand-picked ones: vocabularies of 8 .. 1200 entries, hidden
+    sizes of 64 .. 448 (both logit kernels), empty rollouts, zero and over-long windows."""
+    w = synth.Workload(f"rnd_{V}_{H_s}_{H_t}_{len(lens)}", V, H_s, H_t, synth._offsets(lens),
+                       np.array(win, np.int32), mode)
+    p = synth.hidden_problem(w)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
+                      reduction=O.RED_SUM, mode=mode, summand_norms=True)
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32)
+    adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
+    for k, mask in (("dh_prefix", adm), ("dh_full", np.ones(w.T, bool))):
+        if k == "dh_full" and mode != synth.MODE_PREFIX_AND_FULL:
+            continue
+        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask[:, None] + 1e-6 * np.abs(ref[k]).max()
+        err = np.abs(got[k] - ref[k])
+        assert (err <= tol).all(), (k, err.max(), (err / np.maximum(tol, 1e-30)).max())
+        got[k] = ref[k]                          # checked element by element; the rest at the standard bar
+    _check_fused(w, got, ref, O.RED_SUM)
+
+
 def test_every_output_is_optional(B):
     """NULL for an output means not wanted: each output alone equals the same output of a call
     that asks for everything."""
