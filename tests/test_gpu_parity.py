@@ -140,6 +140,31 @@ def test_logits_given_matches_oracle_every_element(B, name, reduction):
                   1e-2 * np.abs(got["dz"]).sum(axis=1) + 1e-30)
 
 
+@pytest.mark.parametrize("estimator", [O.EST_EXPECTED, O.EST_SAMPLED])
+def test_logits_given_vocabulary_beyond_the_resident_capacity(B, estimator):
+    """The row-resident kernel keeps 153,600 logits of a row pair on chip; a longer row reads
+    the excess from memory in both sweeps.  V = 153,896: 37 vectors beyond the capacity, the
+    last resident iteration full."""
+    V = 153600 + 8 * 37
+    w = synth.Workload("long_rows", V, 0, 0, synth._offsets([2, 0, 3]), np.array([2, 4, 2], np.int32))
+    p = synth.logits_problem(w)
+    f = Hp.oracle_inputs(p)
+    ref = O.supervise_from_logits(f["z_s"], f["z_t"], f["ids"], w.offsets, w.window,
+                                  reduction=O.RED_SUM, estimator=estimator)
+    d = {k: v.cuda() for k, v in p.items()}
+    out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window,
+                                  reduction=O.RED_SUM, estimator=estimator)
+    torch.cuda.synchronize()
+    got = {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
+           for k, v in out.items()}
+    assert int(got["status_dev"][0]) == 0 and int(got["n_adm_out"][0]) == 4
+    Hp.assert_kl(got["kl"], ref["kl"])
+    Hp.assert_cost(got["c"], ref["c"])
+    Hp.assert_grad(got["dz"], ref["dz"], "dz", Hp.BF16_ULP)
+    assert np.all(got["dz"][4] == 0)                      # the row outside its window
+    Hp.assert_close_rel(got["loss_prefix"], ref["loss_prefix"], Hp.LOSS_REL, "loss_prefix")
+
+
 @pytest.mark.parametrize("env", [{"ADWIN_TWO_SWEEP": "1"}, {"ADWIN_NO_DMA": "1"}])
 def test_fallback_schemes_match_oracle(B, env, monkeypatch):
     """The two-sweep scheme and the register-staged logit kernel stay available (selected
