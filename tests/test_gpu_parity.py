@@ -100,6 +100,36 @@ def test_fused_is_deterministic_and_flags_bad_ids(B):
     assert c["c"][0] == 0.0 and np.array_equal(c["kl"], a["kl"])
 
 
+def test_non_finite_rows_are_flagged_and_stay_local(B):
+    """A row whose logits overflow (an infinite hidden state; logits thousands of nats apart, far
+    beyond what exp(z - ref) holds) sets ADWIN_DEV_NONFINITE in status_dev; the other rows are
+    what they are without it."""
+    w = synth.workload("ragged_small")
+    p = synth.hidden_problem(w)
+    clean = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM)
+    assert int(clean["status_dev"][0]) == 0
+    rows = O.plan(w.offsets, w.window)["rows"]
+    for poison in (float("inf"), 3.0e4):
+        q = dict(p)
+        q["h_s"] = p["h_s"].clone()
+        bad = int(rows[3])
+        if poison == float("inf"):
+            q["h_s"][bad, 7] = poison
+        else:
+            q["h_s"][bad] *= poison
+        got = _run_fused(B, w, q, "cuda", reduction=O.RED_SUM)
+        assert int(got["status_dev"][0]) & B.ADWIN_DEV_NONFINITE, poison
+        keep = np.ones(w.T, bool); keep[bad] = False
+        assert np.array_equal(got["kl"][keep], clean["kl"][keep])
+        assert np.array_equal(got["dh_prefix"][keep], clean["dh_prefix"][keep])
+    lo = synth.logits_problem(w)
+    d = {k: v.cuda() for k, v in lo.items()}
+    d["z_s"][int(rows[3]), 5] = float("inf")
+    out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window, reduction=O.RED_SUM)
+    torch.cuda.synchronize()
+    assert int(out["status_dev"][0]) & B.ADWIN_DEV_NONFINITE
+
+
 def test_teacher_equal_to_student_gives_zero(B):
     w = synth.workload("tiny_probe")
     p = synth.hidden_problem(w)
