@@ -30,3 +30,24 @@ def test_mfma_probes_stay_below_the_published_peak(B):
     const = B.adwin_opd_ceiling_mfma()
     rand = B.adwin_opd_ceiling_mfma_random()
     assert 500.0 < rand <= const * 1.05 and const < 2600.0, (const, rand)
+
+
+def test_profiling_entry_points_time_the_same_call(B):
+    """The *_profile variants run the same launches between HIP events: same outputs bit for
+    bit, non-negative phase times, and the phases the call does not have stay zero."""
+    from paper_2605_28396_amd import synth
+    w = synth.workload("ragged_mid")
+    p = {k: v.cuda() for k, v in synth.hidden_problem(w).items()}
+    call = B.FusedCall(p["h_s"], p["h_t"], p["W_s"], p["W_t"], p["ids"], w.offsets, w.window, mode=w.mode)
+    assert call.run() == 0
+    torch.cuda.synchronize()
+    plain = {k: v.clone() for k, v in call.out.items()}
+    ph = B.adwin_opd_fused_profile(call)
+    assert set(ph) == set(B.PHASE_NAMES) and all(v >= 0.0 for v in ph.values())
+    assert ph["stats"] > 0.0 and ph["dz"] > 0.0 and ph["grad"] > 0.0
+    for k, v in call.out.items():
+        assert torch.equal(v, plain[k]), k
+    lo = {k: v.cuda() for k, v in synth.logits_problem(w).items()}
+    lcall = B.LogitsCall(lo["z_s"], lo["z_t"], lo["ids"], w.offsets, w.window)
+    ph = B.adwin_opd_from_logits_profile(lcall)
+    assert ph["stats"] > 0.0 and ph["grad"] == 0.0 and ph["dz"] == 0.0
