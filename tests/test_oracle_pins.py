@@ -600,3 +600,16 @@ def test_error_scale_of_the_sampled_gradient():
         c = abs(O.token_cost(zs, zt, y))
         assert (sc >= np.abs(dz) - 1e-15).all()
         assert sc[y] == pytest.approx(c) and sc.sum() == pytest.approx(c * (2 - np.exp(O.log_softmax(zs))[y]))
+
+
+def test_cosine_against_angles_and_the_zero_convention():
+    """cos between plane vectors at known angles; scale invariance; a zero norm gives 0 (the
+    convention the alignment outputs follow)."""
+    for deg in (0.0, 30.0, 90.0, 135.0, 180.0):
+        th = math.radians(deg)
+        a, b = np.array([2.0, 0.0, 0.0]), 5.0 * np.array([math.cos(th), math.sin(th), 0.0])
+        assert O.cosine(a, b) == pytest.approx(math.cos(th), abs=1e-15)
+        assert O.cosine(-3.0 * a, b) == pytest.approx(-math.cos(th), abs=1e-15)
+    assert O.cosine(np.zeros(4), np.ones(4)) == 0.0 and O.cosine(np.ones(4), np.zeros(4)) == 0.0
+    m = RNG.normal(size=(3, 5))
+    assert O.cosine(m, 2.0 * m) == pytest.approx(1.0)          # arrays are flattened
