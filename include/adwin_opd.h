@@ -29,8 +29,8 @@
  *   - Work is enqueued on the caller's HIP stream (`hip_stream` is a hipStream_t, NULL
  *     = default stream) and the call returns without synchronising.  Outputs are
  *     defined once the stream has drained and the status was ADWIN_OK.  After a first
- *     call on the device (which sets kernel attributes) a call is nothing but kernel
- *     launches, so it may be captured in a HIP graph; the host arrays are read at
+ *     call on the device or adwin_opd_init (either sets the kernel attributes) a call is
+ *     nothing but kernel launches, so it may be captured in a HIP graph; the host arrays are read at
  *     capture, the device buffers at every replay.
  *   - Row t of the packed [T, .] arrays holds the hidden state (or logits) of the
  *     context (x, y_<t) and ids[t] = y_t: the caller has already applied the
@@ -220,6 +220,15 @@ typedef struct adwin_opd_logits_problem {
 
 /* Library version: major*10000 + minor*100 + patch.  Pure host. */
 int adwin_opd_version(void);
+
+/*
+ * Optional per-device set-up: sets the kernel attributes (dynamic LDS sizes) of every kernel
+ * on the current HIP device.  The entry points do this themselves on their first call on a
+ * device; a caller that captures its first call in a HIP graph, or that makes first calls
+ * from several threads at once, calls this once per device beforehand.  Idempotent; no
+ * memory is allocated, nothing is enqueued.  Returns ADWIN_OK or ADWIN_E_HIP.
+ */
+int adwin_opd_init(void);
 
 /* Static, NUL-terminated description of a status code.  Pure host. */
 const char* adwin_opd_strerror(int status);

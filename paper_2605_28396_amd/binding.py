@@ -103,6 +103,8 @@ def _load() -> C.CDLL:
     lib.adwin_opd_from_logits_profile.restype = C.c_int
     lib.adwin_opd_from_logits_profile.argtypes = [C.POINTER(adwin_opd_logits_problem), C.c_void_p,
                                                   C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
+    lib.adwin_opd_init.restype = C.c_int
+    lib.adwin_opd_init.argtypes = []
     lib.adwin_opd_ceiling_copy.restype = C.c_int
     lib.adwin_opd_ceiling_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p,
                                            C.POINTER(C.c_float)]
@@ -370,6 +372,11 @@ def adwin_opd_from_logits(z_s, z_t, ids, offsets, window, stream=None, **kw) -> 
     call = LogitsCall(z_s, z_t, ids, offsets, window, **kw)
     _check(call.run(stream))
     return call.out
+
+
+def adwin_opd_init() -> None:
+    """Sets the kernel attributes on the current device (optional; see the header)."""
+    _check(lib.adwin_opd_init())
 
 
 def adwin_opd_ceiling_copy(nbytes: int = 1 << 30, reps: int = 10, stream=None) -> float:

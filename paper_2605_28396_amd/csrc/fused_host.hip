@@ -177,6 +177,15 @@ static hipError_t ensure_lds_opt_in() {
 
 using namespace adwin;
 
+extern "C" int adwin_opd_init(void) {
+  ADWIN_HIP_TRY(sweep_kernels_opt_in());
+  ADWIN_HIP_TRY(grad_kernels_opt_in());
+  ADWIN_HIP_TRY(logits_kernels_opt_in());
+  (void)first_use_on_device(0);      // the calls need not repeat it on this device
+  (void)first_use_on_device(1);
+  return ADWIN_OK;
+}
+
 extern "C" int adwin_opd_workspace_bytes(const adwin_opd_problem* p, size_t* bytes) {
   if (!bytes) return ADWIN_E_NULL;
   int st = check_problem(p);

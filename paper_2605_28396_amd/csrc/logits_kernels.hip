@@ -417,6 +417,11 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
   }
 }
 
+hipError_t logits_kernels_opt_in() {
+  return hipFuncSetAttribute((const void*)logits_row_resident_kernel,
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes);
+}
+
 struct LogitsLayout {
   size_t o_plan, o_klr, o_seg, o_racc, o_summ, total;
   LogitsLayout(int32_t B, int64_t T) {
@@ -487,16 +492,14 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
     a.t_logp = p->t_logp; a.t_entropy = p->t_entropy; a.t_rank = p->t_rank;
     a.sampled = p->estimator == ADWIN_EST_SAMPLED;
     PhaseScope scope(timer, ADWIN_PHASE_STATS);
-    static const bool streaming = getenv("ADWIN_LOGITS_STREAMING") != nullptr;
+    const bool streaming = getenv("ADWIN_LOGITS_STREAMING") != nullptr;
     if (p->t_logp || p->t_entropy || p->t_rank) {
       // the diagnostics ride on the streaming kernel (the row-resident one has no register to spare)
       logits_row_kernel<true><<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
     } else if (streaming) {
       logits_row_kernel<false><<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);
     } else {
-      if (first_use_on_device(1))
-        ADWIN_HIP_TRY(hipFuncSetAttribute((const void*)logits_row_resident_kernel,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes));
+      if (first_use_on_device(1)) ADWIN_HIP_TRY(logits_kernels_opt_in());
       logits_row_resident_kernel<<<(unsigned)p->T, kResThreads, kResLdsBytes, stream>>>(a);
     }
     ADWIN_HIP_TRY(hipGetLastError());

@@ -30,6 +30,9 @@ HostPlan make_host_plan(int64_t T, int32_t B, const int64_t* offsets, const int3
 
 DevicePlan device_plan_at(unsigned char* ws_plan, int32_t B, int32_t* row_idx, int32_t* row_seq);
 
+// large dynamic LDS of the row-resident logits kernel, once per device (logits_kernels.hip)
+hipError_t logits_kernels_opt_in();
+
 // --- launchers (all asynchronous on `st`) ---------------------------------------------
 hipError_t launch_build_rows(const DevicePlan& pl, int32_t B, int64_t n_rows, int64_t n_pad,
                              hipStream_t st);

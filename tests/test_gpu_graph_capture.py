@@ -18,6 +18,11 @@ def B():
     return binding
 
 
+def test_init_is_idempotent(B):
+    B.adwin_opd_init()
+    B.adwin_opd_init()
+
+
 def _snapshot(out):
     return {k: v.clone() for k, v in out.items()}
 
