@@ -208,6 +208,11 @@ def test_fallback_schemes_match_oracle(B, env, monkeypatch):
                       reduction=O.RED_SUM, grad_scale=1.0, mode=w.mode)
     got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, grad_scale=1.0, dh_dtype=B.ADWIN_DT_F32)
     _check_fused(w, got, ref, O.RED_SUM)
+    # the switch is in force: what rides on the single sweep is refused under it
+    d = {k: v.cuda() for k, v in p.items()}
+    call = B.FusedCall(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window, mode=w.mode,
+                       want=B.FusedCall.DEFAULT_OUTPUTS + ("t_entropy",))
+    assert call.run() == B.ADWIN_E_MODE
 
 
 @pytest.mark.parametrize("name,reduction", [
