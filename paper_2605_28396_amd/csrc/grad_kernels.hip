@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void hst_image_kernel(HstImageArgs a) {
 // Pass 3: g[r][h] = sum_v dz[r][v] W_s[v][h].  256 x 256 output tile, 2 x 2 waves of
 // 128 x 128.  A = slab rows (i = row), B = rows of W_s^T (j = hidden column, contiguous in
 // g).  The k-steps (one 32 KiB block of each operand) go through five block buffers in the
-// LDS, three for A and two for B, by direct global->LDS loads.  Per k-step a wave issues
+// LDS, three for B and two for A, by direct global->LDS loads.  Per k-step a wave issues
 // its 16 wave-loads of the k-step after next in the shadow of MFMAs (see grad_kstep), so
 // that they have a k-step or more (upwards of 2000 matrix-pipe cycles) to land.  The one
 // barrier per k-step sits before the last of the four k16 sub-steps: by then every fragment
@@ -194,23 +194,26 @@ __global__ __launch_bounds__(256) void hst_image_kernel(HstImageArgs a) {
 // the next blocks' first fragments and the matrix pipe never waits for LDS after a barrier.
 // ---------------------------------------------------------------------------------------
 
-constexpr int kGradABufs = 3;                                 // A blocks in flight or in use
-constexpr int kGradBOff = kGradABufs * kImgBytes;             // the two B buffers follow
-constexpr int kGradLds = (kGradABufs + 2) * kImgBytes;        // 160 KiB
+// Five block buffers fill the 160 KiB of LDS: a ring of three for the B operand and a ring
+// of two for the A operand.
+constexpr int kGradRing3 = 3;
+constexpr int kGradRing2Off = kGradRing3 * kImgBytes;         // the ring of two follows
+constexpr int kGradLds = (kGradRing3 + 2) * kImgBytes;        // 160 KiB
 
-// LOADS: in k-step s the A block of k-step s + 2 is loaded in sub-step 1 (into the third A
-// buffer, which no wave reads any more once it has passed the previous step's barrier) and
-// the B block of k-step s + 2 in sub-step 3, after this step's barrier, into the B buffer
-// this step has just finished reading.  The A blocks are the stream that comes from HBM (a
-// slab block is used by the h tiles of one row tile and never again) and get a lead of a
-// k-step and a half, the B blocks, shared by every row tile and mostly found in the L2, one
-// k-step.  Loads return in order: the wait before the barrier leaves the youngest eight,
-// this step's A loads, in flight.
+// LOADS: in k-step s the B block of k-step s + 2 is loaded in sub-step 1 (`early`: into the
+// third buffer of its ring, which no wave reads any more once it has passed the previous
+// step's barrier) and the A block of k-step s + 2 in sub-step 3 (`late`: after this step's
+// barrier, into the buffer of the ring of two that this step has just finished reading).
+// The early operand has a lead of a k-step and a half, the late one of one k-step.  Which
+// operand gets which was measured: in `dz W_s` every XCD streams all of W_s^T (B) once per
+// round of tiles while a slab block (A) is fetched by one XCD only, and the deeper lead on
+// B is worth 2 % (on A 4 % against no third buffer at all).  Loads return in order: the wait
+// before the barrier leaves the youngest eight, this step's early loads, in flight.
 template <bool LOADS, bool LAST>
 __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][4],
                                            const char* curA, const char* curB, const char* nxtA,
-                                           const char* nxtB, int lane, uint32_t lds_a2, uint32_t lds_b2,
-                                           uint32_t voff, const char* sB2, const char* sA2) {
+                                           const char* nxtB, int lane, uint32_t lds_early, uint32_t lds_late,
+                                           uint32_t voff, const char* s_late, const char* s_early) {
   const int key = (lane >> 1) & 7, half = lane >> 5;
   const int rowoff = (lane & 31) * kRowBytes;
   int sw[4];
@@ -223,7 +226,7 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
   ADWIN_FENCE
   // side operation M (0..15) in the shadow of MFMA M of sub-step KK: fragment reads of the
   // next sub-step, then (sub-steps 1 and 3) the wave-loads of the k-step after next: 4 KiB
-  // groups d = 0..7 of the A block, then of the B block, each offset by this wave's 1 KiB
+  // groups d = 0..7 of the early block, then of the late block, each offset by this wave's 1 KiB
 #define ADWIN_SIDE(KK, M)                                                                           \
   if constexpr ((KK) < 3 && (M) < 8) {                                                              \
     if constexpr (((M) & 1) == 0)                                                                   \
@@ -232,10 +235,10 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
       fb[((KK) + 1) & 1][((M) >> 1) & 3] = *(const bf16x8*)(curB + (((M) >> 1) & 3) * 32 * kRowBytes + sw[(KK) + 1]); \
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 1 && (M) >= 8 && LOADS) {                                            \
-    dma16(lds_a2 + (uint32_t)((M) - 8) * 4096u, voff, sA2 + ((M) - 8) * 4096);                      \
+    dma16(lds_early + (uint32_t)((M) - 8) * 4096u, voff, s_early + ((M) - 8) * 4096);                \
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 3 && (M) >= 8 && LOADS) {                                            \
-    dma16(lds_b2 + (uint32_t)((M) - 8) * 4096u, voff, sB2 + ((M) - 8) * 4096);                      \
+    dma16(lds_late + (uint32_t)((M) - 8) * 4096u, voff, s_late + ((M) - 8) * 4096);                  \
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 3 && (M) < 8 && !LAST) {                                             \
     if constexpr (((M) & 1) == 0)                                                                   \
@@ -299,16 +302,17 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       for (int e = 0; e < 16; ++e) acc[fm][fn][e] = 0.f;
 
   if (nk > 0) {
-    // blocks of the first k-step, then its first fragments
+    // the ring of three (offset 0) holds the W_s^T blocks, the ring of two the slab blocks;
+    // first the blocks of k-step 0, then its first fragments
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
-      dma16(ldsw + (uint32_t)d * 4096u, voff, sA + d * 4096);
-      dma16(ldsw + (uint32_t)kGradBOff + (uint32_t)d * 4096u, voff, sB + d * 4096);
+      dma16(ldsw + (uint32_t)d * 4096u, voff, sB + d * 4096);
+      dma16(ldsw + (uint32_t)kGradRing2Off + (uint32_t)d * 4096u, voff, sA + d * 4096);
     }
     wait_vm<0>();
     __syncthreads();
     bf16x8 fa[2][4], fb[2][4];
-    const int waveA = wm * 128 * kRowBytes, waveB = kGradBOff + wn * 128 * kRowBytes;
+    const int waveA = kGradRing2Off + wm * 128 * kRowBytes, waveB = wn * 128 * kRowBytes;
     {
       const int key = (lane >> 1) & 7, half = lane >> 5;
       const int sw0 = (lane & 31) * kRowBytes + ((half ^ key) << 4);
@@ -321,34 +325,34 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     // blocks of k-step 1 (k-step s of the loop loads those of k-step s + 2)
     if (nk > 1) {
 #pragma unroll
-      for (int d = 0; d < 8; ++d) dma16(ldsw + kImgBytes + (uint32_t)d * 4096u, voff, sA + kImgBytes + d * 4096);
+      for (int d = 0; d < 8; ++d) dma16(ldsw + kImgBytes + (uint32_t)d * 4096u, voff, sB + kImgBytes + d * 4096);
 #pragma unroll
       for (int d = 0; d < 8; ++d)
-        dma16(ldsw + kGradBOff + kImgBytes + (uint32_t)d * 4096u, voff, sB + kImgBytes + d * 4096);
+        dma16(ldsw + kGradRing2Off + kImgBytes + (uint32_t)d * 4096u, voff, sA + kImgBytes + d * 4096);
     }
-    // k-step s reads A buffer s % 3 and B buffer s % 2
-    int s = 0, ia = 0;
+    // k-step s reads B buffer s % 3 and A buffer s % 2
+    int s = 0, ib = 0;
     for (; s + 2 < nk; ++s) {
-      const int ia1 = ia == kGradABufs - 1 ? 0 : ia + 1, ia2 = ia1 == kGradABufs - 1 ? 0 : ia1 + 1;
-      const int ib = (s & 1) * kImgBytes, ib1 = kImgBytes - ib;
-      grad_kstep<true, false>(acc, fa, fb, lds + ia * kImgBytes + waveA, lds + ib + waveB,
-                              lds + ia1 * kImgBytes + waveA, lds + ib1 + waveB, lane,
-                              ldsw + ia2 * kImgBytes, ldsw + kGradBOff + ib, voff,
-                              sB + (int64_t)(s + 2) * kImgBytes, sA + (int64_t)(s + 2) * kImgBytes);
-      ia = ia1;
+      const int ib1 = ib == kGradRing3 - 1 ? 0 : ib + 1, ib2 = ib1 == kGradRing3 - 1 ? 0 : ib1 + 1;
+      const int ia = (s & 1) * kImgBytes, ia1 = kImgBytes - ia;
+      grad_kstep<true, false>(acc, fa, fb, lds + ia + waveA, lds + ib * kImgBytes + waveB,
+                              lds + ia1 + waveA, lds + ib1 * kImgBytes + waveB, lane,
+                              ldsw + ib2 * kImgBytes, ldsw + kGradRing2Off + ia, voff,
+                              sA + (int64_t)(s + 2) * kImgBytes, sB + (int64_t)(s + 2) * kImgBytes);
+      ib = ib1;
     }
     if (s + 1 < nk) {
-      const int ia1 = ia == kGradABufs - 1 ? 0 : ia + 1;
-      const int ib = (s & 1) * kImgBytes, ib1 = kImgBytes - ib;
-      grad_kstep<false, false>(acc, fa, fb, lds + ia * kImgBytes + waveA, lds + ib + waveB,
-                               lds + ia1 * kImgBytes + waveA, lds + ib1 + waveB, lane, ldsw, ldsw, voff, sB, sA);
-      ia = ia1;
+      const int ib1 = ib == kGradRing3 - 1 ? 0 : ib + 1;
+      const int ia = (s & 1) * kImgBytes, ia1 = kImgBytes - ia;
+      grad_kstep<false, false>(acc, fa, fb, lds + ia + waveA, lds + ib * kImgBytes + waveB,
+                               lds + ia1 + waveA, lds + ib1 * kImgBytes + waveB, lane, ldsw, ldsw, voff, sA, sB);
+      ib = ib1;
       ++s;
     }
     {
-      const int ib = (s & 1) * kImgBytes;
-      grad_kstep<false, true>(acc, fa, fb, lds + ia * kImgBytes + waveA, lds + ib + waveB, lds, lds, lane,
-                              ldsw, ldsw, voff, sB, sA);
+      const int ia = (s & 1) * kImgBytes;
+      grad_kstep<false, true>(acc, fa, fb, lds + ia + waveA, lds + ib * kImgBytes + waveB, lds, lds, lane,
+                              ldsw, ldsw, voff, sA, sB);
     }
   }
   float* g = a.g + (int64_t)split * a.g_rows * a.H;
