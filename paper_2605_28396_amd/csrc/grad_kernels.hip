@@ -200,11 +200,12 @@ constexpr int kGradRing3 = 3;
 constexpr int kGradRing2Off = kGradRing3 * kImgBytes;         // the ring of two follows
 constexpr int kGradLds = (kGradRing3 + 2) * kImgBytes;        // 160 KiB
 
-// LOADS: in k-step s the B block of k-step s + 2 is loaded in sub-step 1 (`early`: into the
-// third buffer of its ring, which no wave reads any more once it has passed the previous
-// step's barrier) and the A block of k-step s + 2 in sub-step 3 (`late`: after this step's
+// LOADS: in k-step s the B block of k-step s + 2 is loaded in sub-steps 1 and 2, four
+// wave-loads behind the last MFMAs of each (`early`: into the third buffer of its ring, which
+// no wave reads any more once it has passed the previous step's barrier; all eight in one
+// sub-step, whichever, is 1 % slower) and the A block of k-step s + 2 in sub-step 3 (`late`: after this step's
 // barrier, into the buffer of the ring of two that this step has just finished reading).
-// The early operand has a lead of a k-step and a half, the late one of one k-step.  Which
+// The early operand has a lead of a k-step and a quarter to a half, the late one of one k-step.  Which
 // operand gets which was measured: in `dz W_s` every XCD streams all of W_s^T (B) once per
 // round of tiles while a slab block (A) is fetched by one XCD only, and the deeper lead on
 // B is worth 2 % (on A 4 % against no third buffer at all).  Loads return in order: the wait
@@ -225,7 +226,7 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
                                                       acc[I][J], 0, 0, 0);                    \
   ADWIN_FENCE
   // side operation M (0..15) in the shadow of MFMA M of sub-step KK: fragment reads of the
-  // next sub-step, then (sub-steps 1 and 3) the wave-loads of the k-step after next: 4 KiB
+  // next sub-step, then (sub-steps 1, 2 and 3) the wave-loads of the k-step after next: 4 KiB
   // groups d = 0..7 of the early block, then of the late block, each offset by this wave's 1 KiB
 #define ADWIN_SIDE(KK, M)                                                                           \
   if constexpr ((KK) < 3 && (M) < 8) {                                                              \
@@ -234,8 +235,9 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
     else                                                                                            \
       fb[((KK) + 1) & 1][((M) >> 1) & 3] = *(const bf16x8*)(curB + (((M) >> 1) & 3) * 32 * kRowBytes + sw[(KK) + 1]); \
     ADWIN_FENCE                                                                                     \
-  } else if constexpr ((KK) == 1 && (M) >= 8 && LOADS) {                                            \
-    dma16(lds_early + (uint32_t)((M) - 8) * 4096u, voff, s_early + ((M) - 8) * 4096);                \
+  } else if constexpr (((KK) == 1 || (KK) == 2) && (M) >= 12 && LOADS) {                            \
+    dma16(lds_early + (uint32_t)(((KK) - 1) * 4 + (M) - 12) * 4096u, voff,                          \
+          s_early + (((KK) - 1) * 4 + (M) - 12) * 4096);                                            \
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 3 && (M) >= 8 && LOADS) {                                            \
     dma16(lds_late + (uint32_t)((M) - 8) * 4096u, voff, s_late + ((M) - 8) * 4096);                  \
