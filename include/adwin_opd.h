@@ -24,8 +24,13 @@
  *     of them travels in kernel arguments, not in asynchronous copies;
  *     "device" pointers are HIP device memory on the current device, owned by the
  *     caller, row-major and contiguous, 16-byte aligned.
- *   - The library allocates no device memory and keeps no state between calls.  All
- *     scratch comes from the caller's workspace (size from *_workspace_bytes).
+ *   - The library allocates no device memory.  All scratch comes from the caller's
+ *     workspace (size from *_workspace_bytes); the one exception is
+ *     adwin_opd_from_logits_static, whose scratch is a fixed array inside the library.
+ *     What the library remembers between calls: per device, that the kernel attributes
+ *     have been set (first call or adwin_opd_init) and the address of that array; per
+ *     thread, the text of the last HIP error for adwin_opd_strerror.  No result of one
+ *     call depends on an earlier one.
  *   - Work is enqueued on the caller's HIP stream (`hip_stream` is a hipStream_t, NULL
  *     = default stream) and the call returns without synchronising.  Outputs are
  *     defined once the stream has drained and the status was ADWIN_OK.  After a first
@@ -58,8 +63,9 @@ extern "C" {
 #define ADWIN_E_WINDOW     -4  /* a window is negative                                         */
 #define ADWIN_E_ALIGN      -5  /* a device pointer is not 16-byte aligned                      */
 #define ADWIN_E_WORKSPACE  -6  /* workspace NULL, misaligned (256 B) or too small              */
-#define ADWIN_E_MODE       -7  /* unknown mode / reduction / dh_dtype / estimator, struct_bytes  */
-                               /* mismatch, or an option the selected scheme does not offer     */
+#define ADWIN_E_MODE       -7  /* unknown mode / reduction / dh_dtype / estimator / scheme,    */
+                               /* struct_bytes mismatch, or an option the selected scheme does */
+                               /* not offer                                                    */
 #define ADWIN_E_HIP        -8  /* a HIP call or kernel launch failed                           */
 
 /* mode */
@@ -90,7 +96,46 @@ extern "C" {
 
 /* bits of *status_dev (device-detected input faults; the call still completes) */
 #define ADWIN_DEV_BAD_ID     1u  /* some ids[t] on a computed row is outside [0, V): c_t = 0 there */
-#define ADWIN_DEV_NONFINITE  2u  /* a computed row produced a non-finite log-sum-exp            */
+#define ADWIN_DEV_NONFINITE  2u  /* a computed row produced a non-finite log-sum-exp, mean or KL:  */
+                                 /* that row is EXCLUDED -- its KL_t, c_t, diagnostics and          */
+                                 /* gradient rows are written as 0 and it adds 0 to every window    */
+                                 /* loss, batch value, alignment and head-weight gradient, so all   */
+                                 /* outputs stay finite -- and this bit tells the caller that the   */
+                                 /* Sec. 4.1 loss of the batch is short of those rows.  What to do: */
+                                 /* under the single-sweep scheme (below) the cause may be a row    */
+                                 /* whose logits lie more than ~80 nats above its fixed reference;  */
+                                 /* call again with scheme = ADWIN_SCHEME_TWO_SWEEP, which has no   */
+                                 /* such limit.  If the bit is still set, the inputs themselves     */
+                                 /* hold an inf or NaN (or logits beyond the fp32 range).           */
+
+/* scheme: how the fused path orders its passes over the vocabulary (Eq. 2 needs every row's
+ * log-sum-exp and mean before Eq. 4's gradient can be formed)
+ *   AUTO        SINGLE where the shape allows it (H_s >= 128 and H_t >= 128), else TWO_SWEEP_REG
+ *   SINGLE      one sweep: exponentials are taken against per-row references fixed beforehand
+ *               (the largest logit among the first 128 vocabulary entries and the sampled
+ *               token), two gradient factors per logit are kept and combined once the row's
+ *               mean is known.  Fastest; logits more than ~80 nats above the reference overflow
+ *               (the row is then excluded and ADWIN_DEV_NONFINITE set).  ADWIN_E_MODE if the
+ *               shape does not allow it.
+ *   TWO_SWEEP   running-maximum statistics over the vocabulary, then the logits again for the
+ *               gradient: any finite logit range; 1.75x the matrix work.  The diagnostics
+ *               (t_*), the sampled estimator and dW_* are not offered (ADWIN_E_MODE).
+ *   TWO_SWEEP_REG  TWO_SWEEP with operand tiles staged through registers, the kernel that hidden
+ *               sizes of 64 need; any shape.
+ * adwin_opd_workspace_bytes and adwin_opd_fused read the scheme from the same struct, so the
+ * size and the call agree by construction. */
+#define ADWIN_SCHEME_AUTO           0
+#define ADWIN_SCHEME_SINGLE         1
+#define ADWIN_SCHEME_TWO_SWEEP      2
+#define ADWIN_SCHEME_TWO_SWEEP_REG  3
+
+/* scheme of the logits-given path: which kernel streams the rows
+ *   AUTO / RESIDENT  one workgroup per row keeps the row pair on chip between its two sweeps, so
+ *                    memory sees each logit once (the diagnostics t_* always take STREAMING)
+ *   STREAMING        reads the row pair twice; no limit on what stays resident */
+#define ADWIN_LOGITS_AUTO       0
+#define ADWIN_LOGITS_RESIDENT   1
+#define ADWIN_LOGITS_STREAMING  2
 
 /*
  * Problem description for the fused path (hidden states in, Sec. 4.1 / 4.2).
@@ -98,8 +143,17 @@ extern "C" {
  * multiples of 64 (the k-extent of one staged MFMA tile).
  * The sampled estimator, the diagnostics (t_*) and the head-weight gradients (dW_*) ride on
  * the single-sweep kernels, which need H_s >= 128 and H_t >= 128; with a smaller hidden size, or
- * with the two-sweep scheme forced through the environment (ADWIN_TWO_SWEEP, ADWIN_NO_DMA), a
- * call that asks for them returns ADWIN_E_MODE.
+ * with a two-sweep `scheme`, a call that asks for them returns ADWIN_E_MODE.
+ * Precision of dh_*: the logit gradient is contracted with W_s as bf16, except for the few
+ * entries of a row that carry a probability of 1/32 or more, which are taken in fp32 (so that
+ * peaked rows, where a handful of entries make up the gradient, are as accurate as flat ones):
+ * max |dh - exact| <= 2e-3 max |dh| for vocabularies of a thousand entries or more.  Below
+ * that an element sums too few terms for the roundings to average out and is off by up to
+ * ~2^-8 of the Euclidean norm of its own summands instead.
+ * The environment variables ADWIN_SLAB_ROWS, ADWIN_STRIPS, ADWIN_STRIPS2 and ADWIN_TG override
+ * launch geometry (tuning and tests only; results do not depend on them beyond rounding order;
+ * a workspace sized under one setting and used under another is refused with
+ * ADWIN_E_WORKSPACE if it is too small).
  * Outputs are optional (NULL = not wanted).  When none of the requested outputs depends on
  * the gradients -- only kl, c, the window losses, n_out / n_adm_out / status_dev, the
  * diagnostics and their summaries, and batch in mode PREFIX_ONLY -- the call is a forward-only
@@ -180,6 +234,7 @@ typedef struct adwin_opd_problem {
                              /*     of computed positions of the rollout if there is none      */
   float* t_logp_mean;        /* [B + 1, 2] per rollout: window, beyond; row B: over all tokens  */
   float* cand_loss_share;    /* [n_candidates]                                                  */
+  int32_t scheme;            /* ADWIN_SCHEME_*                                                  */
 } adwin_opd_problem;
 
 /*
@@ -216,6 +271,7 @@ typedef struct adwin_opd_logits_problem {
   int32_t topk;              /* > 0 when t_first_reject is wanted                              */
   int32_t* t_first_reject;   /* [B] needs t_rank                                               */
   float* t_logp_mean;        /* [B + 1, 2] needs t_logp; the second column is 0 on this path    */
+  int32_t scheme;            /* ADWIN_LOGITS_*                                                  */
 } adwin_opd_logits_problem;
 
 /* Library version: major*10000 + minor*100 + patch.  Pure host. */

@@ -117,20 +117,6 @@ def token_dz(z_s, z_t):
     return p * (delta - np.sum(p * delta))
 
 
-def token_dz_scale(z_s, z_t):
-    """Magnitude against which a reduced-precision dz_t is to be judged, per entry:
-    p_s (|Delta - KL_t| + D_t) with D_t the standard deviation of Delta under p_s.  An
-    implementation that holds p_s and the centred Delta as separate rounded factors, centred at
-    any p_s-weighted mean of Delta over part of the vocabulary, makes errors proportional to this
-    and not to |dz_t|, which vanishes wherever Delta happens to equal KL_t."""
-    ls, lt = log_softmax(z_s), log_softmax(z_t)
-    p = np.exp(ls)
-    delta = ls - lt
-    kl = np.sum(p * delta)
-    dev = np.sqrt(np.sum(p * (delta - kl) ** 2))
-    return p * (np.abs(delta - kl) + dev)
-
-
 def token_dz_sampled(z_s, z_t, y):
     """The per-token term of the gamma = 0 estimator (Eq. 4) in logit space:
     c_t * d log p_s(y_t) / d z_s = c_t (e_{y_t} - p_s), with c_t held constant."""
@@ -138,17 +124,6 @@ def token_dz_sampled(z_s, z_t, y):
     e_y = np.zeros_like(p)
     e_y[y] = 1.0
     return token_cost(z_s, z_t, y) * (e_y - p)
-
-
-def token_dz_sampled_scale(z_s, z_t, y):
-    """Magnitude against which a reduced-precision sampled-token gradient is judged: |c_t| p_s
-    off the sampled entry and |c_t| on it -- the entry c_t (1 - p_s(y_t)) is a difference of two
-    rounded terms of magnitude up to |c_t| and vanishes as p_s(y_t) -> 1 while their errors do
-    not."""
-    p = np.exp(log_softmax(z_s))
-    s = np.abs(token_cost(z_s, z_t, y)) * p
-    s[y] = np.abs(token_cost(z_s, z_t, y))
-    return s
 
 
 def token_terms(h_s, h_t, W_s, W_t, y=None, estimator=EST_EXPECTED):
@@ -162,34 +137,24 @@ def token_terms(h_s, h_t, W_s, W_t, y=None, estimator=EST_EXPECTED):
     return kl, c, g
 
 
-def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, head_weights=None,
-               g_norms=None):
+def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, head_weights=None):
     """`token_terms` for a stack of independent rows.  Rows are batched through one
     matrix product per block only to let BLAS do the inner products; each row's
     softmax/KL/gradient is the single-row definition above.
 
     head_weights: optional list of per-row weight vectors w; for each one the gradient of
     sum_r w[r] KL_r with respect to the student LM-head weights, sum_r w[r] dz_r^T h_s[r]
-    (z = W h, so d z[v] / d W[v, k] = h[k]), is returned as a fourth value, and as a fifth the
-    Euclidean norm over r of the summands of each element, sqrt(sum_r (w[r] s_r[v] h_s[r][k])^2),
-    with s_r = `token_dz_scale` (expected estimator) or `token_dz_sampled_scale`: the scale of the
-    rounding error of any implementation that rounds the factors of the summands independently
-    (tests bound a reduced-precision result with it).
-    g_norms: optional [K, H_s] array that receives the same norm for the hidden-state gradient,
-    sqrt(sum_v (s_r[v] W_s[v][k])^2)."""
+    (z = W h, so d z[v] / d W[v, k] = h[k]), is returned as a fourth value."""
     K = H_s.shape[0]
     kl = np.zeros(K)
     c = np.zeros(K)
     g = np.zeros((K, W_s.shape[1]))
     dW = None if head_weights is None else [np.zeros(W_s.shape) for _ in head_weights]
-    dW_sq = None if head_weights is None else [np.zeros(W_s.shape) for _ in head_weights]
-    want_norms = g_norms is not None or head_weights is not None
     for r0 in range(0, K, block):
         r1 = min(K, r0 + block)
         Z_s = H_s[r0:r1] @ W_s.T
         Z_t = H_t[r0:r1] @ W_t.T
         D = np.empty_like(Z_s)
-        S = np.empty_like(Z_s) if want_norms else None
         for r in range(r0, r1):
             z_s, z_t = Z_s[r - r0], Z_t[r - r0]
             kl[r] = token_kl(z_s, z_t)
@@ -197,23 +162,15 @@ def rows_terms(H_s, H_t, W_s, W_t, ids=None, block=16, estimator=EST_EXPECTED, h
                 c[r] = token_cost(z_s, z_t, int(ids[r]))
             if estimator == EST_EXPECTED:
                 D[r - r0] = token_dz(z_s, z_t)
-                if want_norms:
-                    S[r - r0] = token_dz_scale(z_s, z_t)
             else:
                 D[r - r0] = token_dz_sampled(z_s, z_t, int(ids[r]))
-                if want_norms:
-                    S[r - r0] = token_dz_sampled_scale(z_s, z_t, int(ids[r]))
         g[r0:r1] = D @ W_s
-        if g_norms is not None:
-            g_norms[r0:r1] = np.sqrt((S ** 2) @ (W_s ** 2))
         if dW is not None:
             for k, w in enumerate(head_weights):
                 wD = D * np.asarray(w)[r0:r1, None]
                 dW[k] += wD.T @ H_s[r0:r1]
-                wS = S * np.asarray(w)[r0:r1, None]
-                dW_sq[k] += (wS ** 2).T @ (H_s[r0:r1] ** 2)
     if dW is not None:
-        return kl, c, g, dW, [np.sqrt(x) for x in dW_sq]
+        return kl, c, g, dW
     return kl, c, g
 
 
@@ -309,14 +266,11 @@ def window_outputs(kl, g, offsets, window, reduction=RED_SEQ_MEAN, grad_scale=1.
 
 def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
               grad_scale=1.0, mode=MODE_PREFIX_ONLY, estimator=EST_EXPECTED, head_gradient=False,
-              block=16, summand_norms=False):
+              block=16):
     """Whole path from hidden states (fp64 arrays holding the bf16-exact inputs).
     head_gradient: also dW_prefix / dW_full, the gradients of the prefix and full-rollout
-    batch objectives (times grad_scale) with respect to the student LM-head weights, and
-    dW_prefix_l2 / dW_full_l2, the Euclidean norms of their per-token summands.
-    block: rows per library matrix product in `rows_terms` (batching only).
-    summand_norms: also g_l2 [T, H_s], the Euclidean norm over the vocabulary of the summands
-    dz_t[v] W_s[v][k] of every element of g (0 on rows not computed)."""
+    batch objectives (times grad_scale) with respect to the student LM-head weights.
+    block: rows per library matrix product in `rows_terms` (batching only)."""
     p = plan(offsets, window)
     T = int(offsets[-1])
     if mode == MODE_PREFIX_AND_FULL:
@@ -324,10 +278,8 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
     else:
         rows = p["rows"]
     kl, c, g = np.zeros(T), np.zeros(T), np.zeros((T, W_s.shape[1]))
-    dW = dW_l2 = None
+    dW = None
     hw = None
-    g_l2 = np.zeros((T, W_s.shape[1])) if summand_norms else None
-    gn = np.zeros((len(rows), W_s.shape[1])) if summand_norms else None
     if head_gradient:
         ap, af = row_weights(p["len"], p["n"], reduction)
         wp, wf = np.zeros(T), np.zeros(T)
@@ -339,16 +291,12 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
     if len(rows):
         res = rows_terms(h_s[rows], h_t[rows], W_s, W_t,
                          None if ids is None else np.asarray(ids)[rows], block=block,
-                         estimator=estimator, head_weights=hw, g_norms=gn)
-        if summand_norms:
-            g_l2[rows] = gn
+                         estimator=estimator, head_weights=hw)
         kl[rows], c[rows], g[rows] = res[0], res[1], res[2]
         if head_gradient:
-            dW, dW_l2 = res[3], res[4]
+            dW = res[3]
     out = window_outputs(kl, g, offsets, window, reduction, grad_scale, mode)
     out.update(kl=kl, c=c, g=g, rows=rows)
-    if summand_norms:
-        out["g_l2"] = g_l2
     if head_gradient:
         zero = np.zeros(W_s.shape)
         out["dW_prefix"] = dW[0] if dW is not None else zero
@@ -356,8 +304,6 @@ def supervise(h_s, h_t, W_s, W_t, ids, offsets, window, reduction=RED_SEQ_MEAN,
         # alignment of the two objectives in the LM-head parameter block (Sec. 4.2's cosine taken
         # over the one parameter block this path differentiates)
         out["rho_head"] = cosine(out["dW_prefix"].ravel(), out["dW_full"].ravel())
-        out["dW_prefix_l2"] = dW_l2[0] if dW is not None else zero
-        out["dW_full_l2"] = (dW_l2[1] if dW is not None else zero) if mode == MODE_PREFIX_AND_FULL else zero
     return out
 
 

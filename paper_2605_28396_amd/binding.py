@@ -26,6 +26,8 @@ ADWIN_DT_BF16, ADWIN_DT_F32 = 0, 1
 ADWIN_DEV_BAD_ID, ADWIN_DEV_NONFINITE = 1, 2
 ADWIN_MAX_CANDIDATES = 16
 ADWIN_EST_EXPECTED, ADWIN_EST_SAMPLED = 0, 1
+ADWIN_SCHEME_AUTO, ADWIN_SCHEME_SINGLE, ADWIN_SCHEME_TWO_SWEEP, ADWIN_SCHEME_TWO_SWEEP_REG = 0, 1, 2, 3
+ADWIN_LOGITS_AUTO, ADWIN_LOGITS_RESIDENT, ADWIN_LOGITS_STREAMING = 0, 1, 2
 
 
 class adwin_opd_problem(C.Structure):
@@ -48,6 +50,7 @@ class adwin_opd_problem(C.Structure):
         ("dW_prefix", C.c_void_p), ("dW_full", C.c_void_p),
         ("topk", C.c_int32), ("t_first_reject", C.c_void_p), ("t_logp_mean", C.c_void_p),
         ("cand_loss_share", C.c_void_p),
+        ("scheme", C.c_int32),
     ]
 
 
@@ -63,6 +66,7 @@ class adwin_opd_logits_problem(C.Structure):
         ("t_logp", C.c_void_p), ("t_entropy", C.c_void_p), ("t_rank", C.c_void_p),
         ("estimator", C.c_int32),
         ("topk", C.c_int32), ("t_first_reject", C.c_void_p), ("t_logp_mean", C.c_void_p),
+        ("scheme", C.c_int32),
     ]
 
 
@@ -217,7 +221,7 @@ class FusedCall:
     def __init__(self, h_s, h_t, W_s, W_t, ids, offsets, window, mode=ADWIN_PREFIX_ONLY,
                  reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0, dh_dtype=ADWIN_DT_F32,
                  want=DEFAULT_OUTPUTS, topk=0, device=None, allocate=True, candidates=None, estimator=ADWIN_EST_EXPECTED,
-                 cand_outputs=True):
+                 cand_outputs=True, scheme=ADWIN_SCHEME_AUTO):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.candidates = None if candidates is None else _host_i32(candidates)
         self.inputs = (h_s, h_t, W_s, W_t, ids)
@@ -234,6 +238,7 @@ class FusedCall:
         p.h_s, p.h_t, p.W_s, p.W_t, p.ids = _ptr(h_s), _ptr(h_t), _ptr(W_s), _ptr(W_t), _ptr(ids)
         p.mode, p.reduction, p.grad_scale, p.dh_dtype = mode, reduction, float(grad_scale), dh_dtype
         p.estimator = estimator
+        p.scheme = scheme
         p.topk = int(topk)
         K = 0 if self.candidates is None else int(self.candidates.shape[0])
         if K:
@@ -319,7 +324,7 @@ class LogitsCall:
 
     def __init__(self, z_s, z_t, ids, offsets, window, reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0,
                  want=("kl", "c", "dz", "loss_prefix", "batch", "n_out", "n_adm_out", "status_dev"),
-                 allocate=True, estimator=ADWIN_EST_EXPECTED, topk=0):
+                 allocate=True, estimator=ADWIN_EST_EXPECTED, topk=0, scheme=ADWIN_LOGITS_AUTO):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.inputs = (z_s, z_t, ids)
         B = int(self.window.shape[0])
@@ -332,6 +337,7 @@ class LogitsCall:
         p.z_s, p.z_t, p.ids = _ptr(z_s), _ptr(z_t), _ptr(ids)
         p.reduction, p.grad_scale = reduction, float(grad_scale)
         p.estimator = estimator
+        p.scheme = scheme
         p.topk = int(topk)
         self.p = p
         self.out = {}

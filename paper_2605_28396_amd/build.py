@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadwin_opd.so")
-SOURCES = ["host_plan.cpp", "reduce_kernels.hip", "logits_kernels.hip", "sweep_kernels.hip", "grad_kernels.hip", "fused_host.hip",
+SOURCES = ["host_plan.cpp", "hip_state.cpp", "reduce_kernels.hip", "logits_kernels.hip", "sweep_kernels.hip", "grad_kernels.hip", "fused_host.hip",
            "ceilings.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -22,8 +22,23 @@ struct FusedLayout {
   int strips, ksplit;
   int64_t slab_rows, Vp;
   size_t o_plan, o_row_idx, o_row_seq, o_part, o_lse2, o_mu, o_klr, o_rownorm, o_WsT, o_slab, o_g,
-      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_s, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, o_summ, o_cosp, total;
+      o_pp, o_pf, o_up, o_uf, o_seg, o_racc, o_uc, o_cacc, o_cS, o_cr, o_zy_s, o_zy_t, o_yid, o_dzT_p, o_dzT_f, o_hsT, o_summ, o_cosp,
+      o_lse_s, o_heavy_cnt, o_heavy_v, total;
 };
+
+// Which kernels a scheme selects for this shape: the direct-to-LDS logit kernel pipelines at
+// least two k-steps per head, so it needs both hidden sizes >= 128.  False: the scheme is not
+// available for the shape.
+static bool resolve_scheme(const adwin_opd_problem* p, bool* use_dma, bool* single) {
+  const bool dma_ok = p->H_s >= 2 * kBK && p->H_t >= 2 * kBK;
+  switch (p->scheme) {
+    case ADWIN_SCHEME_AUTO: *use_dma = dma_ok; *single = dma_ok; return true;
+    case ADWIN_SCHEME_SINGLE: *use_dma = true; *single = true; return dma_ok;
+    case ADWIN_SCHEME_TWO_SWEEP: *use_dma = dma_ok; *single = false; return true;
+    case ADWIN_SCHEME_TWO_SWEEP_REG: *use_dma = false; *single = false; return true;
+    default: *use_dma = false; *single = false; return false;
+  }
+}
 
 static int env_int(const char* name, int dflt) {
   const char* s = getenv(name);
@@ -51,9 +66,7 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   if (strips > vt_total) strips = vt_total;
   if (strips > kMaxStrips) strips = kMaxStrips;
   L.strips = strips;
-  // the direct-to-LDS logit kernel pipelines at least two k-steps per head
-  L.use_dma = !getenv("ADWIN_NO_DMA") && p->H_s >= 2 * kBK && p->H_t >= 2 * kBK;
-  L.single = L.use_dma && !getenv("ADWIN_TWO_SWEEP");
+  (void)resolve_scheme(p, &L.use_dma, &L.single);     // validity was checked with the problem
   int strips1 = env_int("ADWIN_STRIPS2", 32);
   if (strips1 > vt_total) strips1 = vt_total;
   if (strips1 > kMaxStrips) strips1 = kMaxStrips;
@@ -138,6 +151,9 @@ static FusedLayout fused_layout(const adwin_opd_problem* p, const HostPlan& hp) 
   L.o_cosp = take((p->dW_prefix && p->dW_full) ? sizeof(double) * 3 * kCosineBlocks : 0);
   L.o_summ = take((p->t_first_reject || p->t_logp_mean || p->cand_loss_share)
                       ? sizeof(double) * (size_t)p->B * kSummarySlots : 0);
+  L.o_lse_s = take(sizeof(float) * (size_t)n_pad);
+  L.o_heavy_cnt = take(sizeof(int32_t) * (size_t)n_pad);
+  L.o_heavy_v = take(need_g ? sizeof(int32_t) * (size_t)kHeavySlots * (size_t)n_pad : 0);
   L.total = o;
   return L;
 }
@@ -153,6 +169,10 @@ static int check_problem(const adwin_opd_problem* p) {
   if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
   if (p->dh_dtype != ADWIN_DT_BF16 && p->dh_dtype != ADWIN_DT_F32) return ADWIN_E_MODE;
   if (p->estimator != ADWIN_EST_EXPECTED && p->estimator != ADWIN_EST_SAMPLED) return ADWIN_E_MODE;
+  {
+    bool use_dma, single;
+    if (!resolve_scheme(p, &use_dma, &single)) return ADWIN_E_MODE;
+  }
   if (p->n_candidates < 0 || p->n_candidates > ADWIN_MAX_CANDIDATES) return ADWIN_E_SHAPE;
   if (p->candidates && p->n_candidates > 0) {
     if (p->mode != ADWIN_PREFIX_AND_FULL) return ADWIN_E_MODE;
@@ -262,8 +282,11 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     ADWIN_HIP_TRY(launch_fill_f32(p->c, p->T, 0.f, stream));
   }
 
+  HeavyList heavy;
+  heavy.cnt = (int32_t*)(ws + L.o_heavy_cnt); heavy.v = (int32_t*)(ws + L.o_heavy_v);
   if (hp.n_rows > 0) {
     ADWIN_HIP_TRY(launch_build_rows(pl, p->B, hp.n_rows, n_pad, stream));
+    ADWIN_HIP_TRY(launch_fill_u32((uint32_t*)heavy.cnt, n_pad, 0u, stream));
     const int vt_total = (int)(L.Vp / kTileVocab);
     const int n_tiles = (int)(n_pad / kTileTokens);
     // tile images of W_s^T for the gradient GEMM
@@ -299,15 +322,17 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     la.ref_s2 = (const float*)(ws + L.o_lse2); la.ref_t2 = (const float*)(ws + L.o_ref_t2);
     la.mu0 = (const float*)(ws + L.o_mu); la.e2_off = 0;
     la.mu0t = (L.single && !sampled && need_g) ? (float*)(ws + L.o_mu0t) : nullptr; la.mu0t_stride = L.slab_rows;
-    la.tg = env_int("ADWIN_TG", 4);
+    la.tg = env_int("ADWIN_TG", 4);      // tuning override
     la.Wt_img = (const char*)(ws + L.o_wt_img); la.Ws_img = (const char*)(ws + L.o_ws_img);
     la.ht_img = (const char*)(ws + L.o_ht_img); la.hs_img = (const char*)(ws + L.o_hs_img);
+    la.heavy = heavy;
     MergeArgs m;
     m.part = la.part; m.strips = L.strips; m.n_pad = n_pad; m.n_rows = hp.n_rows;
     m.row_idx = pl.row_idx;
     m.h_s = la.h_s; m.h_t = la.h_t; m.W_s = la.W_s; m.W_t = la.W_t;
     m.H_s = p->H_s; m.H_t = p->H_t; m.V = p->V; m.ids = p->ids;
     m.lse2 = (float*)(ws + L.o_lse2); m.mu = (float*)(ws + L.o_mu); m.klr = klr;
+    m.lse_s = (float*)(ws + L.o_lse_s); m.alive = (float*)(ws + L.o_invz);
     m.kl = p->kl; m.c = p->c; m.status = p->status_dev;
     m.diag = diag ? 1 : 0; m.t_logp = p->t_logp; m.t_entropy = p->t_entropy; m.t_rank = p->t_rank;
     m.cr = sampled ? (float*)(ws + L.o_cr) : nullptr;
@@ -372,6 +397,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
         ca.dzT_f = p->dW_full ? (uint4*)(ws + L.o_dzT_f) : nullptr;
         ca.nkr = (int)(rows / kBK); ca.pl = pl; ca.n_rows = hp.n_rows; ca.grad_scale = p->grad_scale;
         ca.cr = (const float*)(ws + L.o_cr); ca.yid = (const int32_t*)(ws + L.o_yid);
+        ca.heavy = heavy;
         if (sampled) {       // contract the E2 factor; c_t and W_s[y_t] enter in finalize_kernel
           ga.slab = la.slab + la.e2_off;
           ga.half_tiles = 0;                       // output rows in the second half of g
@@ -398,6 +424,7 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
           ha.h_s = (const uint16_t*)p->h_s; ha.row_idx = pl.row_idx;
           ha.row0 = r0; ha.H = p->H_s; ha.nkr = wa.nk_total;
           ha.img = (uint16_t*)(ws + L.o_hsT);
+          ha.alive = (const float*)(ws + L.o_invz);
           ADWIN_HIP_TRY(launch_hst_image(ha, h_tiles, stream));
           for (int which = 0; which < 2; ++which) {
             float* out = which == 0 ? p->dW_prefix : p->dW_full;
@@ -446,7 +473,13 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
     f.pl = pl; f.B = p->B; f.T = p->T; f.probe = probe;
     f.g = gws; f.ksplit = L.ksplit; f.n_pad = n_pad; f.H = p->H_s;
     f.g_rows = L.single ? 2 * n_pad : n_pad;
-    f.inv_z = L.single ? (const float*)(ws + L.o_invz) : nullptr;
+    f.inv_z = (const float*)(ws + L.o_invz);
+    // the fp32 part of g; the sampled estimator contracts E2 as stored and lists nothing
+    f.heavy = heavy;
+    if (p->estimator == ADWIN_EST_SAMPLED) f.heavy.cnt = nullptr;
+    f.lse_s = (const float*)(ws + L.o_lse_s);
+    f.mu = (const float*)(ws + (L.single ? L.o_delta : L.o_mu));
+    f.h_s = (const __bf16*)p->h_s; f.h_t = (const __bf16*)p->h_t; f.W_t = (const __bf16*)p->W_t; f.H_t = p->H_t;
     f.cr = (L.single && p->estimator == ADWIN_EST_SAMPLED) ? (const float*)(ws + L.o_cr) : nullptr;
     f.ids = p->ids; f.W_s = (const __bf16*)p->W_s; f.V = p->V;
     f.grad_scale = p->grad_scale; f.dh_bf16 = p->dh_dtype == ADWIN_DT_BF16;

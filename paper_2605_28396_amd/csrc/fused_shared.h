@@ -49,6 +49,44 @@ constexpr int kImgBytesSlab = kSlabBlock * 2;   // 32 KiB
 constexpr int kImgElems = kGradTile * kBK;            // bf16 elements per block
 constexpr int kImgBytes = kImgElems * 2;              // 32 KiB
 
+// Heavy entries.  The logit gradient dz = p_s ((z_s - z_t) - mu) is contracted with W_s as
+// bf16.  On a peaked row a handful of entries carry the whole gradient row and their rounding
+// (2^-9 relative each) does not average out, so every entry with p_s >= kHeavyP is taken out
+// of the bf16 operand (stored as an exact zero) and listed per computed row instead; the
+// scale-and-scatter kernel recomputes those few logits as fp32 dot products and adds
+// dz W_s[v] in fp32.  Probabilities sum to 1, so a row has at most 1 / kHeavyP such entries;
+// a flat row (the random-initialisation regime) has none.
+constexpr float kHeavyP = 1.f / 32.f;
+constexpr int kHeavySlots = 32;
+struct HeavyList {
+  int32_t* cnt;    // [n_pad] entries listed per computed row (zeroed at the start of a call)
+  int32_t* v;      // [n_pad][kHeavySlots] vocabulary indices, in no particular order
+};
+
+// Lists entry v of computed row r; false when the row's list is full (the entry then stays in
+// the bf16 operand).
+__device__ __forceinline__ bool heavy_push(const HeavyList& hl, int64_t r, int v) {
+  const int slot = atomicAdd(hl.cnt + r, 1);
+  if (slot >= kHeavySlots) return false;
+  hl.v[r * kHeavySlots + slot] = v;
+  return true;
+}
+
+// x . y over H bf16 entries (H a multiple of 8), all 64 lanes of the wave; every lane gets the sum.
+__device__ __forceinline__ float dot_bf16_row(const __bf16* x, const __bf16* y, int H, int lane) {
+  float acc = 0.f;
+  const uint4* px = (const uint4*)x;
+  const uint4* py = (const uint4*)y;
+  for (int q = lane; q < (H >> 3); q += 64) {
+    const uint4 a = px[q], b = py[q];
+    acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
+    acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
+    acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
+    acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+  }
+  return wave_sum(acc);
+}
+
 // ---------------------------------------------------------------------------------------
 // Argument blocks
 // ---------------------------------------------------------------------------------------
@@ -76,6 +114,7 @@ struct LogitPassArgs {
   const float* zy_t; const int32_t* yid;
   // direct-to-LDS kernel: tile images of the four operands (see row_image_kernel)
   const char* Wt_img; const char* Ws_img; const char* ht_img; const char* hs_img;
+  HeavyList heavy;             // second sweep of the two-sweep scheme: entries taken out of dz
 };
 
 // Modes of the direct-to-LDS logit kernel.
@@ -102,6 +141,8 @@ struct MergeArgs {
   int H_s, H_t, V;
   const int32_t* ids;
   float* lse2; float* mu; float* klr;
+  float* lse_s;                // [n_pad] student log-sum-exp in nats (for the heavy entries)
+  float* alive;                // [n_pad] two-sweep merge: 1, or 0 for an excluded (non-finite) row
   float* kl; float* c;
   uint32_t* status;
   // teacher-side diagnostics (single-sweep merge only); part planes 3 and 4 hold
@@ -145,6 +186,7 @@ struct CombineArgs {
   // Eq. 4's logit gradient c_t (e_{y_t} - p_s) = c_t (1[v = y_t] - E2 / Z_s), the one-hot term
   // entering before the rounding.  c_t and y_t per computed row (y_t = -1: none).
   const float* cr; const int32_t* yid;
+  HeavyList heavy;             // entries with p_s >= kHeavyP leave the bf16 operand (expected estimator)
 };
 
 // Transposed h_s images of one slab (see hst_image_kernel).
@@ -153,6 +195,7 @@ struct HstImageArgs {
   int64_t row0;
   int H, nkr;
   uint16_t* img;
+  const float* alive;     // per computed row; 0: excluded row, its column is written as zeros
 };
 
 // Gradient GEMM over tile images (see grad_gemm_kernel).
@@ -174,7 +217,11 @@ struct FinalizeArgs {
   DevicePlan pl; int B; int64_t T; int probe;
   float* g; int ksplit; int64_t n_pad; int H;
   int64_t g_rows;                          // rows per k-split plane of g
-  const float* inv_z;                      // 1 / Z_s per computed row (sampled estimator)
+  const float* inv_z;                      // per computed row: 1 / Z_s (single sweep) or 1 (two sweeps);
+                                           // 0 marks an excluded (non-finite) row: zeros everywhere
+  // heavy entries: fp32 part of g, from the row's lse_s and mu and fresh dot products
+  HeavyList heavy; const float* lse_s; const float* mu;
+  const __bf16* h_s; const __bf16* h_t; const __bf16* W_t; int H_t;
   // sampled estimator (Eq. 4): g = c_t (W_s[y_t] - G2 inv_z), G2 = E2 W_s in the second half of
   // g; cr NULL: g is the contraction of the logit gradient itself, in the first half
   const float* cr; const int32_t* ids; const __bf16* W_s; int V;

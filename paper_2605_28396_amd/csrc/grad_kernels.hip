@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   if (TR) {
     const int64_t r = rbase + threadIdx.x;
     float wp = 0.f, wf = 0.f;
-    if (r < a.n_rows) {
+    if (r < a.n_rows && a.inv_z[r] != 0.f) {     // excluded rows carry weight 0
       const int i = a.pl.row_seq[r];
       wf = a.grad_scale * a.pl.alpha_f[i];
       wp = (r - a.pl.comp_off[i]) < a.pl.n[i] ? a.grad_scale * a.pl.alpha_p[i] : 0.f;
@@ -98,21 +98,40 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
       const int e_y = a.yid[r] - v0;
 #pragma unroll
       for (int e = 0; e < 8; ++e) d[e] += (e == e_y) ? c : 0.f;
+      if (TR) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dz[i][e] = d[e];
+      }
     } else {
       const float dl = a.mu[r] - a.mu0t[(int64_t)(kt >> 1) * a.mu0t_stride + rt * kTileTokens + (q >> 3)];
       const uint4 x = p1[q];
-      d[0] = (bf16_lo(x.x) - dl) * (bf16_lo(y.x) * iz); d[1] = (bf16_hi(x.x) - dl) * (bf16_hi(y.x) * iz);
-      d[2] = (bf16_lo(x.y) - dl) * (bf16_lo(y.y) * iz); d[3] = (bf16_hi(x.y) - dl) * (bf16_hi(y.y) * iz);
-      d[4] = (bf16_lo(x.z) - dl) * (bf16_lo(y.z) * iz); d[5] = (bf16_hi(x.z) - dl) * (bf16_hi(y.z) * iz);
-      d[6] = (bf16_lo(x.w) - dl) * (bf16_lo(y.w) * iz); d[7] = (bf16_hi(x.w) - dl) * (bf16_hi(y.w) * iz);
+      float pv[8], xv[8];                      // p_s and the stored D of the vector's 8 entries
+      pv[0] = bf16_lo(y.x) * iz; pv[1] = bf16_hi(y.x) * iz; pv[2] = bf16_lo(y.y) * iz; pv[3] = bf16_hi(y.y) * iz;
+      pv[4] = bf16_lo(y.z) * iz; pv[5] = bf16_hi(y.z) * iz; pv[6] = bf16_lo(y.w) * iz; pv[7] = bf16_hi(y.w) * iz;
+      xv[0] = bf16_lo(x.x); xv[1] = bf16_hi(x.x); xv[2] = bf16_lo(x.y); xv[3] = bf16_hi(x.y);
+      xv[4] = bf16_lo(x.z); xv[5] = bf16_hi(x.z); xv[6] = bf16_lo(x.w); xv[7] = bf16_hi(x.w);
+      const bool dead = iz == 0.f;             // excluded row: its factors may hold inf / NaN
+      float pmax = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        d[e] = dead ? 0.f : (xv[e] - dl) * pv[e];
+        pmax = fmaxf(pmax, pv[e]);
+      }
+      if (TR) {                                // the head-weight operand keeps every entry in bf16
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dz[i][e] = d[e];
+      }
+      if (__builtin_expect(pmax >= kHeavyP && !dead, 0)) {
+        // entries of this vector: 64 kt + 8 (logical chunk) + e
+        const int rl = q >> 3, v0 = kt * kBK + (((q & 7) ^ ((rl >> 1) & 7)) << 3);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (pv[e] >= kHeavyP && heavy_push(a.heavy, r, v0 + e)) d[e] = 0.f;
+      }
       uint4 o;
       o.x = pack_bf16(d[0], d[1]); o.y = pack_bf16(d[2], d[3]);
       o.z = pack_bf16(d[4], d[5]); o.w = pack_bf16(d[6], d[7]);
       p1[q] = o;
-    }
-    if (TR) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) dz[i][e] = d[e];
     }
   }
   if (TR) {
@@ -167,7 +186,9 @@ __global__ __launch_bounds__(256) void hst_image_kernel(HstImageArgs a) {
   for (int i = 0; i < kBK; ++i) {
     const int64_t r = a.row0 + (int64_t)kr * kBK + i;
     const int h = ht * kGradTile + tid;
-    tile[i][tid] = h < a.H ? a.h_s[(int64_t)a.row_idx[r] * a.H + h] : (uint16_t)0;
+    // an excluded row carries weight 0 in the other operand; its own entries (possibly inf or
+    // NaN) must not meet that 0 in the product
+    tile[i][tid] = (h < a.H && a.alive[r] != 0.f) ? a.h_s[(int64_t)a.row_idx[r] * a.H + h] : (uint16_t)0;
   }
   __syncthreads();
   uint16_t* blk = a.img + ((int64_t)ht * a.nkr + kr) * kImgElems;
@@ -413,6 +434,17 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a) {
     return;
   }
   const int64_t r = a.pl.comp_off[i] + j;
+  if (a.inv_z[r] == 0.f) {
+    // excluded row (no finite statistics): zeros in both gradients, in g (the pooled sums
+    // read it) and in the row norm
+    for (int h = lane * 4; h < a.H; h += 256) {
+      *(float4*)(a.g + r * a.H + h) = zero;
+      store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, zero);
+      if (a.probe) store_dh(a.dh_full, a.dh_bf16, t, a.H, h, zero);
+    }
+    if (lane == 0) a.rownorm[r] = 0.f;
+    return;
+  }
   const float sp = admitted ? a.grad_scale * a.pl.alpha_p[i] : 0.f;
   const float sf = a.grad_scale * a.pl.alpha_f[i];
   float nrm = 0.f;
@@ -444,19 +476,59 @@ __global__ __launch_bounds__(256) void finalize_kernel(FinalizeArgs a) {
     if (lane == 0) a.rownorm[r] = nrm;
     return;
   }
-  for (int h = lane * 4; h < a.H; h += 256) {
-    float4 g = *(const float4*)(a.g + r * a.H + h);
-    for (int s = 1; s < a.ksplit; ++s) {
-      const float4 q = *(const float4*)(a.g + ((int64_t)s * a.g_rows + r) * a.H + h);
-      g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w;
+  // Heavy entries of the row (those the bf16 operand holds as zeros): lane k ends up with the
+  // k-th smallest listed vocabulary index hv and that entry's logit gradient hd, taken in fp32
+  // from fresh dot products.  The list is filled in no particular order; adding the entries in
+  // index order keeps the result the same from call to call.
+  int nh = a.heavy.cnt ? a.heavy.cnt[r] : 0;
+  nh = nh < kHeavySlots ? nh : kHeavySlots;
+  int hv = 0;
+  float hd = 0.f;
+  if (nh > 0) {
+    const int mine = lane < nh ? a.heavy.v[r * kHeavySlots + lane] : 0x7fffffff;
+    int rank = 0;                                  // indices of one row are distinct
+    for (int k = 0; k < nh; ++k) rank += (__shfl(mine, k, 64) < mine) ? 1 : 0;
+    for (int k = 0; k < nh; ++k) {
+      const int vk = __shfl(mine, k, 64), rk = __shfl(rank, k, 64);
+      if (rk == lane) hv = vk;
     }
-    if (a.ksplit > 1) *(float4*)(a.g + r * a.H + h) = g;
-    nrm = fmaf(g.x, g.x, fmaf(g.y, g.y, fmaf(g.z, g.z, fmaf(g.w, g.w, nrm))));
-    const float4 p = {g.x * sp, g.y * sp, g.z * sp, g.w * sp};
-    store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, p);
-    if (a.probe) {
-      const float4 f = {g.x * sf, g.y * sf, g.z * sf, g.w * sf};
-      store_dh(a.dh_full, a.dh_bf16, t, a.H, h, f);
+    const float lse = a.lse_s[r], mu = a.mu[r];
+    for (int k = 0; k < nh; ++k) {
+      const int v = __shfl(hv, k, 64);
+      const float zs = dot_bf16_row(a.h_s + t * a.H, a.W_s + (int64_t)v * a.H, a.H, lane);
+      const float zt = dot_bf16_row(a.h_t + t * a.H_t, a.W_t + (int64_t)v * a.H_t, a.H_t, lane);
+      if (lane == k) hd = __expf(zs - lse) * ((zs - zt) - mu);
+    }
+  }
+  for (int h0 = 0; h0 < a.H; h0 += 256) {          // every lane takes part in the shuffles
+    const int h = h0 + lane * 4;
+    const bool act = h < a.H;
+    float4 g = zero;
+    if (act) {
+      g = *(const float4*)(a.g + r * a.H + h);
+      for (int s = 1; s < a.ksplit; ++s) {
+        const float4 q = *(const float4*)(a.g + ((int64_t)s * a.g_rows + r) * a.H + h);
+        g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w;
+      }
+    }
+    for (int k = 0; k < nh; ++k) {
+      const int v = __shfl(hv, k, 64);
+      const float dzv = __shfl(hd, k, 64);
+      if (act) {
+        const uint2 w = *(const uint2*)(a.W_s + (int64_t)v * a.H + h);
+        g.x = fmaf(dzv, bf16_lo(w.x), g.x); g.y = fmaf(dzv, bf16_hi(w.x), g.y);
+        g.z = fmaf(dzv, bf16_lo(w.y), g.z); g.w = fmaf(dzv, bf16_hi(w.y), g.w);
+      }
+    }
+    if (act) {
+      if (a.ksplit > 1 || nh > 0) *(float4*)(a.g + r * a.H + h) = g;
+      nrm = fmaf(g.x, g.x, fmaf(g.y, g.y, fmaf(g.z, g.z, fmaf(g.w, g.w, nrm))));
+      const float4 p = {g.x * sp, g.y * sp, g.z * sp, g.w * sp};
+      store_dh(a.dh_prefix, a.dh_bf16, t, a.H, h, p);
+      if (a.probe) {
+        const float4 f = {g.x * sf, g.y * sf, g.z * sf, g.w * sf};
+        store_dh(a.dh_full, a.dh_bf16, t, a.H, h, f);
+      }
     }
   }
   nrm = wave_sum(nrm);

@@ -1,31 +1,13 @@
-// Host-side integer bookkeeping (Sec. 4.1: rollouts truncated at the window), status
-// strings and the version.  Nothing here touches the GPU.
-#include <atomic>
+// Host-side integer bookkeeping (Sec. 4.1: rollouts truncated at the window), the scheduler
+// of Sec. 4.2, status strings and the version.  Nothing here touches the GPU or includes a HIP
+// header: this file also builds with the host compiler alone (the sanitizer test does that).
 #include <cmath>
-#include <cstdio>
 #include <climits>
 #include <cstring>
 
-#include "common.h"
+#include "host_plan.h"
 
 namespace adwin {
-
-static thread_local char g_hip_error[256] = "";
-
-const char* last_hip_error_text() { return g_hip_error; }
-
-void set_last_hip_error(hipError_t e, const char* where) {
-  snprintf(g_hip_error, sizeof(g_hip_error), "HIP error %d (%s) at %s", (int)e,
-           hipGetErrorString(e), where);
-}
-
-bool first_use_on_device(int slot) {
-  static std::atomic<unsigned long long> seen[4];
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63 || slot < 0 || slot > 3) return true;
-  const unsigned long long bit = 1ull << dev;
-  return (seen[slot].fetch_or(bit) & bit) == 0;
-}
 
 int validate_ragged(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window) {
   if (!offsets || !window) return ADWIN_E_NULL;
@@ -37,6 +19,61 @@ int validate_ragged(int64_t T, int32_t B, const int64_t* offsets, const int32_t*
   for (int32_t i = 0; i < B; ++i)
     if (window[i] < 0) return ADWIN_E_WINDOW;
   return ADWIN_OK;
+}
+
+HostPlan make_host_plan(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
+                        int probe, int reduction, std::vector<unsigned char>* blob) {
+  HostPlan hp;
+  hp.T = T;
+  hp.B = B;
+  PlanBlobLayout L(B);
+  unsigned char* base = nullptr;
+  if (blob) {
+    blob->assign(L.bytes, 0);
+    base = blob->data();
+  }
+  int64_t n_adm = 0;
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t len = offsets[i + 1] - offsets[i];
+    n_adm += window[i] < len ? (int64_t)window[i] : len;
+  }
+  int64_t comp = 0;
+  int64_t chunks = 0;
+  for (int32_t i = 0; i < B; ++i) {
+    const int64_t len = offsets[i + 1] - offsets[i];
+    const int64_t ni = window[i] < len ? (int64_t)window[i] : len;
+    const int64_t hi = probe ? len : ni;
+    if (base) {
+      ((int64_t*)(base + L.o_offsets))[i] = offsets[i];
+      ((int64_t*)(base + L.o_comp_off))[i] = comp;
+      ((int32_t*)(base + L.o_n))[i] = (int32_t)ni;
+      ((int32_t*)(base + L.o_chunk_off))[i] = (int32_t)chunks;
+      double ap = 0.0, af = 0.0;
+      if (reduction == ADWIN_RED_SEQ_MEAN) {
+        ap = ni > 0 ? 1.0 / ((double)B * (double)ni) : 0.0;
+        af = len > 0 ? 1.0 / ((double)B * (double)len) : 0.0;
+      } else if (reduction == ADWIN_RED_SUM) {
+        ap = af = 1.0;
+      } else {
+        ap = n_adm > 0 ? 1.0 / (double)n_adm : 0.0;
+        af = T > 0 ? 1.0 / (double)T : 0.0;
+      }
+      ((float*)(base + L.o_alpha_p))[i] = (float)ap;
+      ((float*)(base + L.o_alpha_f))[i] = (float)af;
+    }
+    comp += hi;
+    chunks += (hi + kChunkRows - 1) / kChunkRows;
+  }
+  if (base) {
+    ((int64_t*)(base + L.o_offsets))[B] = offsets[B];
+    ((int64_t*)(base + L.o_comp_off))[B] = comp;
+    ((int32_t*)(base + L.o_chunk_off))[B] = (int32_t)chunks;
+  }
+  hp.n_adm = n_adm;
+  hp.n_rows = comp;
+  hp.n_pad = (int64_t)align_up((size_t)comp, kTileTokens);
+  hp.n_chunks = chunks;
+  return hp;
 }
 
 }  // namespace adwin
@@ -56,7 +93,9 @@ const char* adwin_opd_strerror(int status) {
     case ADWIN_E_WINDOW: return "window lengths must be >= 0";
     case ADWIN_E_ALIGN: return "device pointers must be 16-byte aligned";
     case ADWIN_E_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
-    case ADWIN_E_MODE: return "unknown mode, reduction or dh_dtype, or struct_bytes mismatch";
+    case ADWIN_E_MODE:
+      return "unknown mode, reduction, dh_dtype, estimator or scheme, struct_bytes mismatch, or an "
+             "option the selected scheme does not offer";
     case ADWIN_E_HIP: {
       const char* t = adwin::last_hip_error_text();
       return t[0] ? t : "a HIP call failed";

@@ -49,7 +49,7 @@ __device__ __forceinline__ void unpack8(const uint4& q, float (&f)[8]) {
 template <bool DIAG>
 __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
   __shared__ float sh[7][kRowThreads / 64];
-  __shared__ float bc[4];
+  __shared__ float bc[5];
   const int64_t t = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int nvec = a.V >> 3;
@@ -148,10 +148,15 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
     }
     const float lse_s = m + logf(Z), lse_t = m2 + logf(Z2);
     const float mu = Aa / Z;                       // E_{p_s}[z_s - z_t]
-    const float kl = kl_from_sums(mu, m - m2, Z, Z2);
+    float kl = kl_from_sums(mu, m - m2, Z, Z2);
+    float ent = DIAG ? lse_t - B2 / Z2 : 0.f;
+    // a row without finite statistics is excluded: zeros in every output
+    const bool dead = !(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f) ||
+                      !(fabsf(mu) < 3.0e38f) || !(fabsf(ent) < 3.0e38f);
     float c = 0.f;
-    uint32_t flag = 0;
-    if (a.ids) {
+    uint32_t flag = dead ? ADWIN_DEV_NONFINITE : 0u;
+    if (dead) { kl = 0.f; ent = 0.f; }
+    if (a.ids && !dead) {
       const int y = a.ids[t];
       if (y >= 0 && y < a.V) {
         const uint16_t* ps = (const uint16_t*)zs;
@@ -163,24 +168,28 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
         flag |= ADWIN_DEV_BAD_ID;
       }
     }
-    if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f))
-      flag |= ADWIN_DEV_NONFINITE;
     if (flag && a.status) atomicOr(a.status, flag);
     if (a.kl) a.kl[t] = kl;
     if (a.c) a.c[t] = c;
     if (DIAG) {
-      if (a.t_entropy) a.t_entropy[t] = lse_t - B2 / Z2;
-      if (a.t_logp) a.t_logp[t] = y >= 0 ? zy_rank - lse_t : 0.f;
-      if (a.t_rank) a.t_rank[t] = y >= 0 ? rank + 1 : 0;
+      if (a.t_entropy) a.t_entropy[t] = ent;
+      if (a.t_logp) a.t_logp[t] = (y >= 0 && !dead) ? zy_rank - lse_t : 0.f;
+      if (a.t_rank) a.t_rank[t] = (y >= 0 && !dead) ? rank + 1 : 0;
     }
     a.klr[a.pl.comp_off[i] + j] = kl;
     bc[0] = lse_s * kLog2e;
     bc[1] = mu;
     bc[2] = c;
     bc[3] = lse_s;
+    bc[4] = dead ? 1.f : 0.f;
   }
   __syncthreads();
   if (!dzr) return;
+  if (bc[4] != 0.f) {
+    const uint4 z = {0u, 0u, 0u, 0u};
+    for (int q = tid; q < nvec; q += kRowThreads) nt_store16(dzr + q, z);
+    return;
+  }
   // ---- sweep 2: dz = scale * p_s * ((z_s - z_t) - mu), or scale * c_t * (e_y - p_s) ---
   const float lse2 = bc[0];
   const float scale = a.grad_scale * a.pl.alpha_p[i];
@@ -282,7 +291,7 @@ __device__ __forceinline__ uint4 dz_vector(const uint4& qs, const uint4& qt, flo
 __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(LogitsArgs a) {
   extern __shared__ __align__(16) char lds_raw[];
   uint4* lds_t = (uint4*)lds_raw;
-  float* sh = (float*)(lds_raw + kResTLds * kResThreads * 16);   // [5][4] + broadcast [2]
+  float* sh = (float*)(lds_raw + kResTLds * kResThreads * 16);   // [5][4] + broadcast [5]
   const int64_t t = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int nvec = a.V >> 3;
@@ -361,10 +370,14 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
     }
     const float lse_s = m + logf(Z), lse_t = m2 + logf(Z2);
     const float mu = Aa / Z;                       // E_{p_s}[z_s - z_t]
-    const float kl = kl_from_sums(mu, m - m2, Z, Z2);
+    float kl = kl_from_sums(mu, m - m2, Z, Z2);
+    // a row without finite statistics is excluded: zeros in every output
+    const bool dead = !(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f) ||
+                      !(fabsf(mu) < 3.0e38f);
     float c = 0.f;
-    uint32_t flag = 0;
-    if (a.ids) {
+    uint32_t flag = dead ? ADWIN_DEV_NONFINITE : 0u;
+    if (dead) kl = 0.f;
+    if (a.ids && !dead) {
       const int y = a.ids[t];
       if (y >= 0 && y < a.V) {
         const float zy_s = __uint_as_float((uint32_t)((const uint16_t*)zs)[y] << 16);
@@ -374,8 +387,6 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
         flag |= ADWIN_DEV_BAD_ID;
       }
     }
-    if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f))
-      flag |= ADWIN_DEV_NONFINITE;
     if (flag && a.status) atomicOr(a.status, flag);
     if (a.kl) a.kl[t] = kl;
     if (a.c) a.c[t] = c;
@@ -384,9 +395,15 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
     sh[21] = mu;
     sh[22] = c;
     sh[23] = lse_s;
+    sh[24] = dead ? 1.f : 0.f;
   }
   __syncthreads();
   if (!dzr) return;
+  if (sh[24] != 0.f) {
+    const uint4 z = {0u, 0u, 0u, 0u};
+    for (int q = tid; q < nvec; q += kResThreads) nt_store16(dzr + q, z);
+    return;
+  }
   // ---- sweep 2: dz from the resident copy ----------------------------------------------
   // expected: scale p_s ((z_s - z_t) - mu); sampled: -k p_s with k = scale c_t (the one-hot
   // term follows); |scale| resp. |k| is folded into the exponent, the sign into the factor
@@ -444,6 +461,7 @@ static int check_logits_problem(const adwin_opd_logits_problem* p) {
   if (p->reduction < ADWIN_RED_SEQ_MEAN || p->reduction > ADWIN_RED_TOKEN_MEAN) return ADWIN_E_MODE;
   if (p->estimator != ADWIN_EST_EXPECTED && p->estimator != ADWIN_EST_SAMPLED) return ADWIN_E_MODE;
   if (p->estimator == ADWIN_EST_SAMPLED && !p->ids) return ADWIN_E_NULL;
+  if (p->scheme < ADWIN_LOGITS_AUTO || p->scheme > ADWIN_LOGITS_STREAMING) return ADWIN_E_MODE;
   if (p->t_first_reject && !p->t_rank) return ADWIN_E_NULL;
   if (p->t_first_reject && p->topk <= 0) return ADWIN_E_SHAPE;
   if (p->t_logp_mean && !p->t_logp) return ADWIN_E_NULL;
@@ -492,7 +510,7 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
     a.t_logp = p->t_logp; a.t_entropy = p->t_entropy; a.t_rank = p->t_rank;
     a.sampled = p->estimator == ADWIN_EST_SAMPLED;
     PhaseScope scope(timer, ADWIN_PHASE_STATS);
-    const bool streaming = getenv("ADWIN_LOGITS_STREAMING") != nullptr;
+    const bool streaming = p->scheme == ADWIN_LOGITS_STREAMING;
     if (p->t_logp || p->t_entropy || p->t_rank) {
       // the diagnostics ride on the streaming kernel (the row-resident one has no register to spare)
       logits_row_kernel<true><<<(unsigned)p->T, kRowThreads, 0, stream>>>(a);

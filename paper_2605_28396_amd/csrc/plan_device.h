@@ -7,27 +7,6 @@
 
 namespace adwin {
 
-// Byte offsets of the plan arrays inside one contiguous upload, a function of B only.
-struct PlanBlobLayout {
-  size_t o_offsets, o_comp_off, o_n, o_chunk_off, o_alpha_p, o_alpha_f, bytes;
-  explicit PlanBlobLayout(int32_t B) {
-    size_t o = 0;
-    o_offsets = o;   o = align_up(o + sizeof(int64_t) * (size_t)(B + 1), 16);
-    o_comp_off = o;  o = align_up(o + sizeof(int64_t) * (size_t)(B + 1), 16);
-    o_n = o;         o = align_up(o + sizeof(int32_t) * (size_t)B, 16);
-    o_chunk_off = o; o = align_up(o + sizeof(int32_t) * (size_t)(B + 1), 16);
-    o_alpha_p = o;   o = align_up(o + sizeof(float) * (size_t)B, 16);
-    o_alpha_f = o;   o = align_up(o + sizeof(float) * (size_t)B, 16);
-    bytes = align_up(o, 256);
-  }
-};
-
-// Integer bookkeeping of Sec. 4.1 (n_i, first computed row and first reduction chunk of
-// each rollout) and the per-rollout weights alpha^p_i, alpha^f_i of the chosen
-// reduction.  `blob` may be NULL when only the counts are wanted.
-HostPlan make_host_plan(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
-                        int probe, int reduction, std::vector<unsigned char>* blob);
-
 DevicePlan device_plan_at(unsigned char* ws_plan, int32_t B, int32_t* row_idx, int32_t* row_seq);
 
 // large dynamic LDS of the row-resident logits kernel, once per device (logits_kernels.hip)

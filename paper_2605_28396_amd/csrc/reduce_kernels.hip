@@ -9,64 +9,6 @@
 
 namespace adwin {
 
-// ---------------------------------------------------------------------------------------
-// host plan
-// ---------------------------------------------------------------------------------------
-HostPlan make_host_plan(int64_t T, int32_t B, const int64_t* offsets, const int32_t* window,
-                        int probe, int reduction, std::vector<unsigned char>* blob) {
-  HostPlan hp;
-  hp.T = T;
-  hp.B = B;
-  PlanBlobLayout L(B);
-  unsigned char* base = nullptr;
-  if (blob) {
-    blob->assign(L.bytes, 0);
-    base = blob->data();
-  }
-  int64_t n_adm = 0;
-  for (int32_t i = 0; i < B; ++i) {
-    const int64_t len = offsets[i + 1] - offsets[i];
-    n_adm += window[i] < len ? (int64_t)window[i] : len;
-  }
-  int64_t comp = 0;
-  int64_t chunks = 0;
-  for (int32_t i = 0; i < B; ++i) {
-    const int64_t len = offsets[i + 1] - offsets[i];
-    const int64_t ni = window[i] < len ? (int64_t)window[i] : len;
-    const int64_t hi = probe ? len : ni;
-    if (base) {
-      ((int64_t*)(base + L.o_offsets))[i] = offsets[i];
-      ((int64_t*)(base + L.o_comp_off))[i] = comp;
-      ((int32_t*)(base + L.o_n))[i] = (int32_t)ni;
-      ((int32_t*)(base + L.o_chunk_off))[i] = (int32_t)chunks;
-      double ap = 0.0, af = 0.0;
-      if (reduction == ADWIN_RED_SEQ_MEAN) {
-        ap = ni > 0 ? 1.0 / ((double)B * (double)ni) : 0.0;
-        af = len > 0 ? 1.0 / ((double)B * (double)len) : 0.0;
-      } else if (reduction == ADWIN_RED_SUM) {
-        ap = af = 1.0;
-      } else {
-        ap = n_adm > 0 ? 1.0 / (double)n_adm : 0.0;
-        af = T > 0 ? 1.0 / (double)T : 0.0;
-      }
-      ((float*)(base + L.o_alpha_p))[i] = (float)ap;
-      ((float*)(base + L.o_alpha_f))[i] = (float)af;
-    }
-    comp += hi;
-    chunks += (hi + kChunkRows - 1) / kChunkRows;
-  }
-  if (base) {
-    ((int64_t*)(base + L.o_offsets))[B] = offsets[B];
-    ((int64_t*)(base + L.o_comp_off))[B] = comp;
-    ((int32_t*)(base + L.o_chunk_off))[B] = (int32_t)chunks;
-  }
-  hp.n_adm = n_adm;
-  hp.n_rows = comp;
-  hp.n_pad = (int64_t)align_up((size_t)comp, kTileTokens);
-  hp.n_chunks = chunks;
-  return hp;
-}
-
 DevicePlan device_plan_at(unsigned char* ws_plan, int32_t B, int32_t* row_idx, int32_t* row_seq) {
   PlanBlobLayout L(B);
   DevicePlan d;

@@ -147,9 +147,11 @@ __device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f
 }
 
 // dz = p_s ((z_s - z_t) - mu), rounded to bf16, into rows wrow + fn*32 + lane%32 of the tile.
+// Entries with p_s >= kHeavyP are listed for computed row crow + fn*32 + lane%32 and stored as 0.
 __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                             const float (&lse2)[2], const float (&mu)[2], __bf16* blk,
-                                            int wrow, int v0, int V, bool tail, int lane) {
+                                            int wrow, int v0, int V, bool tail, int lane,
+                                            const HeavyList& heavy, int64_t crow) {
   const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
@@ -159,10 +161,15 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         float d[4];
+        const bool in = !tail || vlane + fm * 32 + 8 * q < V;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
-          d[e] = fast_exp2(fmaf(s, kLog2e, -lse2[fn])) * ((s - t) - mu[fn]);
+          const float p = fast_exp2(fmaf(s, kLog2e, -lse2[fn]));
+          d[e] = p * ((s - t) - mu[fn]);
+          if (__builtin_expect(p >= kHeavyP && in, 0)) {
+            if (heavy_push(heavy, crow + fn * 32 + (lane & 31), vlane + fm * 32 + 8 * q + e)) d[e] = 0.f;
+          }
         }
         if (tail && vlane + fm * 32 + 8 * q >= V) { d[0] = d[1] = d[2] = d[3] = 0.f; }
         uint2 o;
@@ -368,7 +375,7 @@ __global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
     const bool tail = v0 + kTileVocab > a.V;
     if (!PASS2) stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
     else dz_epilogue(zs, zt, lse2, mu, a.slab + ((int64_t)tt_local * (a.Vp / kBK) + 2 * vt) * kSlabBlock,
-                     wave * 64, v0, a.V, tail, lane);
+                     wave * 64, v0, a.V, tail, lane, a.heavy, (int64_t)tt * kTileTokens + wave * 64);
   }
   if (!PASS2)
     write_partials(st, a.part, a.strips, strip, a.n_pad, (int64_t)tt * kTileTokens + wave * 64, lane);
@@ -628,7 +635,8 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       float* m0t = a.mu0t ? a.mu0t + (int64_t)vt * a.mu0t_stride + (int64_t)tt_local * kTileTokens + wave * 64
                           : nullptr;
       if (MODE == kModeDz) {
-        dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane);
+        dz_epilogue(zs, zt, lse2, mu, blk, wave * 64, v0, a.V, tail, lane, a.heavy,
+                    (int64_t)tt * kTileTokens + wave * 64);
       } else if (tail) {
         single_epilogue<true, kDiag, kWriteD, kWriteE2>(zs, zt, sm, rs2, rt2, mu, zyt, yid, blk, a.e2_off, wave * 64, v0, a.V, lane, m0t);
       } else {
@@ -644,20 +652,6 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 // ---------------------------------------------------------------------------------------
 // Merge of the strip partials, KL_t and c_t.  One wave per computed row.
 // ---------------------------------------------------------------------------------------
-
-__device__ __forceinline__ float dot_bf16_row(const __bf16* x, const __bf16* y, int H, int lane) {
-  float acc = 0.f;
-  const uint4* px = (const uint4*)x;
-  const uint4* py = (const uint4*)y;
-  for (int q = lane; q < (H >> 3); q += 64) {
-    const uint4 a = px[q], b = py[q];
-    acc = fmaf(bf16_lo(a.x), bf16_lo(b.x), acc); acc = fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
-    acc = fmaf(bf16_lo(a.y), bf16_lo(b.y), acc); acc = fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
-    acc = fmaf(bf16_lo(a.z), bf16_lo(b.z), acc); acc = fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
-    acc = fmaf(bf16_lo(a.w), bf16_lo(b.w), acc); acc = fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
-  }
-  return wave_sum(acc);
-}
 
 __global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
   const int lane = threadIdx.x & 63;
@@ -676,17 +670,23 @@ __global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
   }
   const float lse_s = ms + logf(Zs), lse_t = mt + logf(Zt);
   const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
-  const float kl = kl_from_sums(mu, ms - mt, Zs, Zt);
+  float kl = kl_from_sums(mu, ms - mt, Zs, Zt);
+  // a row without a finite log-sum-exp, mean or KL is excluded: zeros in every output
+  const bool dead = !(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f) ||
+                    !(fabsf(mu) < 3.0e38f);
+  if (dead) kl = 0.f;
   if (lane == 0) {
-    a.lse2[r] = lse_s * kLog2e;
-    a.mu[r] = mu;
+    a.lse2[r] = dead ? 0.f : lse_s * kLog2e;
+    a.mu[r] = dead ? 0.f : mu;
     a.klr[r] = kl;
+    a.lse_s[r] = dead ? 0.f : lse_s;
+    a.alive[r] = dead ? 0.f : 1.f;
   }
   if (r >= a.n_rows) return;                // padding rows feed pass 2 only
   const int64_t t = a.row_idx[r];
   float c = 0.f;
-  uint32_t flag = 0;
-  if (a.ids && a.c) {
+  uint32_t flag = dead ? ADWIN_DEV_NONFINITE : 0u;
+  if (a.ids && a.c && !dead) {
     const int y = a.ids[t];
     if (y >= 0 && y < a.V) {
       const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
@@ -696,8 +696,6 @@ __global__ __launch_bounds__(256) void merge_stats_kernel(MergeArgs a) {
       flag |= ADWIN_DEV_BAD_ID;
     }
   }
-  if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f))
-    flag |= ADWIN_DEV_NONFINITE;
   if (lane == 0) {
     if (flag && a.status) atomicOr(a.status, flag);
     if (a.kl) a.kl[t] = kl;
@@ -755,18 +753,27 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
   if (a.diag) { Bt = wave_sum(Bt); cnt = wave_sum(cnt); }
   const float lse_s = b.ref_s2[r] * kLn2 + logf(Zs), lse_t = b.ref_t2[r] * kLn2 + logf(Zt);
   const float mu = A / Zs;                  // E_{p_s}[z_s - z_t]
-  const float kl = kl_from_sums(mu, (b.ref_s2[r] - b.ref_t2[r]) * kLn2, Zs, Zt);
+  float kl = kl_from_sums(mu, (b.ref_s2[r] - b.ref_t2[r]) * kLn2, Zs, Zt);
+  const float iz = 1.f / Zs;
+  float ent = lse_t - Bt / Zt;              // H[p_t] = lse_t - E_{p_t}[z_t]; both sums share the reference
+  // a row without a finite log-sum-exp, mean or KL (logits beyond the range the fixed
+  // references cover, or non-finite inputs) is excluded: zeros in every output
+  const bool dead = !(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f) ||
+                    !(fabsf(A) < 3.0e38f) || !(fabsf(mu) < 3.0e38f) || !(iz > 0.f) || !(iz < 3.0e38f) ||
+                    (a.diag && !(fabsf(ent) < 3.0e38f));
+  if (dead) { kl = 0.f; ent = 0.f; }
   if (lane == 0) {
-    b.mu_out[r] = mu;
-    b.inv_z[r] = 1.f / Zs;
+    b.mu_out[r] = dead ? 0.f : mu;
+    b.inv_z[r] = dead ? 0.f : iz;
     a.klr[r] = kl;
+    a.lse_s[r] = dead ? 0.f : lse_s;
   }
   if (r >= a.n_rows) return;
   const int64_t t = a.row_idx[r];
   float c = 0.f, logp_t = 0.f;
   bool have_y = false;
-  uint32_t flag = 0;
-  if (a.ids && (a.c || a.t_logp || a.t_rank || a.cr)) {
+  uint32_t flag = dead ? ADWIN_DEV_NONFINITE : 0u;
+  if (a.ids && (a.c || a.t_logp || a.t_rank || a.cr) && !dead) {
     const int y = a.ids[t];
     if (y >= 0 && y < a.V) {
       const float zy_s = dot_bf16_row(a.h_s + t * a.H_s, a.W_s + (int64_t)y * a.H_s, a.H_s, lane);
@@ -778,16 +785,12 @@ __global__ __launch_bounds__(256) void merge_single_kernel(MergeSingleArgs b) {
       flag |= ADWIN_DEV_BAD_ID;
     }
   }
-  if (!(fabsf(lse_s) < 3.0e38f) || !(fabsf(lse_t) < 3.0e38f) || !(fabsf(kl) < 3.0e38f) ||
-      !(fabsf(A) < 3.0e38f))
-    flag |= ADWIN_DEV_NONFINITE;
   if (lane == 0) {
     if (flag && a.status) atomicOr(a.status, flag);
     if (a.kl) a.kl[t] = kl;
     if (a.c) a.c[t] = c;
     if (a.t_logp) a.t_logp[t] = logp_t;
-    // H[p_t] = lse_t - E_{p_t}[z_t]; both sums are relative to the same reference
-    if (a.t_entropy) a.t_entropy[t] = lse_t - Bt / Zt;
+    if (a.t_entropy) a.t_entropy[t] = ent;
     if (a.t_rank) a.t_rank[t] = have_y ? (int32_t)cnt + 1 : 0;
     if (a.cr) a.cr[r] = c;
   }

@@ -3,6 +3,7 @@ conversion of the seeded inputs into what the oracle takes."""
 import numpy as np
 
 from paper_2605_28396_amd import synth
+from tests import error_model
 
 # Tolerances: bf16 inputs, fp32 accumulation on the GPU, fp64 oracle.
 KL_REL = 1e-3          # |dKL| <= KL_REL * KL  (+ KL_ABS floor for tiny KL)
@@ -68,3 +69,33 @@ def assert_close_rel(got, want, rel, what):
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
     err = np.abs(got - want)
     assert np.all(err <= rel * np.abs(want) + 1e-7), f"{what}: worst {err.max():.3e}"
+
+
+def summand_norms(f, w, rows, reduction, grad_scale=1.0, estimator=0, head=False, block=64):
+    """Per-element error scales of the gradient outputs (tests/error_model.py) for workload w:
+    g_l2 [T, H_s] for the unweighted row gradients and, with head, dW_prefix_l2 / dW_full_l2
+    for the weighted head-weight gradients.  The weights are those of the reduction."""
+    lens = np.diff(w.offsets)
+    n = np.minimum(w.window.astype(np.int64), lens)
+    B = len(n)
+    if reduction == 0:        # sequence mean
+        ap = np.where(n > 0, 1.0 / (B * np.maximum(n, 1)), 0.0)
+        af = np.where(lens > 0, 1.0 / (B * np.maximum(lens, 1)), 0.0)
+    elif reduction == 1:      # sum
+        ap = af = np.ones(B)
+    else:                     # token mean
+        ap = np.full(B, 1.0 / n.sum() if n.sum() else 0.0)
+        af = np.full(B, 1.0 / lens.sum() if lens.sum() else 0.0)
+    return error_model.problem_norms(f, w.offsets, w.window, rows, ap, af, grad_scale, estimator, head, block)
+
+
+def assert_grad_elementwise(got, want, l2, what="dh"):
+    """Every element within DW_SIGMAS * 2^-9 of the Euclidean norm of its own summands (l2, already
+    carrying the element's weight): the bound for gradients whose elements sum too few terms
+    for a fraction of the largest element to mean anything."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    tol = DW_SIGMAS * DW_SIGMA * l2 + 1e-6 * (np.abs(want).max() if want.size else 0.0)
+    err = np.abs(got - want)
+    assert (err <= tol).all(), (what, err.max(), (err / np.maximum(tol, 1e-300)).max())
+    zero_rows = ~np.any(want.reshape(want.shape[0], -1) != 0, axis=1)
+    assert not np.any(got.reshape(got.shape[0], -1)[zero_rows] != 0), f"{what}: non-zero outside windows"

@@ -29,6 +29,19 @@ def _sample_ids_from_student(w, p):
     return torch.from_numpy(ids)
 
 
+def _grad_l2(f, w, ref, reduction, grad_scale=1.0, estimator=0):
+    """Per-element error scales of dh_prefix / dh_full: the summand norms of g times the weight
+    of each row under the two objectives."""
+    nrm = Hp.summand_norms(f, w, ref["rows"], reduction, grad_scale, estimator)["g_l2"]
+    lens = np.diff(w.offsets)
+    a_p, a_f = O.row_weights(lens, ref["n"], reduction)
+    seq = np.repeat(np.arange(w.B), lens)
+    adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
+    wp = np.abs(grad_scale) * a_p[seq] * adm
+    wf = np.abs(grad_scale) * a_f[seq]
+    return nrm * wp[:, None], nrm * wf[:, None]
+
+
 def _run_fused(B, w, p, dev, **kw):
     d = {k: v.to(dev) for k, v in p.items()}
     out = B.adwin_opd_fused(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window,
@@ -38,17 +51,26 @@ def _run_fused(B, w, p, dev, **kw):
             for k, v in out.items()}
 
 
-def _check_fused(w, got, ref, reduction, dh_bf16=False, logit_scale=None, abs_cap=True):
+def _check_fused(w, got, ref, reduction, dh_bf16=False, logit_scale=None, abs_cap=True, grad_l2=None):
+    """grad_l2: (l2 of dh_prefix, l2 of dh_full) -- hold the gradients to the per-element bound of
+    their own summands (small vocabularies) instead of the fraction-of-maximum bar."""
     assert np.array_equal(got["n_out"], ref["n"]) and int(got["n_adm_out"][0]) == ref["n_adm"]
     assert int(got["status_dev"][0]) == 0
     Hp.assert_kl(got["kl"], ref["kl"], logit_scale=logit_scale)
     Hp.assert_cost(got["c"], ref["c"])
     ulp = Hp.BF16_ULP if dh_bf16 else 0.0
-    Hp.assert_grad(got["dh_prefix"], ref["dh_prefix"], "dh_prefix", ulp, abs_cap)
+    probe = w.mode == synth.MODE_PREFIX_AND_FULL
+    if grad_l2 is None:
+        Hp.assert_grad(got["dh_prefix"], ref["dh_prefix"], "dh_prefix", ulp, abs_cap)
+    else:
+        Hp.assert_grad_elementwise(got["dh_prefix"], ref["dh_prefix"], grad_l2[0], "dh_prefix")
+        if probe:
+            Hp.assert_grad_elementwise(got["dh_full"], ref["dh_full"], grad_l2[1], "dh_full")
     Hp.assert_close_rel(got["loss_prefix"], ref["loss_prefix"], Hp.LOSS_REL, "loss_prefix")
     Hp.assert_close_rel(got["batch"][:2], ref["batch"][:2], Hp.LOSS_REL, "batch losses")
     if w.mode == synth.MODE_PREFIX_AND_FULL:
-        Hp.assert_grad(got["dh_full"], ref["dh_full"], "dh_full", ulp, abs_cap)
+        if grad_l2 is None:
+            Hp.assert_grad(got["dh_full"], ref["dh_full"], "dh_full", ulp, abs_cap)
         Hp.assert_close_rel(got["loss_full"], ref["loss_full"], Hp.LOSS_REL, "loss_full")
         for k in ("rho_pooled", "rho_field"):
             assert np.all(np.abs(got[k] - ref[k]) <= Hp.RHO_ABS), (k, got[k], ref[k])
@@ -117,17 +139,56 @@ def test_non_finite_rows_are_flagged_and_stay_local(B):
             q["h_s"][bad, 7] = poison
         else:
             q["h_s"][bad] *= poison
-        got = _run_fused(B, w, q, "cuda", reduction=O.RED_SUM)
-        assert int(got["status_dev"][0]) & B.ADWIN_DEV_NONFINITE, poison
-        keep = np.ones(w.T, bool); keep[bad] = False
-        assert np.array_equal(got["kl"][keep], clean["kl"][keep])
-        assert np.array_equal(got["dh_prefix"][keep], clean["dh_prefix"][keep])
+        for scheme in (B.ADWIN_SCHEME_SINGLE, B.ADWIN_SCHEME_TWO_SWEEP):
+            if scheme == B.ADWIN_SCHEME_TWO_SWEEP and poison != float("inf"):
+                continue      # finite logits, however far apart, are in range for the running maximum
+            got = _run_fused(B, w, q, "cuda", reduction=O.RED_SUM, scheme=scheme,
+                             want=B.FusedCall.DEFAULT_OUTPUTS + (("dW_prefix", "t_entropy") if scheme == B.ADWIN_SCHEME_SINGLE else ()))
+            assert int(got["status_dev"][0]) & B.ADWIN_DEV_NONFINITE, (poison, scheme)
+            keep = np.ones(w.T, bool); keep[bad] = False
+            ref_run = clean if scheme == B.ADWIN_SCHEME_SINGLE else _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, scheme=scheme)
+            assert np.array_equal(got["kl"][keep], ref_run["kl"][keep])
+            assert np.array_equal(got["dh_prefix"][keep], ref_run["dh_prefix"][keep])
+            # the row itself is excluded: zeros, and every reduced output stays finite and is that
+            # of the batch without the row
+            assert got["kl"][bad] == 0 and got["c"][bad] == 0 and not got["dh_prefix"][bad].any()
+            assert not got["dh_full"][bad].any()
+            for k, v in got.items():
+                assert np.all(np.isfinite(v)), (k, poison, scheme)
+            i_bad = int(np.searchsorted(w.offsets, bad, side="right") - 1)
+            n_bad = min(int(w.window[i_bad]), int(w.offsets[i_bad + 1] - w.offsets[i_bad]))
+            want_loss = ref_run["loss_prefix"].astype(np.float64).copy()
+            want_loss[i_bad] -= float(ref_run["kl"][bad]) / n_bad
+            assert np.allclose(got["loss_prefix"], want_loss, rtol=1e-5, atol=1e-6)
+            others = np.arange(w.B) != i_bad
+            assert np.allclose(got["rho_pooled"][others], ref_run["rho_pooled"][others], atol=1e-6)
+    # a finite row far outside the single sweep's range is in range for the running maxima
+    q = dict(p); q["h_s"] = p["h_s"].clone(); q["h_s"][int(rows[3])] *= 3.0e4
+    got = _run_fused(B, w, q, "cuda", reduction=O.RED_SUM, scheme=B.ADWIN_SCHEME_TWO_SWEEP)
+    assert int(got["status_dev"][0]) == 0
+    fq = Hp.oracle_inputs(q)
+    t = int(rows[3])
+    kl_t = O.token_kl(fq["W_s"] @ fq["h_s"][t], fq["W_t"] @ fq["h_t"][t])
+    assert abs(got["kl"][t] - kl_t) <= 2e-3 * kl_t          # logits of magnitude 1e4: fp32 rounding of z
     lo = synth.logits_problem(w)
     d = {k: v.cuda() for k, v in lo.items()}
-    d["z_s"][int(rows[3]), 5] = float("inf")
-    out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window, reduction=O.RED_SUM)
-    torch.cuda.synchronize()
-    assert int(out["status_dev"][0]) & B.ADWIN_DEV_NONFINITE
+    poisoned = d["z_s"].clone()
+    poisoned[int(rows[3]), 5] = float("inf")
+    for scheme in (B.ADWIN_LOGITS_RESIDENT, B.ADWIN_LOGITS_STREAMING):
+        base = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window, reduction=O.RED_SUM,
+                                       scheme=scheme)
+        torch.cuda.synchronize()
+        base = {k: v.float().cpu().numpy() for k, v in base.items()}
+        d_bad = dict(d, z_s=poisoned)
+        out = B.adwin_opd_from_logits(d_bad["z_s"], d["z_t"], d["ids"], w.offsets, w.window, reduction=O.RED_SUM,
+                                      scheme=scheme)
+        torch.cuda.synchronize()
+        assert int(out["status_dev"][0]) & B.ADWIN_DEV_NONFINITE
+        o = {k: v.float().cpu().numpy() for k, v in out.items()}
+        assert all(np.all(np.isfinite(v)) for v in o.values())
+        assert o["kl"][int(rows[3])] == 0 and not o["dz"][int(rows[3])].any()
+        keep = np.ones(w.T, bool); keep[int(rows[3])] = False
+        assert np.array_equal(o["kl"][keep], base["kl"][keep]) and np.array_equal(o["dz"][keep], base["dz"][keep])
 
 
 def test_teacher_equal_to_student_gives_zero(B):
@@ -195,24 +256,33 @@ def test_logits_given_vocabulary_beyond_the_resident_capacity(B, estimator):
     Hp.assert_close_rel(got["loss_prefix"], ref["loss_prefix"], Hp.LOSS_REL, "loss_prefix")
 
 
-@pytest.mark.parametrize("env", [{"ADWIN_TWO_SWEEP": "1"}, {"ADWIN_NO_DMA": "1"}])
-def test_fallback_schemes_match_oracle(B, env, monkeypatch):
-    """The two-sweep scheme and the register-staged logit kernel stay available (selected
-    by environment variables read at call time) and meet the same bar."""
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
+@pytest.mark.parametrize("scheme", ["ADWIN_SCHEME_SINGLE", "ADWIN_SCHEME_TWO_SWEEP", "ADWIN_SCHEME_TWO_SWEEP_REG"])
+def test_fallback_schemes_match_oracle(B, scheme):
+    """The scheme field of the problem struct selects the single sweep, the two-sweep scheme
+    (running maxima) or the latter with register-staged tiles; all meet the same bar."""
+    scheme = getattr(B, scheme)
     w = synth.workload("ragged_small")
     p = synth.hidden_problem(w)
     f = Hp.oracle_inputs(p)
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
                       reduction=O.RED_SUM, grad_scale=1.0, mode=w.mode)
-    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, grad_scale=1.0, dh_dtype=B.ADWIN_DT_F32)
+    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, grad_scale=1.0, dh_dtype=B.ADWIN_DT_F32,
+                     scheme=scheme)
     _check_fused(w, got, ref, O.RED_SUM)
-    # the switch is in force: what rides on the single sweep is refused under it
     d = {k: v.cuda() for k, v in p.items()}
     call = B.FusedCall(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window, mode=w.mode,
-                       want=B.FusedCall.DEFAULT_OUTPUTS + ("t_entropy",))
-    assert call.run() == B.ADWIN_E_MODE
+                       want=B.FusedCall.DEFAULT_OUTPUTS + ("t_entropy",), scheme=scheme)
+    if scheme == B.ADWIN_SCHEME_SINGLE:
+        assert call.run() == 0
+    else:       # what rides on the single sweep is refused under the others
+        assert call.run() == B.ADWIN_E_MODE
+    # the workspace follows the scheme of the same struct
+    single = B.FusedCall(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window, mode=w.mode,
+                         scheme=B.ADWIN_SCHEME_SINGLE, allocate=False)
+    other = B.FusedCall(d["h_s"], d["h_t"], d["W_s"], d["W_t"], d["ids"], w.offsets, w.window, mode=w.mode,
+                        scheme=scheme, allocate=False)
+    assert (B.adwin_opd_workspace_bytes(single.p) == B.adwin_opd_workspace_bytes(other.p)) == (scheme == B.ADWIN_SCHEME_SINGLE)
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("name,reduction", [
@@ -341,10 +411,8 @@ def test_sampled_estimator_fused(B, name, reduction):
     assert np.abs(ref["dh_prefix"] - exp["dh_prefix"]).max() > 0.1 * np.abs(exp["dh_prefix"]).max()
 
 
-@pytest.mark.parametrize("env", [{}, {"ADWIN_LOGITS_STREAMING": "1"}])
-def test_sampled_estimator_from_logits(B, env, monkeypatch):
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
+@pytest.mark.parametrize("scheme", [0, 2])          # row-resident (default), streaming
+def test_sampled_estimator_from_logits(B, scheme):
     w = synth.workload("ragged_small")
     p = synth.logits_problem(w)
     f = Hp.oracle_inputs(p)
@@ -352,7 +420,8 @@ def test_sampled_estimator_from_logits(B, env, monkeypatch):
                                   reduction=O.RED_SEQ_MEAN, grad_scale=-2.0, estimator=O.EST_SAMPLED)
     d = {k: v.cuda() for k, v in p.items()}
     out = B.adwin_opd_from_logits(d["z_s"], d["z_t"], d["ids"], w.offsets, w.window,
-                                  reduction=O.RED_SEQ_MEAN, grad_scale=-2.0, estimator=B.ADWIN_EST_SAMPLED)
+                                  reduction=O.RED_SEQ_MEAN, grad_scale=-2.0, estimator=B.ADWIN_EST_SAMPLED,
+                                  scheme=scheme)
     torch.cuda.synchronize()
     got = {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
            for k, v in out.items()}
@@ -398,11 +467,12 @@ WANT_HEAD = ("kl", "c", "dh_prefix", "dh_full", "loss_prefix", "loss_full", "rho
              "batch", "n_out", "n_adm_out", "status_dev", "dW_prefix", "dW_full")
 
 
-def _check_head_gradient(got, ref, probe):
+def _check_head_gradient(got, ref, probe, nrm):
+    """nrm: Hp.summand_norms(..., head=True) of the same problem."""
     for k in ("dW_prefix", "dW_full") if probe else ("dW_prefix",):
         scale = np.abs(ref[k]).max()
         err = np.abs(got[k] - ref[k])
-        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref[k + "_l2"] + 1e-6 * scale
+        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * nrm[k + "_l2"] + 1e-6 * scale
         assert (err <= tol).all(), (k, err.max(), scale, (err / tol).max())
         assert err.max() <= 2.0 ** -7 * scale
         # every dz row sums to zero over the vocabulary, so every column of dW does
@@ -427,7 +497,7 @@ def test_head_weight_gradient(B, name, reduction):
                       reduction=reduction, grad_scale=-1.5, mode=w.mode, head_gradient=True)
     got = _run_fused(B, w, p, "cuda", reduction=reduction, grad_scale=-1.5, want=WANT_HEAD)
     _check_fused(w, got, ref, reduction)
-    _check_head_gradient(got, ref, probe)
+    _check_head_gradient(got, ref, probe, Hp.summand_norms(f, w, ref["rows"], reduction, -1.5, head=True))
 
 
 @pytest.mark.parametrize("name", ["tiny_probe", "ragged_small", "ragged_mid"])
@@ -442,7 +512,7 @@ def test_head_weight_gradient_sampled_estimator(B, name):
     got = _run_fused(B, w, p, "cuda", reduction=O.RED_SEQ_MEAN, grad_scale=2.0, want=WANT_HEAD,
                      estimator=B.ADWIN_EST_SAMPLED)
     _check_fused(w, got, ref, O.RED_SEQ_MEAN)
-    _check_head_gradient(got, ref, True)
+    _check_head_gradient(got, ref, True, Hp.summand_norms(f, w, ref["rows"], O.RED_SEQ_MEAN, 2.0, O.EST_SAMPLED, head=True))
 
 
 def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
@@ -457,6 +527,7 @@ def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
     f = Hp.oracle_inputs(p)
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
                       reduction=O.RED_SUM, mode=w.mode, head_gradient=True)
+    nrm = Hp.summand_norms(f, w, ref["rows"], O.RED_SUM, head=True)
     first = None
     for _ in range(2):          # a second run over the same buffers overwrites, never adds to, the first
         assert call.run() == 0
@@ -464,7 +535,7 @@ def test_head_weight_gradient_accumulates_over_slabs(B, monkeypatch):
         got = {k: v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
                for k, v in call.out.items()}
         _check_fused(w, got, ref, O.RED_SUM)
-        _check_head_gradient(got, ref, True)
+        _check_head_gradient(got, ref, True, nrm)
         if first is None:
             first = got
     for k in ("dW_prefix", "dW_full", "dh_full", "kl", "batch"):      # and reproduces it bit for bit
@@ -524,20 +595,12 @@ def test_minimal_and_odd_shapes(B, V, H_s, H_t, lens, win):
         p = synth.hidden_problem(w)
         f = Hp.oracle_inputs(p)
         ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
-                          reduction=O.RED_SUM, mode=mode, summand_norms=True)
+                          reduction=O.RED_SUM, mode=mode)
         got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32)
         # A gradient element sums only V terms here, too few for the fraction-of-maximum bound
         # (stated for vocabularies where rounding averages out) to have its statistical margin:
-        # bound every element by its own summands instead, as for the head-weight gradient.
-        adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
-        for k, mask in (("dh_prefix", adm), ("dh_full", np.ones(w.T, bool))):
-            if k == "dh_full" and mode != synth.MODE_PREFIX_AND_FULL:
-                continue
-            tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask[:, None] + 1e-6 * np.abs(ref[k]).max()
-            err = np.abs(got[k] - ref[k])
-            assert (err <= tol).all(), (k, err.max(), (err / tol).max())
-            got[k] = ref[k]                      # checked; the remaining checks use the standard bar
-        _check_fused(w, got, ref, O.RED_SUM)
+        # every element is bounded by its own summands instead, as for the head-weight gradient.
+        _check_fused(w, got, ref, O.RED_SUM, grad_l2=_grad_l2(f, w, ref, O.RED_SUM))
     lo = synth.logits_problem(w)
     fl = Hp.oracle_inputs(lo)
     d = {k: v.cuda() for k, v in lo.items()}
@@ -572,17 +635,10 @@ def test_random_small_shapes(B, V, H_s, H_t, lens, win, mode):
     p = synth.hidden_problem(w)
     f = Hp.oracle_inputs(p)
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
-                      reduction=O.RED_SUM, mode=mode, summand_norms=True)
+                      reduction=O.RED_SUM, mode=mode)
     got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32)
-    adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
-    for k, mask in (("dh_prefix", adm), ("dh_full", np.ones(w.T, bool))):
-        if k == "dh_full" and mode != synth.MODE_PREFIX_AND_FULL:
-            continue
-        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask[:, None] + 1e-6 * np.abs(ref[k]).max()
-        err = np.abs(got[k] - ref[k])
-        assert (err <= tol).all(), (k, err.max(), (err / np.maximum(tol, 1e-30)).max())
-        got[k] = ref[k]                          # checked element by element; the rest at the standard bar
-    _check_fused(w, got, ref, O.RED_SUM)
+    # vocabularies of at most 1,200 entries: gradient elements bounded by their own summands
+    _check_fused(w, got, ref, O.RED_SUM, grad_l2=_grad_l2(f, w, ref, O.RED_SUM))
 
 
 def test_every_output_is_optional(B):
@@ -627,36 +683,24 @@ def test_peaked_distributions(B, estimator, on_policy):
     """Logits with a spread of 4 nats (half the mass on one entry, row maximum 14 nats on average
     and up to 25 above the largest of the first 128 entries) and a teacher that is a perturbed
     copy of the student: the regime of trained models, where the fixed references of the
-    single sweep sit far below the row maximum."""
+    single sweep sit far below the row maximum and a gradient row is carried by a handful of
+    vocabulary entries.  The gradients are held to the same bar as everywhere else (2e-3 of the
+    largest element): the entries with p_s >= 1/32 are contracted in fp32."""
     w = _peaked_workload()
     p = synth.peaked_problem(w)
     if on_policy:                       # y_t ~ p_s, as in the method; else uniform over the vocabulary
         p["ids"] = _sample_ids_from_student(w, p)
     f = Hp.oracle_inputs(p)
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
-                      reduction=O.RED_SUM, mode=w.mode, estimator=estimator,
-                      head_gradient=True, summand_norms=True)
+                      reduction=O.RED_SUM, mode=w.mode, estimator=estimator, head_gradient=True)
     assert 0.5 < ref["kl"].mean() < 3.0
     want = B.FusedCall.DEFAULT_OUTPUTS + ("t_logp", "t_entropy", "t_rank", "dW_prefix", "dW_full")
     got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32, estimator=estimator,
                      want=want)
     z_t = f["h_t"] @ f["W_t"].T
     lse_t = np.array([np.log(np.exp(z - z.max()).sum()) + z.max() for z in z_t])
-    if estimator == O.EST_EXPECTED:
-        # A gradient row is carried by a handful of vocabulary entries here, so the rounding of
-        # dz to bf16 does not average out: even with the exact mu known in advance (the two-sweep
-        # scheme) the error is 0.4 % of the largest gradient element.  Every element is held to
-        # the bound of its own summands instead; the per-tile references of the sweep keep the
-        # rounding of the two stored factors proportional to p_s |d - mu|, which this checks.
-        adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
-        for k, mask in (("dh_prefix", adm), ("dh_full", np.ones(w.T, bool))):
-            tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask[:, None] + 1e-6 * np.abs(ref[k]).max()
-            err = np.abs(got[k] - ref[k])
-            assert (err <= tol).all(), (k, err.max(), np.abs(ref[k]).max(), (err / tol).max())
-            assert err.max() <= 3 * Hp.DH_REL * np.abs(ref[k]).max(), (k, err.max(), np.abs(ref[k]).max())
-            got[k] = ref[k]
     _check_fused(w, got, ref, O.RED_SUM, logit_scale=np.abs(lse_t), abs_cap=False)
-    _check_head_gradient(got, ref, True)
+    _check_head_gradient(got, ref, True, Hp.summand_norms(f, w, ref["rows"], O.RED_SUM, 1.0, estimator, head=True))
     ent, logp, lo, hi = _teacher_reference(z_t, f["ids"], list(ref["rows"]), 1e-3)
     for t in ref["rows"]:
         assert abs(got["t_entropy"][t] - ent[t]) <= 2e-3, (t, got["t_entropy"][t], ent[t])
@@ -664,9 +708,9 @@ def test_peaked_distributions(B, estimator, on_policy):
         assert lo[t] <= got["t_rank"][t] <= hi[t]
 
 
-def test_peaked_distributions_other_paths(B, monkeypatch):
+def test_peaked_distributions_other_paths(B):
     """The same peaked pair through the logits-given kernels (both) and through the two-sweep
-    fallback of the fused path."""
+    schemes of the fused path."""
     w = _peaked_workload()
     p = synth.peaked_problem(w)
     p["ids"] = _sample_ids_from_student(w, p)
@@ -676,27 +720,19 @@ def test_peaked_distributions_other_paths(B, monkeypatch):
     fz_s, fz_t = synth.to_f64(z_s), synth.to_f64(z_t)
     refl = O.supervise_from_logits(fz_s, fz_t, f["ids"], w.offsets, w.window, reduction=O.RED_SUM)
     lse = np.array([np.log(np.exp(z - z.max()).sum()) + z.max() for z in fz_t])
-    for env in ({}, {"ADWIN_LOGITS_STREAMING": "1"}):
-        for k, v in env.items():
-            monkeypatch.setenv(k, v)
+    for scheme in (B.ADWIN_LOGITS_RESIDENT, B.ADWIN_LOGITS_STREAMING):
         out = B.adwin_opd_from_logits(z_s.cuda(), z_t.cuda(), p["ids"].cuda(), w.offsets, w.window,
-                                      reduction=O.RED_SUM)
+                                      reduction=O.RED_SUM, scheme=scheme)
         torch.cuda.synchronize()
         Hp.assert_kl(out["kl"].cpu().numpy(), refl["kl"], logit_scale=np.abs(lse))
         Hp.assert_cost(out["c"].cpu().numpy(), refl["c"])
         Hp.assert_grad(out["dz"].float().cpu().numpy(), refl["dz"], "dz", Hp.BF16_ULP, abs_cap=False)
-    monkeypatch.delenv("ADWIN_LOGITS_STREAMING")
-    monkeypatch.setenv("ADWIN_TWO_SWEEP", "1")
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
-                      reduction=O.RED_SUM, mode=w.mode, summand_norms=True)
-    got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32)
+                      reduction=O.RED_SUM, mode=w.mode)
     lse_t = np.array([np.log(np.exp(z - z.max()).sum()) + z.max() for z in f["h_t"] @ f["W_t"].T])
-    for k in ("dh_prefix", "dh_full"):
-        mask = (np.abs(ref[k]).sum(axis=1) > 0)[:, None]
-        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * mask + 1e-6 * np.abs(ref[k]).max()
-        assert (np.abs(got[k] - ref[k]) <= tol).all(), k
-        got[k] = ref[k]
-    _check_fused(w, got, ref, O.RED_SUM, logit_scale=np.abs(lse_t), abs_cap=False)
+    for scheme in (B.ADWIN_SCHEME_TWO_SWEEP, B.ADWIN_SCHEME_TWO_SWEEP_REG):
+        got = _run_fused(B, w, p, "cuda", reduction=O.RED_SUM, dh_dtype=B.ADWIN_DT_F32, scheme=scheme)
+        _check_fused(w, got, ref, O.RED_SUM, logit_scale=np.abs(lse_t), abs_cap=False)
 
 
 @pytest.mark.parametrize("name", ["ragged_small", "ragged_mid", "tiny"])
@@ -742,19 +778,12 @@ def test_many_short_rollouts(B):
     cands = [1, 3, 8, 20, 64]
     for reduction in (O.RED_SEQ_MEAN, O.RED_TOKEN_MEAN):
         ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
-                          reduction=reduction, mode=w.mode, summand_norms=True)
+                          reduction=reduction, mode=w.mode)
         got = _run_fused(B, w, p, "cuda", reduction=reduction, dh_dtype=B.ADWIN_DT_F32, candidates=cands,
                          want=B.FusedCall.DEFAULT_OUTPUTS + ("t_rank", "t_logp", "t_first_reject", "t_logp_mean",
                                                             "cand_loss_share"), topk=100)
         # gradient elements: V = 264 is a tiny vocabulary (see test_minimal_and_odd_shapes)
-        a_p, a_f = O.row_weights(lens, np.minimum(win, lens), reduction)
-        seq = np.repeat(np.arange(nb), lens)
-        adm = np.zeros(w.T, bool); adm[O.plan(w.offsets, w.window)["rows"]] = True
-        for k, wt in (("dh_prefix", a_p[seq] * adm), ("dh_full", a_f[seq])):
-            tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * np.abs(wt)[:, None] + 1e-6 * np.abs(ref[k]).max()
-            assert (np.abs(got[k] - ref[k]) <= tol).all(), k
-            got[k] = ref[k]
-        _check_fused(w, got, ref, reduction)
+        _check_fused(w, got, ref, reduction, grad_l2=_grad_l2(f, w, ref, reduction))
         aud = O.audit_candidates(ref["g"], w.offsets, cands, reduction)
         assert np.all(np.abs(got["cand_rho_pooled"] - aud["rho_pooled"]) <= Hp.RHO_ABS)
         assert np.all(np.abs(got["cand_rho_field"] - aud["rho_field"]) <= Hp.RHO_ABS)
@@ -774,15 +803,9 @@ def test_one_long_rollout(B):
     f = Hp.oracle_inputs(p)
     cands = [1, 1000, 33333, 65536, 100000]
     ref = O.supervise(f["h_s"], f["h_t"], f["W_s"], f["W_t"], f["ids"], w.offsets, w.window,
-                      reduction=O.RED_SEQ_MEAN, mode=w.mode, summand_norms=True, block=256)
+                      reduction=O.RED_SEQ_MEAN, mode=w.mode, block=256)
     got = _run_fused(B, w, p, "cuda", reduction=O.RED_SEQ_MEAN, dh_dtype=B.ADWIN_DT_F32, candidates=cands)
-    a_p, a_f = O.row_weights(np.array([70000]), np.array([33333]), O.RED_SEQ_MEAN)
-    adm = np.arange(w.T) < 33333
-    for k, wt in (("dh_prefix", a_p[0] * adm), ("dh_full", np.full(w.T, a_f[0]))):
-        tol = Hp.DW_SIGMAS * Hp.DW_SIGMA * ref["g_l2"] * np.abs(wt)[:, None] + 1e-6 * np.abs(ref[k]).max()
-        assert (np.abs(got[k] - ref[k]) <= tol).all(), k
-        got[k] = ref[k]
-    _check_fused(w, got, ref, O.RED_SEQ_MEAN)
+    _check_fused(w, got, ref, O.RED_SEQ_MEAN, grad_l2=_grad_l2(f, w, ref, O.RED_SEQ_MEAN))
     aud = O.audit_candidates(ref["g"], w.offsets, cands, O.RED_SEQ_MEAN)
     assert np.all(np.abs(got["cand_rho_pooled"] - aud["rho_pooled"]) <= Hp.RHO_ABS)
     assert np.all(np.abs(got["cand_rho_field"] - aud["rho_field"]) <= Hp.RHO_ABS)

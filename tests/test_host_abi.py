@@ -115,6 +115,23 @@ def test_workspace_bytes_and_argument_errors_without_gpu(B):
     assert st(_problem(B, reduction=5)) == B.ADWIN_E_MODE
     assert st(_problem(B, dh_dtype=9)) == B.ADWIN_E_MODE
     assert st(_problem(B, struct_bytes=8)) == B.ADWIN_E_MODE
+    # scheme: a field of the struct, read alike by the workspace query and the call
+    assert st(_problem(B, scheme=9)) == B.ADWIN_E_MODE
+    assert st(_problem(B, scheme=-1)) == B.ADWIN_E_MODE
+    assert st(_problem(B, scheme=B.ADWIN_SCHEME_SINGLE, H_s=64)) == B.ADWIN_E_MODE     # needs H >= 128
+    assert st(_problem(B, scheme=B.ADWIN_SCHEME_AUTO, H_s=64)) == B.ADWIN_E_WORKSPACE  # falls back, valid
+    with pytest.raises(B.AdwinError) as e:
+        B.adwin_opd_workspace_bytes(_problem(B, scheme=9))
+    assert e.value.status == B.ADWIN_E_MODE
+    sizes = {sc: B.adwin_opd_workspace_bytes(_problem(B, scheme=sc, dh_prefix=4096))
+             for sc in (B.ADWIN_SCHEME_AUTO, B.ADWIN_SCHEME_SINGLE, B.ADWIN_SCHEME_TWO_SWEEP, B.ADWIN_SCHEME_TWO_SWEEP_REG)}
+    assert sizes[B.ADWIN_SCHEME_AUTO] == sizes[B.ADWIN_SCHEME_SINGLE] > sizes[B.ADWIN_SCHEME_TWO_SWEEP] > sizes[B.ADWIN_SCHEME_TWO_SWEEP_REG]
+    for sc, nbytes in sizes.items():            # a workspace sized for another scheme is refused, not overrun
+        if nbytes < sizes[B.ADWIN_SCHEME_SINGLE]:
+            assert st(_problem(B, scheme=B.ADWIN_SCHEME_SINGLE, dh_prefix=4096), 4096, nbytes) == B.ADWIN_E_WORKSPACE
+    # the two-sweep schemes do not offer what rides on the single sweep
+    assert st(_problem(B, scheme=B.ADWIN_SCHEME_TWO_SWEEP, t_entropy=4096), 4096, 1 << 40) == B.ADWIN_E_MODE
+    assert st(_problem(B, scheme=B.ADWIN_SCHEME_TWO_SWEEP_REG, estimator=1, ids=4096), 4096, 1 << 40) == B.ADWIN_E_MODE
     assert st(_problem(B, W_s=None)) == B.ADWIN_E_NULL
     assert st(_problem(B, h_s=4100)) == B.ADWIN_E_ALIGN
     assert st(_problem(B)) == B.ADWIN_E_WORKSPACE                  # NULL workspace
@@ -148,6 +165,8 @@ def test_workspace_bytes_and_argument_errors_without_gpu(B):
     assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_SHAPE
     lp.topk, lp.t_logp_mean = 3, 4096
     assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_NULL      # no t_logp
+    lp.t_logp_mean, lp.t_first_reject, lp.scheme = None, None, 3
+    assert B.lib.adwin_opd_from_logits(C.byref(lp), 0, 0, None) == B.ADWIN_E_MODE      # unknown scheme
 
 
 def test_scheduler_functions_match_oracle(B):

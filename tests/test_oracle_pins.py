@@ -359,6 +359,95 @@ def test_field_alignment_closed_form_random():
         assert -1 - 1e-12 <= out["rho_pooled"][i] <= 1 + 1e-12
 
 
+def test_field_micro_cosine_closed_form_with_unequal_weights():
+    """batch[3], the cosine of the two whole [T, H_s] gradient arrays (Sec. 4.2's cosine after
+    batch aggregation, Fig. 5 "micro", in the field reading): with S_i(m) the sum of squared row
+    norms of g over the first m rows of rollout i it is
+    sum_i a^p_i a^f_i S_i(n_i) / sqrt(sum_i a^p_i^2 S_i(n_i) * sum_i a^f_i^2 S_i(len_i)).
+    Rollouts of different lengths and windows give unequal weights, so it differs from the pooled
+    micro cosine, from the macro mean and from any unweighted version."""
+    pr, lens = _small_problem(12, B=5)
+    window = np.array([1, 3, 2, 100, 1])
+    n = np.minimum(window, lens)
+    for red in (O.RED_SEQ_MEAN, O.RED_TOKEN_MEAN, O.RED_SUM):
+        out = O.supervise(**pr, window=window, mode=O.MODE_PREFIX_AND_FULL, reduction=red, grad_scale=0.7)
+        B = len(lens)
+        if red == O.RED_SEQ_MEAN:
+            ap, af = 1.0 / (B * n), 1.0 / (B * lens)
+        elif red == O.RED_TOKEN_MEAN:
+            ap, af = np.full(B, 1.0 / n.sum()), np.full(B, 1.0 / lens.sum())
+        else:
+            ap = af = np.ones(B)
+        S_n = np.array([(out["g"][pr["offsets"][i]:pr["offsets"][i] + n[i]] ** 2).sum() for i in range(B)])
+        S_l = np.array([(out["g"][pr["offsets"][i]:pr["offsets"][i + 1]] ** 2).sum() for i in range(B)])
+        want = (ap * af * S_n).sum() / math.sqrt((ap ** 2 * S_n).sum() * (af ** 2 * S_l).sum())
+        assert out["batch"][3] == pytest.approx(want, rel=1e-12)
+        # and it is none of its neighbours
+        assert abs(out["batch"][3] - out["batch"][2]) > 1e-3      # pooled micro
+        assert abs(out["batch"][3] - out["batch"][5]) > 1e-4      # field macro
+    # the candidate audit's micro field cosine is the same quantity at a shared window
+    a = O.audit_candidates(out["g"], pr["offsets"], (2,), O.RED_SEQ_MEAN)
+    n2 = np.minimum(2, lens)
+    S_2 = np.array([(out["g"][pr["offsets"][i]:pr["offsets"][i] + n2[i]] ** 2).sum() for i in range(len(lens))])
+    ap2, af2 = 1.0 / (len(lens) * n2), 1.0 / (len(lens) * lens)
+    want = (ap2 * af2 * S_2).sum() / math.sqrt((ap2 ** 2 * S_2).sum() * (af2 ** 2 * S_l).sum())
+    assert a["micro_field"][0] == pytest.approx(want, rel=1e-12)
+
+
+def test_macro_means_leave_out_rollouts_without_a_gradient():
+    """Reading of Sec. 4.2 / Fig. 5 "macro": the mean of the per-rollout cosines over the rollouts
+    whose two gradients are both non-zero.  Hand-built batch: rollout 0 regular, rollout 1 empty,
+    rollout 2 with window 0, rollout 3 whose gradient rows are all zero."""
+    H = 3
+    e = np.eye(H)
+    g = np.stack([e[0], e[1], e[1],            # rollout 0: len 3, window 1 -> field sqrt(1/3), pooled 1/sqrt(5)
+                  e[2], e[2],                  # rollout 2: len 2, window 0
+                  0 * e[0], 0 * e[0]])         # rollout 3: len 2, window 1, zero gradient
+    offsets = [0, 3, 3, 5, 7]
+    out = O.window_outputs(np.zeros(7), g, offsets, [1, 4, 0, 1])
+    assert out["rho_field"].tolist() == pytest.approx([math.sqrt(1 / 3), 0.0, 0.0, 0.0])
+    assert out["rho_pooled"].tolist() == pytest.approx([1 / math.sqrt(5), 0.0, 0.0, 0.0])
+    assert out["batch"][5] == pytest.approx(math.sqrt(1 / 3), rel=1e-12)     # not sqrt(1/3) / 4
+    assert out["batch"][4] == pytest.approx(1 / math.sqrt(5), rel=1e-12)
+    # a second regular rollout enters both means with weight 1/2
+    g2 = np.concatenate([g, np.stack([e[0], e[0], e[0], e[0]])])
+    out = O.window_outputs(np.zeros(11), g2, offsets + [11], [1, 4, 0, 1, 1])
+    assert out["batch"][5] == pytest.approx((math.sqrt(1 / 3) + 0.5) / 2, rel=1e-12)
+    assert out["batch"][4] == pytest.approx((1 / math.sqrt(5) + 1.0) / 2, rel=1e-12)
+
+
+def test_logits_given_sampled_estimator_agrees_with_hidden_state_path():
+    """Eq. 4 on the sampled token through the logits-given variant: dz[t] = grad_scale a^p_i c_t
+    (e_{y_t} - p_s), so dz W_s must be the dh_prefix of the hidden-state path under the same
+    estimator, weights included (sequence-mean reduction, grad_scale != 1)."""
+    pr, lens = _small_problem(13, B=4)
+    window = np.array([2, 1, 5, 3])
+    z_s, z_t = pr["h_s"] @ pr["W_s"].T, pr["h_t"] @ pr["W_t"].T
+    a = O.supervise(**pr, window=window, mode=O.MODE_PREFIX_ONLY, reduction=O.RED_SEQ_MEAN,
+                    grad_scale=-1.75, estimator=O.EST_SAMPLED)
+    b = O.supervise_from_logits(z_s, z_t, pr["ids"], pr["offsets"], window, reduction=O.RED_SEQ_MEAN,
+                                grad_scale=-1.75, estimator=O.EST_SAMPLED)
+    assert np.abs(a["dh_prefix"]).max() > 1e-3
+    assert np.allclose(b["dz"] @ pr["W_s"], a["dh_prefix"], rtol=1e-10, atol=1e-15)
+    assert np.allclose(a["kl"], b["kl"], rtol=1e-12) and np.allclose(a["c"], b["c"], rtol=1e-12)
+    # row by row: the weight is that of the row's own rollout, the score that of its own token
+    n = np.minimum(window, lens)
+    for i in range(4):
+        for j in range(int(lens[i])):
+            t = int(pr["offsets"][i]) + j
+            if j < n[i]:
+                p = scipy.special.softmax(z_s[t])
+                c = scipy.special.log_softmax(z_s[t])[pr["ids"][t]] - scipy.special.log_softmax(z_t[t])[pr["ids"][t]]
+                want = -1.75 / (4 * n[i]) * c * (np.eye(len(p))[pr["ids"][t]] - p)
+                assert np.allclose(b["dz"][t], want, rtol=1e-11, atol=1e-16)
+            else:
+                assert not b["dz"][t].any()
+    # the expected-gradient variant is a different array
+    e = O.supervise_from_logits(z_s, z_t, pr["ids"], pr["offsets"], window, reduction=O.RED_SEQ_MEAN,
+                                grad_scale=-1.75)
+    assert np.abs(e["dz"] - b["dz"]).max() > 1e-3
+
+
 def test_logits_given_variant_agrees_with_hidden_state_path():
     pr, lens = _small_problem(8, B=3)
     window = np.array([2, 1, 4])
@@ -471,16 +560,9 @@ def test_head_weight_gradient_finite_differences():
     same = O.supervise(h_s, h_s, W_s, W_s, None, offsets, window, mode=O.MODE_PREFIX_AND_FULL,
                        head_gradient=True)
     assert np.abs(same["dW_full"]).max() < 1e-15
-    # the summand norm: one admitted token -> the norm is the summand itself; in general it lies
-    # between |dW| / sqrt(#summands) and the sum of magnitudes
     one = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.array([1, 0]), reduction=O.RED_SUM,
                       head_gradient=True)
-    sc = np.stack([O.token_dz_scale(W_s @ h_s[t], W_t @ h_t[t]) for t in range(T)])
-    assert np.allclose(one["dW_prefix_l2"], np.outer(sc[0], np.abs(h_s[0])), rtol=1e-12)
-    assert np.allclose(one["dW_prefix"], np.outer(dz[0], h_s[0]), rtol=1e-12)
-    l1 = sc.T @ np.abs(h_s)
-    assert (out["dW_full_l2"] <= l1 + 1e-15).all()
-    assert (np.abs(out["dW_full"]) <= np.sqrt(T) * out["dW_full_l2"] + 1e-15).all()
+    assert np.allclose(one["dW_prefix"], np.outer(dz[0], h_s[0]), rtol=1e-12)      # one admitted token
 
 
 def test_teacher_diagnostics():
@@ -560,46 +642,6 @@ def test_head_block_alignment():
     none = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.zeros(3, int), mode=O.MODE_PREFIX_AND_FULL,
                        head_gradient=True)
     assert none["rho_head"] == 0.0
-
-
-def test_summand_norms_of_the_hidden_gradient():
-    V, Hs, Ht = 6, 3, 4
-    W_s, W_t = RNG.normal(0, 0.7, (V, Hs)), RNG.normal(0, 0.7, (V, Ht))
-    offsets = np.array([0, 3]); h_s, h_t = RNG.normal(0, 1, (3, Hs)), RNG.normal(0, 1, (3, Ht))
-    out = O.supervise(h_s, h_t, W_s, W_t, None, offsets, np.array([2]), summand_norms=True)
-    for t in range(3):
-        dz = O.token_dz_scale(W_s @ h_s[t], W_t @ h_t[t])
-        for k in range(Hs):
-            terms = dz * W_s[:, k]
-            want = math.sqrt(sum(x * x for x in terms)) if t < 2 else 0.0
-            assert out["g_l2"][t, k] == pytest.approx(want, rel=1e-12)
-            if t < 2:
-                assert abs(out["g"][t, k]) <= math.sqrt(V) * out["g_l2"][t, k] + 1e-15
-
-
-def test_error_scale_of_the_logit_gradient():
-    # p (|Delta - KL| + D): two-entry closed form, dominance over |dz|, zero for equal models
-    a, b = 0.8, 0.3                                   # p_s = (a, 1-a), p_t = (b, 1-b)
-    z_s, z_t = np.log([a, 1 - a]), np.log([b, 1 - b])
-    delta = np.array([math.log(a / b), math.log((1 - a) / (1 - b))])
-    kl = a * delta[0] + (1 - a) * delta[1]
-    dev = math.sqrt(a * (delta[0] - kl) ** 2 + (1 - a) * (delta[1] - kl) ** 2)
-    want = np.array([a, 1 - a]) * (np.abs(delta - kl) + dev)
-    assert np.allclose(O.token_dz_scale(z_s, z_t), want, rtol=1e-12)
-    assert np.allclose(O.token_dz_scale(z_s + 3.0, z_t - 1.0), want, rtol=1e-12)     # shift invariance
-    for _ in range(5):
-        zs, zt = RNG.normal(0, 3, 11), RNG.normal(0, 3, 11)
-        assert (O.token_dz_scale(zs, zt) >= np.abs(O.token_dz(zs, zt)) - 1e-15).all()
-        assert np.abs(O.token_dz_scale(zs, zs + 2.5)).max() < 1e-12
-
-
-def test_error_scale_of_the_sampled_gradient():
-    zs, zt = RNG.normal(0, 3, 9), RNG.normal(0, 3, 9)
-    for y in (0, 4, 8):
-        sc, dz = O.token_dz_sampled_scale(zs, zt, y), O.token_dz_sampled(zs, zt, y)
-        c = abs(O.token_cost(zs, zt, y))
-        assert (sc >= np.abs(dz) - 1e-15).all()
-        assert sc[y] == pytest.approx(c) and sc.sum() == pytest.approx(c * (2 - np.exp(O.log_softmax(zs))[y]))
 
 
 def test_cosine_against_angles_and_the_zero_convention():
