@@ -279,7 +279,7 @@ int adwin_opd_version(void);
 
 /*
  * Optional per-device set-up: sets the kernel attributes (dynamic LDS sizes) of every kernel
- * on the current HIP device.  The entry points do this themselves on their first call on a
+ * on the current HIP device and looks up the address of the static scratch array there.  The entry points do this themselves on their first call on a
  * device; a caller that captures its first call in a HIP graph, or that makes first calls
  * from several threads at once, calls this once per device beforehand.  Idempotent; no
  * memory is allocated, nothing is enqueued.  Returns ADWIN_OK or ADWIN_E_HIP.
@@ -351,6 +351,25 @@ int adwin_opd_logits_workspace_bytes(const adwin_opd_logits_problem* p, size_t* 
  */
 int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* workspace,
                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * adwin_opd_from_logits for callers that cannot allocate device memory or size a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, checks, kernels and results as adwin_opd_from_logits, but the scratch (plan
+ * arrays, a KL copy per row, per-rollout accumulators) lives in a fixed array of
+ * ADWIN_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends;
+ * the call itself allocates nothing, on the device or through any library.  A problem whose
+ * adwin_opd_logits_workspace_bytes() exceeds that size is refused with ADWIN_E_WORKSPACE and
+ * nothing is enqueued (1 MiB covers T + 60 B up to about 260,000: e.g. 32 rollouts of 8,192
+ * rows).  Inputs and outputs are the caller's, as always.  Every call on a GPU uses that GPU's
+ * one array: calls that overlap in time on the same GPU (different streams, or threads) race
+ * and give undefined results; calls on one stream, or ordered by events, are fine, and nothing
+ * one call leaves in the array is read by the next.  The array's address is looked up on the
+ * first call on a device, or by adwin_opd_init: a caller that captures its first call in a HIP
+ * graph calls adwin_opd_init beforehand.
+ */
+#define ADWIN_STATIC_SCRATCH_BYTES (1 << 20)
+int adwin_opd_from_logits_static(const adwin_opd_logits_problem* p, void* hip_stream);
 
 /*
  * Profiling variants: identical work and results, but every kernel launch is bracketed

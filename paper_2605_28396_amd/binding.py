@@ -25,6 +25,7 @@ ADWIN_RED_SEQ_MEAN, ADWIN_RED_SUM, ADWIN_RED_TOKEN_MEAN = 0, 1, 2
 ADWIN_DT_BF16, ADWIN_DT_F32 = 0, 1
 ADWIN_DEV_BAD_ID, ADWIN_DEV_NONFINITE = 1, 2
 ADWIN_MAX_CANDIDATES = 16
+ADWIN_STATIC_SCRATCH_BYTES = 1 << 20
 ADWIN_EST_EXPECTED, ADWIN_EST_SAMPLED = 0, 1
 ADWIN_SCHEME_AUTO, ADWIN_SCHEME_SINGLE, ADWIN_SCHEME_TWO_SWEEP, ADWIN_SCHEME_TWO_SWEEP_REG = 0, 1, 2, 3
 ADWIN_LOGITS_AUTO, ADWIN_LOGITS_RESIDENT, ADWIN_LOGITS_STREAMING = 0, 1, 2
@@ -101,6 +102,8 @@ def _load() -> C.CDLL:
     lib.adwin_opd_from_logits.restype = C.c_int
     lib.adwin_opd_from_logits.argtypes = [C.POINTER(adwin_opd_logits_problem), C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+    lib.adwin_opd_from_logits_static.restype = C.c_int
+    lib.adwin_opd_from_logits_static.argtypes = [C.POINTER(adwin_opd_logits_problem), C.c_void_p]
     lib.adwin_opd_fused_profile.restype = C.c_int
     lib.adwin_opd_fused_profile.argtypes = [C.POINTER(adwin_opd_problem), C.c_void_p, C.c_size_t,
                                             C.c_void_p, C.POINTER(C.c_float)]
@@ -324,7 +327,8 @@ class LogitsCall:
 
     def __init__(self, z_s, z_t, ids, offsets, window, reduction=ADWIN_RED_SEQ_MEAN, grad_scale=1.0,
                  want=("kl", "c", "dz", "loss_prefix", "batch", "n_out", "n_adm_out", "status_dev"),
-                 allocate=True, estimator=ADWIN_EST_EXPECTED, topk=0, scheme=ADWIN_LOGITS_AUTO):
+                 allocate=True, estimator=ADWIN_EST_EXPECTED, topk=0, scheme=ADWIN_LOGITS_AUTO,
+                 workspace=True):
         self.offsets, self.window = _host_i64(offsets), _host_i32(window)
         self.inputs = (z_s, z_t, ids)
         B = int(self.window.shape[0])
@@ -358,7 +362,8 @@ class LogitsCall:
                 self.out[k] = torch.empty(shp, dtype=dt, device=dev)
                 setattr(p, k, _ptr(self.out[k]))
             self.workspace_bytes = adwin_opd_logits_workspace_bytes(p)
-            self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=dev)
+            if workspace:       # run_static() needs none
+                self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=dev)
 
     def _ws_ptr(self) -> int:
         return (int(self.workspace.data_ptr()) + 255) // 256 * 256
@@ -366,6 +371,10 @@ class LogitsCall:
     def run(self, stream=None) -> int:
         return int(lib.adwin_opd_from_logits(C.byref(self.p), self._ws_ptr(), self.workspace_bytes,
                                              _stream_handle(stream)))
+
+    def run_static(self, stream=None) -> int:
+        """The same call through the entry point that takes no workspace and allocates nothing."""
+        return int(lib.adwin_opd_from_logits_static(C.byref(self.p), _stream_handle(stream)))
 
 
 def adwin_opd_logits_workspace_bytes(p: adwin_opd_logits_problem) -> int:
@@ -377,6 +386,14 @@ def adwin_opd_logits_workspace_bytes(p: adwin_opd_logits_problem) -> int:
 def adwin_opd_from_logits(z_s, z_t, ids, offsets, window, stream=None, **kw) -> dict:
     call = LogitsCall(z_s, z_t, ids, offsets, window, **kw)
     _check(call.run(stream))
+    return call.out
+
+
+def adwin_opd_from_logits_static(z_s, z_t, ids, offsets, window, stream=None, **kw) -> dict:
+    """adwin_opd_from_logits with the library's own static scratch (outputs are still allocated
+    here, by torch; the library call itself allocates nothing)."""
+    call = LogitsCall(z_s, z_t, ids, offsets, window, workspace=False, **kw)
+    _check(call.run_static(stream))
     return call.out
 
 

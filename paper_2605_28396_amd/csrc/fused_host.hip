@@ -201,6 +201,7 @@ extern "C" int adwin_opd_init(void) {
   ADWIN_HIP_TRY(sweep_kernels_opt_in());
   ADWIN_HIP_TRY(grad_kernels_opt_in());
   ADWIN_HIP_TRY(logits_kernels_opt_in());
+  ADWIN_HIP_TRY(logits_static_setup());
   (void)first_use_on_device(0);      // the calls need not repeat it on this device
   (void)first_use_on_device(1);
   return ADWIN_OK;

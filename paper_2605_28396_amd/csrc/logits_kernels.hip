@@ -2,6 +2,7 @@
 // reverse KL (Eq. 2 at token level), sampled cost c_t (Sec. 2.3) and the logit gradient
 // p_s((z_s - z_t) - mu) (Eq. 4 in expectation, App. A.1) on the admitted rows
 // (Sec. 4.1), streamed from HBM.  One workgroup per packed row; two sweeps over the row.
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -544,6 +545,59 @@ static int logits_impl(const adwin_opd_logits_problem* p, void* workspace, size_
 extern "C" int adwin_opd_from_logits(const adwin_opd_logits_problem* p, void* workspace,
                                      size_t workspace_bytes, void* hip_stream) {
   return logits_impl(p, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+// ---------------------------------------------------------------------------------------
+// The entry point that allocates nothing: the same call with its scratch (plan blob,
+// per-row KL copy, per-rollout accumulators) in a fixed array inside the library.  Every GPU
+// holds its own copy of the array at its own address; the name `static_scratch` is only the
+// host-side handle of the symbol, so host code asks the runtime for the device address once per
+// device and uses that pointer from then on.  (No `used` attribute on the array: the compiler
+// makes a file-local device variable visible to the runtime's lookup by name only because host
+// code refers to it, and that attribute switches this off.)
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char static_scratch[ADWIN_STATIC_SCRATCH_BYTES];
+
+namespace adwin {
+
+static std::mutex g_static_mu;
+static void* g_static_ptr[64];          // device address of static_scratch, per device ordinal
+
+// Address of the current device's copy of static_scratch (looked up on first use per device).
+static hipError_t static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr || ((uintptr_t)ptr & 255)) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = ptr;
+  }
+  *out = g_static_ptr[dev];
+  return hipSuccess;
+}
+
+hipError_t logits_static_setup() {
+  void* ptr = nullptr;
+  return static_scratch_ptr(&ptr);
+}
+
+}  // namespace adwin
+
+extern "C" int adwin_opd_from_logits_static(const adwin_opd_logits_problem* p, void* hip_stream) {
+  int st = check_logits_problem(p);
+  if (st != ADWIN_OK) return st;
+  if (LogitsLayout(p->B, p->T).total > (size_t)ADWIN_STATIC_SCRATCH_BYTES) return ADWIN_E_WORKSPACE;
+  void* ptr = nullptr;
+  ADWIN_HIP_TRY(static_scratch_ptr(&ptr));
+  // Nothing in the scratch has to start at zero: every kernel of the call writes what a later
+  // one reads (the plan blob, KL of every admitted row, the per-rollout sums), so what the
+  // previous call left behind is never read.
+  return logits_impl(p, ptr, (size_t)ADWIN_STATIC_SCRATCH_BYTES, hip_stream, nullptr);
 }
 
 extern "C" int adwin_opd_from_logits_profile(const adwin_opd_logits_problem* p, void* workspace,

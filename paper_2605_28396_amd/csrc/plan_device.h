@@ -11,6 +11,8 @@ DevicePlan device_plan_at(unsigned char* ws_plan, int32_t B, int32_t* row_idx, i
 
 // large dynamic LDS of the row-resident logits kernel, once per device (logits_kernels.hip)
 hipError_t logits_kernels_opt_in();
+// looks up the current device's address of the library's static scratch array (logits_kernels.hip)
+hipError_t logits_static_setup();
 
 // --- launchers (all asynchronous on `st`) ---------------------------------------------
 hipError_t launch_build_rows(const DevicePlan& pl, int32_t B, int64_t n_rows, int64_t n_pad,
