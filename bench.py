@@ -233,6 +233,9 @@ def main() -> int:
             "config": {"workload": "logits_given", "rollouts": lg["rollouts"], "packed_rows": lg["packed_rows"],
                        "computed_rows": lg["computed_rows"], "V": lg["V"], "estimator": args.estimator},
             "roofline": lg["roofline"], "cpu_baseline": lg.get("cpu_baseline"), "parity": lg.get("parity"),
+            "ceilings": {"copy_GBps": B.adwin_opd_ceiling_copy(),
+                         "note": "measured on this box: the library's streaming copy of 1 GiB (read+write bytes); "
+                                 "it also calibrates the HBM counters of a profiling run"},
         }
         print(json.dumps(line))
         return 0

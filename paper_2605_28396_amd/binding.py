@@ -15,7 +15,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libadwin_opd.so")
+# ADWIN_OPD_LIB: load another build of the same library (A/B timing of kernel variants)
+LIB_PATH = os.environ.get("ADWIN_OPD_LIB") or os.path.join(_HERE, "libadwin_opd.so")
 
 ADWIN_OK = 0
 ADWIN_E_NULL, ADWIN_E_SHAPE, ADWIN_E_OFFSETS, ADWIN_E_WINDOW = -1, -2, -3, -4

@@ -232,6 +232,7 @@ constexpr int kResIters = 75;                      // vectors of 8 logits per th
 constexpr int kResTLds = 39;                       // of which z_t vectors parked in LDS
 constexpr int kResTReg = kResIters - kResTLds;     // and in registers
 constexpr int kResBatch = 5;                       // iterations whose loads are issued together
+constexpr int kResDepth = 1;                       // batches in flight ahead of the arithmetic (2 and 3: no faster)
 constexpr int kResVec = kResIters * kResThreads;   // 19,200 vectors = 153,600 logits
 constexpr int kResLdsBytes = kResTLds * kResThreads * 16 + 256;
 
@@ -244,6 +245,27 @@ __device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>
 template <int N, typename F>
 __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+// Row access through buffer descriptors: base = the row, extent = its bytes.  Every 16-byte
+// access is then one instruction with a lane offset shared by all of them (16 * thread index)
+// and a scalar offset per iteration, no 64-bit address per access to compute or to keep in
+// vector registers (with 150 accesses per sweep those addresses, computed ahead by the
+// compiler, crowded the row itself out of the register file); an access beyond the extent reads
+// zeros / is dropped by the hardware, which is what the ragged last iteration needs.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t row_rsrc(const void* row, int bytes) {
+  // flag word: the raw-buffer setting of the gfx9 family (32-bit data format, no swizzle)
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(row), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 row_load16(__amdgpu_buffer_rsrc_t r, int lane_off, int iter_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, iter_off, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void row_store16(__amdgpu_buffer_rsrc_t r, int lane_off, int iter_off, const uint4& v) {
+  u32x4 x;
+  x.x = v.x; x.y = v.y; x.z = v.z; x.w = v.w;
+  __builtin_amdgcn_raw_buffer_store_b128(x, r, lane_off, iter_off, 0);
 }
 
 struct RowStats { float ms, Zs, A, mt, Zt; };
@@ -319,37 +341,39 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
   uint4 rt[kResTReg];
   RowStats st = {kNegBig, 0.f, 0.f, kNegBig, 0.f};
   // ---- sweep 1: load the row pair once, keep it, accumulate the statistics ------------
-  // Loads are issued one batch (kResBatch iterations) ahead of the arithmetic so that the
-  // single wave per SIMD always has 2*kResBatch 16-byte loads in flight.  They are
-  // unconditional (out-of-range lanes fetch the row's last vector and use a neutral value)
-  // so that the number of loads in flight is the same on every path and the compiler can
-  // wait for exactly the ones it needs.
-  uint4 tb[2][kResBatch];
-  const int last = nvec - 1;
+  // Loads are issued kResDepth batches (of kResBatch iterations) ahead of the arithmetic, so
+  // that the single wave per SIMD always has 2 * kResBatch 16-byte loads in flight per lane.
+  // z_s vectors and the register-resident z_t vectors land in their final registers (the
+  // loads write accumulation registers directly); the z_t vectors that go to the LDS pass
+  // through a small staging ring.  Lanes beyond the row read zeros and take a neutral value.
+  const int row_bytes = nvec * 16, lane_off = tid * 16;
+  const __amdgpu_buffer_rsrc_t bs = row_rsrc(zs, row_bytes), bt = row_rsrc(zt, row_bytes);
+  uint4 tb[kResDepth + 1][kResBatch];
   auto issue = [&](auto b_c) {
     constexpr int b = decltype(b_c)::value;
     if constexpr (b < kResIters / kResBatch) {
       static_for<kResBatch>([&](auto g_c) {
         constexpr int g = decltype(g_c)::value;
-        int q = (b * kResBatch + g) * kResThreads + tid;
-        q = q < last ? q : last;
-        rs[b * kResBatch + g] = zs[q];
-        tb[b & 1][g] = zt[q];
+        constexpr int it = b * kResBatch + g;
+        rs[it] = row_load16(bs, lane_off, it * kResThreads * 16);
+        if constexpr (it < kResTLds) tb[b % (kResDepth + 1)][g] = row_load16(bt, lane_off, it * kResThreads * 16);
+        else rt[it - kResTLds] = row_load16(bt, lane_off, it * kResThreads * 16);
       });
     }
   };
-  issue(std::integral_constant<int, 0>{});
+  static_for<kResDepth>([&](auto b_c) { issue(b_c); });
   static_for<kResIters / kResBatch>([&](auto b_c) {
     constexpr int b = decltype(b_c)::value;
-    issue(std::integral_constant<int, b + 1>{});
+    issue(std::integral_constant<int, b + kResDepth>{});
     if (b * kResBatch * kResThreads < nvec) {
       static_for<kResBatch>([&](auto g_c) {
         constexpr int g = decltype(g_c)::value;
         constexpr int it = b * kResBatch + g;
         const bool in = it * kResThreads + tid < nvec;
-        uint4 qs = rs[it], qt = tb[b & 1][g];
+        uint4 qs = rs[it], qt;
+        if constexpr (it < kResTLds) qt = tb[b % (kResDepth + 1)][g]; else qt = rt[it - kResTLds];
         if (!in) { qs = neutral; qt = neutral; }
-        if constexpr (it < kResTLds) lds_t[it * kResThreads + tid] = qt; else rt[it - kResTLds] = qt;
+        if constexpr (it < kResTLds) lds_t[it * kResThreads + tid] = qt;
         stats_update(st, qs, qt);
       });
     }
@@ -413,14 +437,13 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
   const float sg = k_s < 0.f ? -1.f : 1.f;
   const float sgn = a.sampled ? 0.f : sg;
   const float lse2 = sh[20] - log2f(fabsf(k_s)), nmu = a.sampled ? -sg : -sg * sh[21];
+  const __amdgpu_buffer_rsrc_t bd = row_rsrc(dzr, row_bytes);
   static_for<kResIters>([&](auto it_c) {
     constexpr int it = decltype(it_c)::value;
     if (it * kResThreads < nvec) {
-      const int q = it * kResThreads + tid;
       uint4 qt;
       if constexpr (it < kResTLds) qt = lds_t[it * kResThreads + tid]; else qt = rt[it - kResTLds];
-      const uint4 o = dz_vector(rs[it], qt, lse2, sgn, nmu);
-      if (q < nvec) nt_store16(dzr + q, o);
+      row_store16(bd, lane_off, it * kResThreads * 16, dz_vector(rs[it], qt, lse2, sgn, nmu));
     }
   });
   for (int q = kResVec + tid; q < nvec; q += kResThreads)
