@@ -9,7 +9,7 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
                                                    int64_t n) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-    nt_store16(dst + i, src[i]);
+    store16(dst + i, src[i]);
 }
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));

@@ -23,7 +23,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 
 // 16-byte store.  Plain (write-back) stores measured faster than non-temporal ones on
 // MI355X: 6.8 TB/s against 4.6 TB/s for a pure fill.
-__device__ __forceinline__ void nt_store16(uint4* p, const uint4& v) { *p = v; }
+__device__ __forceinline__ void store16(uint4* p, const uint4& v) { *p = v; }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 

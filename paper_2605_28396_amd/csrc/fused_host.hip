@@ -300,12 +300,12 @@ static int fused_impl(const adwin_opd_problem* p, void* workspace, size_t worksp
       // tile images of the logit operands: vocabulary tiles of 128 rows (zero beyond V),
       // token tiles of 256 computed rows gathered through row_idx
       RowImageArgs ia;
-      ia.row_idx = nullptr; ia.n_rows = p->V; ia.th = kTileVocab;
+      ia.row_idx = nullptr; ia.n_rows = p->V; ia.th = kTileVocab; ia.permute = 1;
       ia.src = (const uint4*)p->W_t; ia.img = (uint4*)(ws + L.o_wt_img); ia.H = p->H_t; ia.nk = p->H_t / kBK;
       ADWIN_HIP_TRY(launch_row_image(ia, (unsigned)vt_total, stream));
       ia.src = (const uint4*)p->W_s; ia.img = (uint4*)(ws + L.o_ws_img); ia.H = p->H_s; ia.nk = p->H_s / kBK;
       ADWIN_HIP_TRY(launch_row_image(ia, (unsigned)vt_total, stream));
-      ia.row_idx = pl.row_idx; ia.n_rows = n_pad; ia.th = kTileTokens;
+      ia.row_idx = pl.row_idx; ia.n_rows = n_pad; ia.th = kTileTokens; ia.permute = 0;
       ia.src = (const uint4*)p->h_t; ia.img = (uint4*)(ws + L.o_ht_img); ia.H = p->H_t; ia.nk = p->H_t / kBK;
       ADWIN_HIP_TRY(launch_row_image(ia, (unsigned)n_tiles, stream));
       ia.src = (const uint4*)p->h_s; ia.img = (uint4*)(ws + L.o_hs_img); ia.H = p->H_s; ia.nk = p->H_s / kBK;

@@ -131,6 +131,7 @@ constexpr int kModeSingleFwdDiag = 7; // the same plus the diagnostics
 struct RowImageArgs {
   const uint4* src; uint4* img; const int32_t* row_idx;
   int64_t n_rows; int H, nk, th;
+  int permute;     // rows of every group of 32 in the order the logit kernels' epilogues want (W tiles)
 };
 
 // Merge of the strip partials into lse, mu, KL_t and c_t.

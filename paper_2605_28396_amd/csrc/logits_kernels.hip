@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
   if (j >= a.pl.n[i]) {   // outside the window: zero gradient row, zero KL
     if (dzr) {
       const uint4 z = {0u, 0u, 0u, 0u};
-      for (int q = tid; q < nvec; q += kRowThreads) nt_store16(dzr + q, z);
+      for (int q = tid; q < nvec; q += kRowThreads) store16(dzr + q, z);
     }
     if (tid == 0) {
       if (a.kl) a.kl[t] = 0.f;
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
   if (!dzr) return;
   if (bc[4] != 0.f) {
     const uint4 z = {0u, 0u, 0u, 0u};
-    for (int q = tid; q < nvec; q += kRowThreads) nt_store16(dzr + q, z);
+    for (int q = tid; q < nvec; q += kRowThreads) store16(dzr + q, z);
     return;
   }
   // ---- sweep 2: dz = scale * p_s * ((z_s - z_t) - mu), or scale * c_t * (e_y - p_s) ---
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kRowThreads) void logits_row_kernel(LogitsArgs a) {
     o.y = pack_bf16(d[2], d[3]);
     o.z = pack_bf16(d[4], d[5]);
     o.w = pack_bf16(d[6], d[7]);
-    nt_store16(dzr + q, o);
+    store16(dzr + q, o);
   }
   if (a.sampled) {
     __syncthreads();
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
   if (j >= a.pl.n[i]) {
     if (dzr) {
       const uint4 z = {0u, 0u, 0u, 0u};
-      for (int q = tid; q < nvec; q += kResThreads) nt_store16(dzr + q, z);
+      for (int q = tid; q < nvec; q += kResThreads) store16(dzr + q, z);
     }
     if (tid == 0) {
       if (a.kl) a.kl[t] = 0.f;
@@ -426,7 +426,7 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
   if (!dzr) return;
   if (sh[24] != 0.f) {
     const uint4 z = {0u, 0u, 0u, 0u};
-    for (int q = tid; q < nvec; q += kResThreads) nt_store16(dzr + q, z);
+    for (int q = tid; q < nvec; q += kResThreads) store16(dzr + q, z);
     return;
   }
   // ---- sweep 2: dz from the resident copy ----------------------------------------------
@@ -447,7 +447,7 @@ __global__ __launch_bounds__(kResThreads, 1) void logits_row_resident_kernel(Log
     }
   });
   for (int q = kResVec + tid; q < nvec; q += kResThreads)
-    nt_store16(dzr + q, dz_vector(zs[q], zt[q], lse2, sgn, nmu));
+    store16(dzr + q, dz_vector(zs[q], zt[q], lse2, sgn, nmu));
   if (a.sampled) {
     __syncthreads();
     if (tid == 0 && a.ids) {

@@ -17,6 +17,11 @@
 // with i in registers and j = lane % 32.  A = W tile (i = vocabulary) and B = h tile
 // (j = token), so each lane owns one token column and the reduction over the vocabulary
 // runs down its own registers with no cross-lane traffic.
+// A lane holds rows i = 8 (e / 4) + 4 (lane / 32) + e % 4 of a 32 x 32 block, e = 0..15.  The
+// W tiles are staged with their rows permuted inside every group of 32 (tile_row_of_entry), so
+// that these are 16 consecutive vocabulary entries, 16 (lane / 32) + e: a lane then owns 32
+// consecutive bytes of a slab row per block and writes them with two 16-byte stores, where the
+// natural order gives it four separate 8-byte pieces.
 #include "fused_shared.h"
 
 namespace adwin {
@@ -46,6 +51,12 @@ struct RowStager {
 __device__ __forceinline__ int stage_thread_off(int tid) {
   const int r = tid >> 3, c = tid & 7;
   return r * kRowBytes + ((c ^ ((r >> 1) & 7)) << 4);
+}
+
+// Row order of the staged W tiles: tile row 8 q + 4 h + r of a group of 32 holds vocabulary entry
+// 16 h + 4 q + r of the group (q = 0..3, h = 0..1, r = 0..3).
+__device__ __forceinline__ int entry_of_tile_row(int i) {
+  return (i & ~31) + 16 * ((i >> 2) & 1) + 4 * ((i >> 3) & 3) + (i & 3);
 }
 
 // acc[FM][FN] += A_tile(wave rows) * B_tile(wave rows)^T for one staged k-step of 64.
@@ -109,11 +120,11 @@ __device__ __forceinline__ void gemm_kloop(f32x16 (&acc)[FM][FN], RowStager<RA>&
 // Running per-token statistics held by one lane for its two token columns.
 struct LaneStats { float m_s[2], Z_s[2], A_s[2], m_t[2], Z_t[2]; };
 
-// Element e of block fm sits at vocabulary row v0 + fm*32 + 8*(e/4) + 4*(lane/32) + e%4.
+// Element e of block fm is vocabulary entry v0 + fm*32 + 16*(lane/32) + e.
 // Online update of (m_s, Z_s, A, m_t, Z_t) with one 128 x 64 logit tile per wave.
 __device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                LaneStats& st, int v0, int V, bool tail, int lane) {
-  const int vlane = v0 + 4 * (lane >> 5);
+  const int vlane = v0 + 16 * (lane >> 5);
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
     float mxs = st.m_s[fn], mxt = st.m_t[fn];
@@ -121,7 +132,7 @@ __device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < V;
+        const bool ok = !tail || (vlane + fm * 32 + e) < V;
         if (ok) { mxs = fmaxf(mxs, zs[fm][fn][e]); mxt = fmaxf(mxt, zt[fm][fn][e]); }
       }
     const float scs = fast_exp2((st.m_s[fn] - mxs) * kLog2e);
@@ -132,7 +143,7 @@ __device__ __forceinline__ void stats_epilogue(const f32x16 (&zs)[4][2], const f
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const bool ok = !tail || (vlane + fm * 32 + 8 * (e >> 2) + (e & 3)) < V;
+        const bool ok = !tail || (vlane + fm * 32 + e) < V;
         const float s = zs[fm][fn][e], t = zt[fm][fn][e];
         float es = fast_exp2(fmaf(s, kLog2e, -ms2));
         float et = fast_exp2(fmaf(t, kLog2e, -mt2));
@@ -152,30 +163,31 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
                                             const float (&lse2)[2], const float (&mu)[2], __bf16* blk,
                                             int wrow, int v0, int V, bool tail, int lane,
                                             const HeavyList& heavy, int64_t crow) {
-  const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
+  // chunk c = 4 (fm & 1) + 2 half + p of slab block fm / 2 holds the lane's entries 8 p .. 8 p + 7
+  // of block fm; its position in the row is c ^ key = (4 (fm & 1) + p) ^ key2
+  const int half = lane >> 5, vlane = v0 + 16 * half, key2 = ((lane >> 1) & 7) ^ (2 * half);
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
-    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK + 4 * half;
+    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK;
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float d[4];
-        const bool in = !tail || vlane + fm * 32 + 8 * q < V;
+      for (int p = 0; p < 2; ++p) {
+        float d[8];
+        const bool in = !tail || vlane + fm * 32 + 8 * p < V;      // V is a multiple of 8
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
-          const float p = fast_exp2(fmaf(s, kLog2e, -lse2[fn]));
-          d[e] = p * ((s - t) - mu[fn]);
-          if (__builtin_expect(p >= kHeavyP && in, 0)) {
-            if (heavy_push(heavy, crow + fn * 32 + (lane & 31), vlane + fm * 32 + 8 * q + e)) d[e] = 0.f;
+        for (int e = 0; e < 8; ++e) {
+          const float s = zs[fm][fn][p * 8 + e], t = zt[fm][fn][p * 8 + e];
+          const float pr = fast_exp2(fmaf(s, kLog2e, -lse2[fn]));
+          d[e] = in ? pr * ((s - t) - mu[fn]) : 0.f;
+          if (__builtin_expect(pr >= kHeavyP && in, 0)) {
+            if (heavy_push(heavy, crow + fn * 32 + (lane & 31), vlane + fm * 32 + 8 * p + e)) d[e] = 0.f;
           }
         }
-        if (tail && vlane + fm * 32 + 8 * q >= V) { d[0] = d[1] = d[2] = d[3] = 0.f; }
-        uint2 o;
-        o.x = pack_bf16(d[0], d[1]);
-        o.y = pack_bf16(d[2], d[3]);
-        *(uint2*)(out + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3)) = o;
+        uint4 o;
+        o.x = pack_bf16(d[0], d[1]); o.y = pack_bf16(d[2], d[3]);
+        o.z = pack_bf16(d[4], d[5]); o.w = pack_bf16(d[6], d[7]);
+        *(uint4*)(out + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + p) ^ key2) << 3)) = o;
       }
   }
 }
@@ -199,22 +211,23 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
                                                 const float (&zyt)[2], const int (&yid)[2],
                                                 __bf16* blk, int64_t e2_off, int wrow,
                                                 int v0, int V, int lane, float* mu0_out) {
-  const int half = lane >> 5, vlane = v0 + 4 * half, key = (lane >> 1) & 7;
+  // lane's entries of block fm: v0 + fm*32 + 16*half + e, e = 0..15; chunk positions as in dz_epilogue
+  const int half = lane >> 5, vlane = v0 + 16 * half, key2 = ((lane >> 1) & 7) ^ (2 * half);
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
-    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK + 4 * half;
+    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK;
     float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn], Bt = sm.B_t[fn];
     int cnt = sm.cnt[fn];
     const int vy = yid[fn] - vlane;        // position of the sampled token among this lane's entries
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float e2[4];
-        const bool ok = !TAIL || (vlane + fm * 32 + 8 * q) < V;
+      for (int p = 0; p < 2; ++p) {
+        float e2[8];
+        const bool ok = !TAIL || (vlane + fm * 32 + 8 * p) < V;      // V is a multiple of 8
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float s = zs[fm][fn][q * 4 + e], t = zt[fm][fn][q * 4 + e];
+        for (int e = 0; e < 8; ++e) {
+          const float s = zs[fm][fn][p * 8 + e], t = zt[fm][fn][p * 8 + e];
           float es = fast_exp2(fmaf(s, kLog2e, -rs2[fn]));
           float et = fast_exp2(fmaf(t, kLog2e, -rt2[fn]));
           float d = s - t;
@@ -224,14 +237,16 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
           Zt += et;
           if (DIAG) {
             Bt = fmaf(et, t, Bt);
-            cnt += (t > zyt[fn] && (fm * 32 + 8 * q + e) != vy && ok) ? 1 : 0;
+            cnt += (t > zyt[fn] && (fm * 32 + 8 * p + e) != vy && ok) ? 1 : 0;
           }
           e2[e] = es;
         }
-        uint2 o2;
-        o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
-        const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
-        if (WRITE_E2) *(uint2*)(out + e2_off + at) = o2;
+        if (WRITE_E2) {
+          uint4 o2;
+          o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
+          o2.z = pack_bf16(e2[4], e2[5]); o2.w = pack_bf16(e2[6], e2[7]);
+          *(uint4*)(out + e2_off + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + p) ^ key2) << 3)) = o2;
+        }
       }
     sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
     if (DIAG) { sm.B_t[fn] = Bt; sm.cnt[fn] = cnt; }
@@ -249,14 +264,14 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
 #pragma unroll
       for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float dd[4];
+        for (int p = 0; p < 2; ++p) {
+          float dd[8];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) dd[e] = (zs[fm][fn][q * 4 + e] - m0) - zt[fm][fn][q * 4 + e];
-          uint2 o1;
+          for (int e = 0; e < 8; ++e) dd[e] = (zs[fm][fn][p * 8 + e] - m0) - zt[fm][fn][p * 8 + e];
+          uint4 o1;
           o1.x = pack_bf16(dd[0], dd[1]); o1.y = pack_bf16(dd[2], dd[3]);
-          const int at = (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + q) ^ key) << 3);
-          *(uint2*)(out + at) = o1;
+          o1.z = pack_bf16(dd[4], dd[5]); o1.w = pack_bf16(dd[6], dd[7]);
+          *(uint4*)(out + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + p) ^ key2) << 3)) = o1;
         }
     }
   }
@@ -356,7 +371,7 @@ __global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
       const int r = tid >> 3, c = tid & 7;
 #pragma unroll
       for (int i = 0; i < kTileVocab / 32; ++i) {
-        int v = v0 + r + 32 * i;
+        int v = v0 + entry_of_tile_row(r + 32 * i);   // staged row order, see entry_of_tile_row
         v = v < a.V ? v : a.V - 1;               // tail rows: load a valid row, masked below
         ws.p[i] = (const uint4*)(a.W_s + (int64_t)v * a.H_s) + c;
         wt.p[i] = (const uint4*)(a.W_t + (int64_t)v * a.H_t) + c;
@@ -406,7 +421,8 @@ constexpr int kDmaPerWave = (kTileVocab + kTileTokens) / 8 / 4;   // 12 wave-loa
 // `th` consecutive rows; block (tile, kt) holds their k-entries 64 kt .. 64 kt + 63, row r at
 // r * 128 B, its 16-byte chunk c at chunk position c ^ ((r >> 1) & 7); rows >= n_rows are
 // zero.  Blocks of one tile are consecutive in kt.  Every wave-load then moves 1 KiB of
-// consecutive bytes and no operand needs 32-bit lane offsets from its base.
+// consecutive bytes and no operand needs 32-bit lane offsets from its base.  With `permute`
+// (the W operands) tile row r holds source row entry_of_tile_row(r) of the tile.
 
 __global__ __launch_bounds__(256) void row_image_kernel(RowImageArgs a) {
   const int kt = blockIdx.x;
@@ -414,7 +430,7 @@ __global__ __launch_bounds__(256) void row_image_kernel(RowImageArgs a) {
   uint4* blk = a.img + ((tile * a.nk + kt) * a.th) * 8;
   for (int q = threadIdx.x; q < a.th * 8; q += 256) {
     const int r = q >> 3, pos = q & 7, c = pos ^ ((r >> 1) & 7);
-    const int64_t row = tile * a.th + r;
+    const int64_t row = tile * a.th + (a.permute ? entry_of_tile_row(r) : r);
     uint4 v = {0u, 0u, 0u, 0u};
     if (row < a.n_rows) {
       const int64_t src_row = a.row_idx ? (int64_t)a.row_idx[row] : row;
