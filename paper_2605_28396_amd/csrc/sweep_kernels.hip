@@ -204,6 +204,30 @@ __device__ __forceinline__ void dz_epilogue(const f32x16 (&zs)[4][2], const f32x
 // only maintained in diagnostics mode.
 struct LaneSums { float Z_s[2], A_s[2], Z_t[2], B_t[2]; int cnt[2]; };
 
+// One accumulator element for vector arithmetic.  The operand constraint keeps the accumulators
+// in their registers up to the read: left alone, the register allocator moves blocks of them
+// about (and one into scratch memory) during the epilogue, and every reload from scratch waits
+// for all the stores in flight.
+__device__ __forceinline__ float acc_read(const float& a) {
+  float v;
+  asm("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+  return v;
+}
+
+// The two slab blocks of a logit tile through a buffer descriptor: the lane's offset is one
+// 32-bit register and the block, the token column group and the chunk are immediates or
+// scalars, so the stores need no 64-bit address registers.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_rsrc(__bf16* blk) {
+  return __builtin_amdgcn_make_buffer_rsrc(blk, 0, 2 * kImgBytesSlab, 0x00020000);
+}
+__device__ __forceinline__ void slab_store16(__amdgpu_buffer_rsrc_t r, int lane_off, int block_off, const float (&x)[8]) {
+  u32x4 o;
+  o.x = pack_bf16(x[0], x[1]); o.y = pack_bf16(x[2], x[3]);
+  o.z = pack_bf16(x[4], x[5]); o.w = pack_bf16(x[6], x[7]);
+  __builtin_amdgcn_raw_buffer_store_b128(o, r, lane_off, block_off, 0);
+}
+
 template <bool TAIL, bool DIAG, bool WRITE_D, bool WRITE_E2>
 __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const f32x16 (&zt)[4][2],
                                                 LaneSums& sm, const float (&rs2)[2],
@@ -213,9 +237,11 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
                                                 int v0, int V, int lane, float* mu0_out) {
   // lane's entries of block fm: v0 + fm*32 + 16*half + e, e = 0..15; chunk positions as in dz_epilogue
   const int half = lane >> 5, vlane = v0 + 16 * half, key2 = ((lane >> 1) & 7) ^ (2 * half);
+  // byte offset of chunk cb of the lane's row (fn = 0, first block): rowb ^ (cb << 4)
+  const int rowb = (wrow + (lane & 31)) * kRowBytes + (key2 << 4);
+  const __amdgpu_buffer_rsrc_t rd = slab_rsrc(blk), re = slab_rsrc(blk + e2_off);
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
-    __bf16* out = blk + (wrow + fn * 32 + (lane & 31)) * kBK;
     float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn], Bt = sm.B_t[fn];
     int cnt = sm.cnt[fn];
     const int vy = yid[fn] - vlane;        // position of the sampled token among this lane's entries
@@ -227,7 +253,7 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
         const bool ok = !TAIL || (vlane + fm * 32 + 8 * p) < V;      // V is a multiple of 8
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float s = zs[fm][fn][p * 8 + e], t = zt[fm][fn][p * 8 + e];
+          const float s = acc_read(zs[fm][fn][p * 8 + e]), t = acc_read(zt[fm][fn][p * 8 + e]);
           float es = fast_exp2(fmaf(s, kLog2e, -rs2[fn]));
           float et = fast_exp2(fmaf(t, kLog2e, -rt2[fn]));
           float d = s - t;
@@ -241,12 +267,8 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
           }
           e2[e] = es;
         }
-        if (WRITE_E2) {
-          uint4 o2;
-          o2.x = pack_bf16(e2[0], e2[1]); o2.y = pack_bf16(e2[2], e2[3]);
-          o2.z = pack_bf16(e2[4], e2[5]); o2.w = pack_bf16(e2[6], e2[7]);
-          *(uint4*)(out + e2_off + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + p) ^ key2) << 3)) = o2;
-        }
+        if (WRITE_E2)
+          slab_store16(re, rowb ^ (((fm & 1) * 4 + p) << 4), (fm >> 1) * kImgBytesSlab + fn * 32 * kRowBytes, e2);
       }
     sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
     if (DIAG) { sm.B_t[fn] = Bt; sm.cnt[fn] = cnt; }
@@ -267,11 +289,9 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
         for (int p = 0; p < 2; ++p) {
           float dd[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) dd[e] = (zs[fm][fn][p * 8 + e] - m0) - zt[fm][fn][p * 8 + e];
-          uint4 o1;
-          o1.x = pack_bf16(dd[0], dd[1]); o1.y = pack_bf16(dd[2], dd[3]);
-          o1.z = pack_bf16(dd[4], dd[5]); o1.w = pack_bf16(dd[6], dd[7]);
-          *(uint4*)(out + (fm >> 1) * kSlabBlock + ((((fm & 1) * 4 + p) ^ key2) << 3)) = o1;
+          for (int e = 0; e < 8; ++e)
+            dd[e] = (acc_read(zs[fm][fn][p * 8 + e]) - m0) - acc_read(zt[fm][fn][p * 8 + e]);
+          slab_store16(rd, rowb ^ (((fm & 1) * 4 + p) << 4), (fm >> 1) * kImgBytesSlab + fn * 32 * kRowBytes, dd);
         }
     }
   }
