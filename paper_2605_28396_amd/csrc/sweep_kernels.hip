@@ -240,60 +240,82 @@ __device__ __forceinline__ void single_epilogue(const f32x16 (&zs)[4][2], const 
   // byte offset of chunk cb of the lane's row (fn = 0, first block): rowb ^ (cb << 4)
   const int rowb = (wrow + (lane & 31)) * kRowBytes + (key2 << 4);
   const __amdgpu_buffer_rsrc_t rd = slab_rsrc(blk), re = slab_rsrc(blk + e2_off);
+  float Zs[2], As[2], Zt[2], Bt[2];
+  int cnt[2], vy[2];
 #pragma unroll
   for (int fn = 0; fn < 2; ++fn) {
-    float Zs = sm.Z_s[fn], As = sm.A_s[fn], Zt = sm.Z_t[fn], Bt = sm.B_t[fn];
-    int cnt = sm.cnt[fn];
-    const int vy = yid[fn] - vlane;        // position of the sampled token among this lane's entries
+    Zs[fn] = sm.Z_s[fn]; As[fn] = sm.A_s[fn]; Zt[fn] = sm.Z_t[fn]; Bt[fn] = sm.B_t[fn];
+    cnt[fn] = sm.cnt[fn];
+    vy[fn] = yid[fn] - vlane;              // position of the sampled token among this lane's entries
+  }
+  // first pass over 8 entries of token column fn: sums and the E2 factor
+  auto sums8 = [&](int fn, int fm, int p) __attribute__((always_inline)) {
+    float e2[8];
+    const bool ok = !TAIL || (vlane + fm * 32 + 8 * p) < V;      // V is a multiple of 8
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float s = acc_read(zs[fm][fn][p * 8 + e]), t = acc_read(zt[fm][fn][p * 8 + e]);
+      float es = fast_exp2(fmaf(s, kLog2e, -rs2[fn]));
+      float et = fast_exp2(fmaf(t, kLog2e, -rt2[fn]));
+      float d = s - t;
+      if (TAIL && !ok) { es = 0.f; et = 0.f; d = 0.f; }
+      Zs[fn] += es;
+      As[fn] = fmaf(es, d, As[fn]);
+      Zt[fn] += et;
+      if (DIAG) {
+        Bt[fn] = fmaf(et, t, Bt[fn]);
+        cnt[fn] += (t > zyt[fn] && (fm * 32 + 8 * p + e) != vy[fn] && ok) ? 1 : 0;
+      }
+      e2[e] = es;
+    }
+    if (WRITE_E2)
+      slab_store16(re, rowb ^ (((fm & 1) * 4 + p) << 4), (fm >> 1) * kImgBytesSlab + fn * 32 * kRowBytes, e2);
+  };
+  // Second factor: D = d - mu0 with mu0 the strip's running mean of d = z_s - z_t under the
+  // student weights, this tile included (both half-columns of the row).  A heavy entry
+  // dominates the mean of its own tile, so its D is stored small and the correction
+  // (mu - mu0) carries its gradient: the rounding of both factors stays proportional to
+  // p_s |d - mu| even when the row is peaked and the first vocabulary entries say nothing
+  // about mu.  The masked entries of a tail tile have E2 = 0; their D is immaterial.
+  auto mean_of = [&](int fn) __attribute__((always_inline)) {
+    const float Zr = Zs[fn] + __shfl_xor(Zs[fn], 32, 64), Ar = As[fn] + __shfl_xor(As[fn], 32, 64);
+    if (Zr > 0.f) mu0[fn] = Ar / Zr;
+    if (mu0_out && lane < 32) mu0_out[fn * 32 + lane] = mu0[fn];
+    return mu0[fn];
+  };
+  auto factor8 = [&](int fn, int fm, int p, float m0) __attribute__((always_inline)) {
+    float dd[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      dd[e] = (acc_read(zs[fm][fn][p * 8 + e]) - m0) - acc_read(zt[fm][fn][p * 8 + e]);
+    slab_store16(rd, rowb ^ (((fm & 1) * 4 + p) << 4), (fm >> 1) * kImgBytesSlab + fn * 32 * kRowBytes, dd);
+  };
+  // The stores of D have little arithmetic of their own to hide behind, so column 0's second
+  // pass is interleaved with column 1's first pass, whose exponentials cover them.
+#pragma unroll
+  for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+    for (int p = 0; p < 2; ++p) sums8(0, fm, p);
+  float m0 = 0.f;
+  if (WRITE_D) m0 = mean_of(0);
+#pragma unroll
+  for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+      sums8(1, fm, p);
+      if (WRITE_D) factor8(0, fm, p, m0);
+    }
+  if (WRITE_D) {
+    m0 = mean_of(1);
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-      for (int p = 0; p < 2; ++p) {
-        float e2[8];
-        const bool ok = !TAIL || (vlane + fm * 32 + 8 * p) < V;      // V is a multiple of 8
+      for (int p = 0; p < 2; ++p) factor8(1, fm, p, m0);
+  }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float s = acc_read(zs[fm][fn][p * 8 + e]), t = acc_read(zt[fm][fn][p * 8 + e]);
-          float es = fast_exp2(fmaf(s, kLog2e, -rs2[fn]));
-          float et = fast_exp2(fmaf(t, kLog2e, -rt2[fn]));
-          float d = s - t;
-          if (TAIL && !ok) { es = 0.f; et = 0.f; d = 0.f; }
-          Zs += es;
-          As = fmaf(es, d, As);
-          Zt += et;
-          if (DIAG) {
-            Bt = fmaf(et, t, Bt);
-            cnt += (t > zyt[fn] && (fm * 32 + 8 * p + e) != vy && ok) ? 1 : 0;
-          }
-          e2[e] = es;
-        }
-        if (WRITE_E2)
-          slab_store16(re, rowb ^ (((fm & 1) * 4 + p) << 4), (fm >> 1) * kImgBytesSlab + fn * 32 * kRowBytes, e2);
-      }
-    sm.Z_s[fn] = Zs; sm.A_s[fn] = As; sm.Z_t[fn] = Zt;
-    if (DIAG) { sm.B_t[fn] = Bt; sm.cnt[fn] = cnt; }
-    if (WRITE_D) {
-      // Second factor: D = d - mu0 with mu0 the strip's running mean of d = z_s - z_t under the
-      // student weights, this tile included (both half-columns of the row).  A heavy entry
-      // dominates the mean of its own tile, so its D is stored small and the correction
-      // (mu - mu0) carries its gradient: the rounding of both factors stays proportional to
-      // p_s |d - mu| even when the row is peaked and the first vocabulary entries say nothing
-      // about mu.  The masked entries of a tail tile have E2 = 0; their D is immaterial.
-      const float Zr = Zs + __shfl_xor(Zs, 32, 64), Ar = As + __shfl_xor(As, 32, 64);
-      if (Zr > 0.f) mu0[fn] = Ar / Zr;
-      const float m0 = mu0[fn];
-      if (mu0_out && lane < 32) mu0_out[fn * 32 + lane] = m0;
-#pragma unroll
-      for (int fm = 0; fm < 4; ++fm)
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-          float dd[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            dd[e] = (acc_read(zs[fm][fn][p * 8 + e]) - m0) - acc_read(zt[fm][fn][p * 8 + e]);
-          slab_store16(rd, rowb ^ (((fm & 1) * 4 + p) << 4), (fm >> 1) * kImgBytesSlab + fn * 32 * kRowBytes, dd);
-        }
-    }
+  for (int fn = 0; fn < 2; ++fn) {
+    sm.Z_s[fn] = Zs[fn]; sm.A_s[fn] = As[fn]; sm.Z_t[fn] = Zt[fn];
+    if (DIAG) { sm.B_t[fn] = Bt[fn]; sm.cnt[fn] = cnt[fn]; }
   }
 }
 
