@@ -640,8 +640,11 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) { zt[fm][fn][e] = 0.f; zs[fm][fn][e] = 0.f; }
 
-    // step 0 of this tile has landed once at most the 12 loads of step 1 are outstanding
-    wait_vm<kDmaPerWave>();
+    // Step 0 of this tile has landed once at most the 12 loads of step 1 are outstanding.  For
+    // the strip's first tile that is waited for here; for every later tile it was waited for
+    // before the previous tile's epilogue (below): the counter takes loads and stores in order,
+    // so a wait placed here would also wait for nearly all of that epilogue's stores.
+    if (vt == vt_begin) wait_vm<kDmaPerWave>();
     __syncthreads();
     bf16x8 fa[2][4], fb[2][2];
     {
@@ -681,6 +684,7 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       const char* sWn = blocks_wt(vt + 1);
       step(yes, no, zs, sWn, sHt);
       step(yes, yes, zs, sWn + kImgABytes, sHt + kImgBBytes);
+      wait_vm<kDmaPerWave>();                  // the next tile's step 0 (see the top of the loop)
     } else {
       step(no, no, zs, sWs, sHs);
       step(no, yes, zs, sWs, sHs);
