@@ -507,11 +507,19 @@ __device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, uint32_t v
 // sub-step's MFMAs cover the reads of the next stage's first fragments (stage `nxt`, whose
 // loads were issued one k-step earlier and are waited for here).  LAST: no next stage in
 // this vocabulary tile; no barrier and no fragment reads.
-template <bool ISSUE, bool LAST>
+// FRESH: the k-step starts a new accumulation (first k-step of a head): its first MFMA on each
+// block takes a zero addend, so the accumulators are never cleared.
+// RELAXED > 0 (with `relaxed` set): the wait before the barrier lets RELAXED more operations
+// stay in flight.  The counter takes loads and stores in the order of issue; the first k-step
+// of a tile follows an epilogue that issued at least RELAXED stores after the loads this wait is
+// for, and waiting for "all but this step's 9 loads" would mean waiting for every one of them.
+template <bool ISSUE, bool LAST, bool FRESH = false, int RELAXED = 0>
 __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
                                             const char* curA, const char* curB, const char* nxtA,
                                             const char* nxtB, int lane, uint32_t lds_stage, int wave,
-                                            uint32_t voff, const char* sA, const char* sB) {
+                                            uint32_t voff, const char* sA, const char* sB, bool relaxed = false) {
+  static_assert(9 + RELAXED <= 63, "the wait count has six bits");
+  const f32x16 kZeroTile = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const int key = (lane >> 1) & 7, half = lane >> 5;
   const int rowoff = (lane & 31) * kRowBytes;
   int sw[4];
@@ -522,7 +530,7 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
 #define ADWIN_RB(TB, KK, I) fb[((KK) + 1) & 1][I] = *(const bf16x8*)((TB) + (I) * 32 * kRowBytes + sw[((KK) + 1) & 3]); ADWIN_FENCE
 #define ADWIN_MM(KK, FMI, FNI)                                                                  \
   acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
-                                                          acc[FMI][FNI], 0, 0, 0);              \
+                                                          (FRESH && (KK) == 0) ? kZeroTile : acc[FMI][FNI], 0, 0, 0); \
   ADWIN_FENCE
 #define ADWIN_DMA(I) if constexpr (ISSUE) { dma_one<I>(lds_stage, wave, voff, sA, sB); ADWIN_FENCE }
   // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from (TA, TB) when READ
@@ -541,8 +549,14 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
   ADWIN_SUB(2, true, curA, curB, 6, 7, 8)
   if constexpr (!LAST) {
     // loads issued after those of the next stage: the 9 above (none when !ISSUE)
-    if constexpr (ISSUE) asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if constexpr (ISSUE && RELAXED > 0) {
+      if (relaxed) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(9 + RELAXED) : "memory");
+      else asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
+    } else if constexpr (ISSUE) {
+      asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    }
     __syncthreads();
   }
   ADWIN_FENCE
@@ -608,45 +622,75 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 
   // The k-steps of all vocabulary tiles of the strip form one pipeline: per tile nk_t
   // teacher steps, then nk_s student steps; step g is staged into ring slot g % 3 two steps
-  // before it is consumed, also across the tile boundary (the next tile's first two steps
-  // are loaded during this tile's last two, i.e. before and under the epilogue).
+  // before it is consumed, also across head and tile boundaries (the next tile's first two steps
+  // are loaded during this tile's last two, i.e. before and under the epilogue).  ld*: the step
+  // that the next loads are for; past the strip's last step the walk wraps to the strip's first
+  // tile, so that every k-step loads (those last blocks land in slots nobody reads any more).
   uint32_t wr = 0, rd = 0;     // ring slots of the next step to load / to consume
   auto slot_inc = [](uint32_t x) { return x + 1 == kDmaStages ? 0u : x + 1; };
-  {
-    const char* sWt = blocks_wt(vt_begin);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const uint32_t dst = lds0 + wr * kLogitStage;
-      const char* sA = sWt + i * kImgABytes;
-      const char* sB = sHt + i * kImgBBytes;
-      dma_one<0>(dst, wave, voff, sA, sB); dma_one<1>(dst, wave, voff, sA, sB);
-      dma_one<2>(dst, wave, voff, sA, sB); dma_one<3>(dst, wave, voff, sA, sB);
-      dma_one<4>(dst, wave, voff, sA, sB); dma_one<5>(dst, wave, voff, sA, sB);
-      dma_one<6>(dst, wave, voff, sA, sB); dma_one<7>(dst, wave, voff, sA, sB);
-      dma_one<8>(dst, wave, voff, sA, sB); dma_one<9>(dst, wave, voff, sA, sB);
-      dma_one<10>(dst, wave, voff, sA, sB); dma_one<11>(dst, wave, voff, sA, sB);
-      wr = slot_inc(wr);
-    }
+  int ld_vt = vt_begin, ld_k = 0;
+  bool ld_student = false;
+  const char* ldA = blocks_wt(vt_begin);
+  const char* ldB = sHt;
+#define ADWIN_ADVANCE_LOADS()                                              \
+  {                                                                        \
+    ++ld_k;                                                                \
+    ldA += kImgABytes;                                                     \
+    ldB += kImgBBytes;                                                     \
+    if (ld_k == (ld_student ? nk_s : nk_t)) {                              \
+      ld_k = 0;                                                            \
+      if (!ld_student) {                                                   \
+        ld_student = true;                                                 \
+        ldA = blocks_ws(ld_vt); ldB = sHs;                                 \
+      } else {                                                             \
+        ld_student = false;                                                \
+        ld_vt = ld_vt + 1 < vt_end ? ld_vt + 1 : vt_begin;                 \
+        ldA = blocks_wt(ld_vt); ldB = sHt;                                 \
+      }                                                                    \
+    }                                                                      \
   }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const uint32_t dst = lds0 + wr * kLogitStage;
+    dma_one<0>(dst, wave, voff, ldA, ldB); dma_one<1>(dst, wave, voff, ldA, ldB);
+    dma_one<2>(dst, wave, voff, ldA, ldB); dma_one<3>(dst, wave, voff, ldA, ldB);
+    dma_one<4>(dst, wave, voff, ldA, ldB); dma_one<5>(dst, wave, voff, ldA, ldB);
+    dma_one<6>(dst, wave, voff, ldA, ldB); dma_one<7>(dst, wave, voff, ldA, ldB);
+    dma_one<8>(dst, wave, voff, ldA, ldB); dma_one<9>(dst, wave, voff, ldA, ldB);
+    dma_one<10>(dst, wave, voff, ldA, ldB); dma_one<11>(dst, wave, voff, ldA, ldB);
+    wr = slot_inc(wr);
+    ADWIN_ADVANCE_LOADS()
+  }
+  // 16-byte stores a wave issues per tile in its epilogue, at the least (see sweep_kstep, RELAXED)
+  constexpr int kEpilogueStores = MODE == kModeDz ? 16 : (kWriteE2 && kSingle ? 16 : 0) + (kWriteD ? 16 : 0);
+  f32x16 zt[4][2], zs[4][2];
+  bf16x8 fa[2][4], fb[2][2];
+  // one k-step: consume slot rd, prefetch fragments from the following slot, load into wr
+  auto step = [&](auto last_c, auto fresh_c, auto relaxed_c, f32x16 (&acc)[4][2], bool relaxed)
+                  __attribute__((always_inline)) {
+    constexpr bool kLast = decltype(last_c)::value, kFresh = decltype(fresh_c)::value;
+    constexpr int kRelaxed = decltype(relaxed_c)::value;
+    const char* cur = lds + rd * kLogitStage;
+    const uint32_t rn = slot_inc(rd);
+    const char* nxt = lds + rn * kLogitStage;
+    sweep_kstep<true, kLast, kFresh, kRelaxed>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB,
+                                               lane, lds0 + wr * kLogitStage, wave, voff, ldA, ldB, relaxed);
+    wr = slot_inc(wr);
+    rd = rn;
+    ADWIN_ADVANCE_LOADS()
+  };
+  const std::true_type yes{};
+  const std::false_type no{};
+  const std::integral_constant<int, 0> strict{};
+  const std::integral_constant<int, kEpilogueStores> after_epilogue{};
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int v0 = vt * kTileVocab;
-    const char* sWt = blocks_wt(vt);
-    const char* sWs = blocks_ws(vt);
-    f32x16 zt[4][2], zs[4][2];
-#pragma unroll
-    for (int fm = 0; fm < 4; ++fm)
-#pragma unroll
-      for (int fn = 0; fn < 2; ++fn)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { zt[fm][fn][e] = 0.f; zs[fm][fn][e] = 0.f; }
-
     // Step 0 of this tile has landed once at most the 12 loads of step 1 are outstanding.  For
     // the strip's first tile that is waited for here; for every later tile it was waited for
     // before the previous tile's epilogue (below): the counter takes loads and stores in order,
     // so a wait placed here would also wait for nearly all of that epilogue's stores.
     if (vt == vt_begin) wait_vm<kDmaPerWave>();
     __syncthreads();
-    bf16x8 fa[2][4], fb[2][2];
     {
       const char* cur = lds + rd * kLogitStage;
       const int key = (lane >> 1) & 7, half = lane >> 5;
@@ -656,39 +700,14 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) fb[0][i] = *(const bf16x8*)(cur + waveB + i * 32 * kRowBytes + sw0);
     }
-    // one k-step: consume slot rd, prefetch fragments from the following slot, load into wr
-    auto step = [&](auto issue_c, auto last_c, f32x16 (&acc)[4][2], const char* sA, const char* sB) {
-      constexpr bool kIssue = decltype(issue_c)::value, kLast = decltype(last_c)::value;
-      const char* cur = lds + rd * kLogitStage;
-      const uint32_t rn = slot_inc(rd);
-      const char* nxt = lds + rn * kLogitStage;
-      sweep_kstep<kIssue, kLast>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB, lane,
-                                 lds0 + wr * kLogitStage, wave, voff, sA, sB);
-      if (kIssue) wr = slot_inc(wr);
-      rd = rn;
-    };
-    const std::true_type yes{};
-    const std::false_type no{};
-    int s = 0;
-    for (; s + 2 < nk_t; ++s)                  // teacher k-steps loading teacher k-steps
-      step(yes, no, zt, sWt + (s + 2) * kImgABytes, sHt + (s + 2) * kImgBBytes);
-    for (; s < nk_t; ++s) {                    // last two teacher k-steps load student k-steps 0, 1
-      const int n = s + 2 - nk_t;
-      step(yes, no, zt, sWs + n * kImgABytes, sHs + n * kImgBBytes);
-    }
-    for (; s + 2 < nk; ++s) {                  // student k-steps loading student k-steps
-      const int n = s + 2 - nk_t;
-      step(yes, no, zs, sWs + n * kImgABytes, sHs + n * kImgBBytes);
-    }
-    if (vt + 1 < vt_end) {                     // last two: load the next tile's teacher k-steps 0, 1
-      const char* sWn = blocks_wt(vt + 1);
-      step(yes, no, zs, sWn, sHt);
-      step(yes, yes, zs, sWn + kImgABytes, sHt + kImgBBytes);
-      wait_vm<kDmaPerWave>();                  // the next tile's step 0 (see the top of the loop)
-    } else {
-      step(no, no, zs, sWs, sHs);
-      step(no, yes, zs, sWs, sHs);
-    }
+    // teacher: nk_t k-steps (the first on a zero addend; after an epilogue its wait leaves that
+    // epilogue's stores in flight), then student: nk_s k-steps, the last without a barrier
+    step(no, yes, after_epilogue, zt, vt != vt_begin);
+    for (int s = 1; s < nk_t; ++s) step(no, no, strict, zt, false);
+    step(no, yes, strict, zs, false);
+    for (int s = 1; s + 1 < nk_s; ++s) step(no, no, strict, zs, false);
+    step(yes, no, strict, zs, false);
+    wait_vm<kDmaPerWave>();                    // the next tile's step 0 (see the top of the loop)
     const bool tail = v0 + kTileVocab > a.V;
     if (MODE == kModeStats) {
       stats_epilogue(zs, zt, st, v0, a.V, tail, lane);
@@ -706,6 +725,8 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       }
     }
   }
+#undef ADWIN_ADVANCE_LOADS
+  wait_vm<0>();      // the strip's last two k-steps loaded blocks nobody reads: landed before the LDS is released
   const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
   if (MODE == kModeStats) write_partials(st, a.part, a.strips, strip, a.n_pad, row0, lane);
   else if (kSingle) write_sums<kDiag>(sm, a.part, a.strips, strip, a.n_pad, row0, lane);
