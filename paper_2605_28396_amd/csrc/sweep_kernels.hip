@@ -219,6 +219,8 @@ __device__ __forceinline__ float acc_read(const float& a) {
 // scalars, so the stores need no 64-bit address registers.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t slab_rsrc(__bf16* blk) {
+  // extent: the tile's two blocks; flag word: the raw-buffer setting of the gfx9 family
+  // (32-bit data format, no swizzle)
   return __builtin_amdgcn_make_buffer_rsrc(blk, 0, 2 * kImgBytesSlab, 0x00020000);
 }
 __device__ __forceinline__ void slab_store16(__amdgpu_buffer_rsrc_t r, int lane_off, int block_off, const float (&x)[8]) {
