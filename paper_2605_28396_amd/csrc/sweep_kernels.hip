@@ -18,7 +18,7 @@
 // (j = token), so each lane owns one token column and the reduction over the vocabulary
 // runs down its own registers with no cross-lane traffic.
 // A lane holds rows i = 8 (e / 4) + 4 (lane / 32) + e % 4 of a 32 x 32 block, e = 0..15.  The
-// W tiles are staged with their rows permuted inside every group of 32 (tile_row_of_entry), so
+// W tiles are staged with their rows permuted inside every group of 32 (entry_of_tile_row), so
 // that these are 16 consecutive vocabulary entries, 16 (lane / 32) + e: a lane then owns 32
 // consecutive bytes of a slab row per block and writes them with two 16-byte stores, where the
 // natural order gives it four separate 8-byte pieces.
