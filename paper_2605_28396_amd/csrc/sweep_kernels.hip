@@ -502,8 +502,8 @@ __device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, uint32_t v
 // One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  On entry fa[0],
 // fb[0] hold the fragments of sub-step 0.  The instruction order is pinned: after each MFMA
 // one or two side operations are issued in its shadow -- an LDS read of a fragment of the
-// next sub-step (fragments are double-buffered) and, when ISSUE, one of the 12 global->LDS
-// loads of the stage two k-steps ahead -- so that neither the LDS latency nor the
+// next sub-step (fragments are double-buffered) and one of the 12 global->LDS loads of the
+// stage two k-steps ahead (every k-step loads) -- so that neither the LDS latency nor the
 // vector-memory issue holds up the matrix pipe.  The one barrier of the k-step sits before
 // the last sub-step: by then every fragment of this stage is in registers, and the last
 // sub-step's MFMAs cover the reads of the next stage's first fragments (stage `nxt`, whose
@@ -515,7 +515,7 @@ __device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, uint32_t v
 // stay in flight.  The counter takes loads and stores in the order of issue; the first k-step
 // of a tile follows an epilogue that issued at least RELAXED stores after the loads this wait is
 // for, and waiting for "all but this step's 9 loads" would mean waiting for every one of them.
-template <bool ISSUE, bool LAST, bool FRESH = false, int RELAXED = 0>
+template <bool LAST, bool FRESH, int RELAXED>
 __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
                                             const char* curA, const char* curB, const char* nxtA,
                                             const char* nxtB, int lane, uint32_t lds_stage, int wave,
@@ -534,7 +534,7 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
   acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
                                                           (FRESH && (KK) == 0) ? kZeroTile : acc[FMI][FNI], 0, 0, 0); \
   ADWIN_FENCE
-#define ADWIN_DMA(I) if constexpr (ISSUE) { dma_one<I>(lds_stage, wave, voff, sA, sB); ADWIN_FENCE }
+#define ADWIN_DMA(I) dma_one<I>(lds_stage, wave, voff, sA, sB); ADWIN_FENCE
   // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from (TA, TB) when READ
 #define ADWIN_SUB(KK, READ, TA, TB, D0, D1, D2)                         \
   ADWIN_MM(KK, 0, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 0) }        \
@@ -550,14 +550,12 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
   ADWIN_SUB(1, true, curA, curB, 3, 4, 5)
   ADWIN_SUB(2, true, curA, curB, 6, 7, 8)
   if constexpr (!LAST) {
-    // loads issued after those of the next stage: the 9 above (none when !ISSUE)
-    if constexpr (ISSUE && RELAXED > 0) {
+    // loads issued after those of the next stage: the 9 above
+    if constexpr (RELAXED > 0) {
       if (relaxed) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" :: "n"(9 + RELAXED) : "memory");
       else asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
-    } else if constexpr (ISSUE) {
-      asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
     } else {
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      asm volatile("s_waitcnt vmcnt(9) lgkmcnt(0)" ::: "memory");
     }
     __syncthreads();
   }
@@ -675,7 +673,7 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     const char* cur = lds + rd * kLogitStage;
     const uint32_t rn = slot_inc(rd);
     const char* nxt = lds + rn * kLogitStage;
-    sweep_kstep<true, kLast, kFresh, kRelaxed>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB,
+    sweep_kstep<kLast, kFresh, kRelaxed>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB,
                                                lane, lds0 + wr * kLogitStage, wave, voff, ldA, ldB, relaxed);
     wr = slot_inc(wr);
     rd = rn;
