@@ -33,6 +33,15 @@ __device__ __forceinline__ void dma16(uint32_t lds_dst, uint32_t voff, const cha
                :: "s"(lds_dst), "v"(voff), "s"(sbase) : "memory");
 }
 
+// The same with the wave's LDS destination given as scalar base + literal, added straight into
+// M0, so that the load costs three instructions: a wave issues one instruction at a time and
+// the loads share the shadow of an MFMA with LDS reads.
+template <int IMM>
+__device__ __forceinline__ void dma16_at(uint32_t lds_base, uint32_t voff, const char* sbase) {
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base), "v"(voff), "s"(sbase), "n"(IMM) : "memory", "scc");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");

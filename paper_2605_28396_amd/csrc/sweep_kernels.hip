@@ -488,15 +488,16 @@ constexpr int kImgABytes = kTileVocab * kRowBytes;    // 16 KiB: one W block
 constexpr int kImgBBytes = kTileTokens * kRowBytes;   // 32 KiB: one h block
 
 // Wave-load I (0..11) of this wave for one stage: KiB (wave + 4 I) of the A block, then of
-// the B block; lane l moves bytes 16 l .. 16 l + 15 of that KiB.
+// the B block; lane l moves bytes 16 l .. 16 l + 15 of that KiB.  lds_wave = the stage's LDS
+// address + 1024 wave; voffw[j] = 16 lane + 1024 (wave + 4 j): the wave's part of both addresses
+// is folded into operands that are set up once, the rest is a literal.
 template <int I>
-__device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, uint32_t voff, const char* sA,
+__device__ __forceinline__ void dma_one(uint32_t lds_wave, const uint32_t (&voffw)[8], const char* sA,
                                         const char* sB) {
   if constexpr (I < kTileVocab / 32)
-    dma16(lds_stage + (uint32_t)(wave + 4 * I) * 1024u, voff, sA + (wave + 4 * I) * 1024);
+    dma16_at<4 * I * 1024>(lds_wave, voffw[I], sA);
   else
-    dma16(lds_stage + (uint32_t)(kTileVocab / 8 + wave + 4 * (I - kTileVocab / 32)) * 1024u, voff,
-          sB + (wave + 4 * (I - kTileVocab / 32)) * 1024);
+    dma16_at<(kTileVocab / 8 + 4 * (I - kTileVocab / 32)) * 1024>(lds_wave, voffw[I - kTileVocab / 32], sB);
 }
 
 // One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  On entry fa[0],
@@ -518,8 +519,9 @@ __device__ __forceinline__ void dma_one(uint32_t lds_stage, int wave, uint32_t v
 template <bool LAST, bool FRESH, int RELAXED>
 __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
                                             const char* curA, const char* curB, const char* nxtA,
-                                            const char* nxtB, int lane, uint32_t lds_stage, int wave,
-                                            uint32_t voff, const char* sA, const char* sB, bool relaxed = false) {
+                                            const char* nxtB, int lane, uint32_t lds_wave,
+                                            const uint32_t (&voffw)[8], const char* sA, const char* sB,
+                                            bool relaxed = false) {
   static_assert(9 + RELAXED <= 63, "the wait count has six bits");
   const f32x16 kZeroTile = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const int key = (lane >> 1) & 7, half = lane >> 5;
@@ -534,7 +536,7 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
   acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
                                                           (FRESH && (KK) == 0) ? kZeroTile : acc[FMI][FNI], 0, 0, 0); \
   ADWIN_FENCE
-#define ADWIN_DMA(I) dma_one<I>(lds_stage, wave, voff, sA, sB); ADWIN_FENCE
+#define ADWIN_DMA(I) dma_one<I>(lds_wave, voffw, sA, sB); ADWIN_FENCE
   // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from (TA, TB) when READ
 #define ADWIN_SUB(KK, READ, TA, TB, D0, D1, D2)                         \
   ADWIN_MM(KK, 0, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 0) }        \
@@ -585,7 +587,12 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   if (vt_begin >= vt_end) return;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
-  const uint32_t voff = (uint32_t)lane * 16u;
+  uint32_t voffw[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    voffw[j] = (uint32_t)lane * 16u + (uint32_t)(wave + 4 * j) * 1024u;
+    asm volatile("" : "+v"(voffw[j]));   // kept in registers, not recomputed at every load
+  }
   const int waveA = 0, waveB = kTileVocab * kRowBytes + wave * 64 * kRowBytes;
   const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;   // each >= 2 on this path
   // blocks of this token tile (fixed) and of vocabulary tile vt, teacher and student
@@ -651,13 +658,13 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const uint32_t dst = lds0 + wr * kLogitStage;
-    dma_one<0>(dst, wave, voff, ldA, ldB); dma_one<1>(dst, wave, voff, ldA, ldB);
-    dma_one<2>(dst, wave, voff, ldA, ldB); dma_one<3>(dst, wave, voff, ldA, ldB);
-    dma_one<4>(dst, wave, voff, ldA, ldB); dma_one<5>(dst, wave, voff, ldA, ldB);
-    dma_one<6>(dst, wave, voff, ldA, ldB); dma_one<7>(dst, wave, voff, ldA, ldB);
-    dma_one<8>(dst, wave, voff, ldA, ldB); dma_one<9>(dst, wave, voff, ldA, ldB);
-    dma_one<10>(dst, wave, voff, ldA, ldB); dma_one<11>(dst, wave, voff, ldA, ldB);
+    const uint32_t dst = lds0 + wr * kLogitStage + (uint32_t)wave * 1024u;
+    dma_one<0>(dst, voffw, ldA, ldB); dma_one<1>(dst, voffw, ldA, ldB);
+    dma_one<2>(dst, voffw, ldA, ldB); dma_one<3>(dst, voffw, ldA, ldB);
+    dma_one<4>(dst, voffw, ldA, ldB); dma_one<5>(dst, voffw, ldA, ldB);
+    dma_one<6>(dst, voffw, ldA, ldB); dma_one<7>(dst, voffw, ldA, ldB);
+    dma_one<8>(dst, voffw, ldA, ldB); dma_one<9>(dst, voffw, ldA, ldB);
+    dma_one<10>(dst, voffw, ldA, ldB); dma_one<11>(dst, voffw, ldA, ldB);
     wr = slot_inc(wr);
     ADWIN_ADVANCE_LOADS()
   }
@@ -674,7 +681,7 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     const uint32_t rn = slot_inc(rd);
     const char* nxt = lds + rn * kLogitStage;
     sweep_kstep<kLast, kFresh, kRelaxed>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB,
-                                               lane, lds0 + wr * kLogitStage, wave, voff, ldA, ldB, relaxed);
+                                               lane, lds0 + wr * kLogitStage + (uint32_t)wave * 1024u, voffw, ldA, ldB, relaxed);
     wr = slot_inc(wr);
     rd = rn;
     ADWIN_ADVANCE_LOADS()
