@@ -500,57 +500,93 @@ __device__ __forceinline__ void dma_one(uint32_t lds_wave, const uint32_t (&voff
     dma16_at<(kTileVocab / 8 + 4 * (I - kTileVocab / 32)) * 1024>(lds_wave, voffw[I - kTileVocab / 32], sB);
 }
 
+// Wave-uniform bookkeeping of the k-step pipeline, written as instructions at a fixed place:
+// plain scalar arithmetic has no place of its own in the pinned order below and would be
+// gathered in front of the k-step's first MFMA, where the wave, which issues one instruction at
+// a time, keeps the matrix pipe waiting.
+// Ring slot after slot x (addresses; the ring is [begin, end), slots kLogitStage apart).
+__device__ __forceinline__ uint32_t ring_next(uint32_t x, uint32_t ring_begin, uint32_t ring_end) {
+  uint32_t y;
+  asm volatile("s_add_u32 %0, %1, %4\n\ts_cmp_lg_u32 %0, %2\n\ts_cselect_b32 %0, %0, %3"
+               : "=&s"(y) : "s"(x), "s"(ring_end), "s"(ring_begin), "n"(kLogitStage) : "scc");
+  return y;
+}
+// 64-bit address, kept as two halves, += BYTES.
+template <int BYTES>
+__device__ __forceinline__ void addr_advance(uint32_t& lo, uint32_t& hi) {
+  asm volatile("s_add_u32 %0, %0, %2\n\ts_addc_u32 %1, %1, 0" : "+s"(lo), "+s"(hi) : "n"(BYTES) : "scc");
+}
+__device__ __forceinline__ const char* addr_of(uint32_t lo, uint32_t hi) {
+  return (const char*)(((uint64_t)hi << 32) | lo);
+}
+
+typedef const __attribute__((address_space(3))) bf16x8* LdsFragPtr;
+
 // One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  On entry fa[0],
 // fb[0] hold the fragments of sub-step 0.  The instruction order is pinned: after each MFMA
 // one or two side operations are issued in its shadow -- an LDS read of a fragment of the
-// next sub-step (fragments are double-buffered) and one of the 12 global->LDS loads of the
-// stage two k-steps ahead (every k-step loads) -- so that neither the LDS latency nor the
-// vector-memory issue holds up the matrix pipe.  The one barrier of the k-step sits before
-// the last sub-step: by then every fragment of this stage is in registers, and the last
-// sub-step's MFMAs cover the reads of the next stage's first fragments (stage `nxt`, whose
-// loads were issued one k-step earlier and are waited for here).  LAST: no next stage in
-// this vocabulary tile; no barrier and no fragment reads.
+// next sub-step (fragments are double-buffered), one of the 12 global->LDS loads of the
+// stage two k-steps ahead (every k-step loads) or a piece of the pipeline's bookkeeping -- so
+// that neither the LDS latency nor the vector-memory issue holds up the matrix pipe.  The one
+// barrier of the k-step sits before the last sub-step: by then every fragment of this stage is
+// in registers, and the last sub-step's MFMAs cover the reads of the next stage's first
+// fragments (the following ring slot, whose loads were issued one k-step earlier and are waited
+// for here).  LAST: no next stage in this vocabulary tile; no barrier and no fragment reads.
 // FRESH: the k-step starts a new accumulation (first k-step of a head): its first MFMA on each
 // block takes a zero addend, so the accumulators are never cleared.
 // RELAXED > 0 (with `relaxed` set): the wait before the barrier lets RELAXED more operations
 // stay in flight.  The counter takes loads and stores in the order of issue; the first k-step
 // of a tile follows an epilogue that issued at least RELAXED stores after the loads this wait is
 // for, and waiting for "all but this step's 9 loads" would mean waiting for every one of them.
+// Ring and load state: r_rd = address (LDS base + 1024 wave + slot) of the slot consumed, on
+// return that of the next k-step; swA/swB = the lane's fragment offsets from such an address
+// per sub-step; (a_lo, a_hi), (b_lo, b_hi) = the blocks that the previous k-step loaded, on
+// return those that this one loaded.
 template <bool LAST, bool FRESH, int RELAXED>
 __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][2],
-                                            const char* curA, const char* curB, const char* nxtA,
-                                            const char* nxtB, int lane, uint32_t lds_wave,
-                                            const uint32_t (&voffw)[8], const char* sA, const char* sB,
-                                            bool relaxed = false) {
+                                            uint32_t& r_rd, uint32_t ring_begin, uint32_t ring_end,
+                                            const uint32_t (&swA)[4], const uint32_t (&swB)[4],
+                                            const uint32_t (&voffw)[8], uint32_t& a_lo, uint32_t& a_hi,
+                                            uint32_t& b_lo, uint32_t& b_hi, bool relaxed = false) {
   static_assert(9 + RELAXED <= 63, "the wait count has six bits");
   const f32x16 kZeroTile = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  const int key = (lane >> 1) & 7, half = lane >> 5;
-  const int rowoff = (lane & 31) * kRowBytes;
-  int sw[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) sw[kk] = rowoff + (((kk * 2 + half) ^ key) << 4);
+  uint32_t r_nx, r_wr;
 #define ADWIN_FENCE __builtin_amdgcn_sched_barrier(0);
-#define ADWIN_RA(TA, KK, I) fa[((KK) + 1) & 1][I] = *(const bf16x8*)((TA) + (I) * 32 * kRowBytes + sw[((KK) + 1) & 3]); ADWIN_FENCE
-#define ADWIN_RB(TB, KK, I) fb[((KK) + 1) & 1][I] = *(const bf16x8*)((TB) + (I) * 32 * kRowBytes + sw[((KK) + 1) & 3]); ADWIN_FENCE
+#define ADWIN_RA(KK, I) fa[((KK) + 1) & 1][I] = ((LdsFragPtr)xa)[(I) * 32 * kRowBytes / 16]; ADWIN_FENCE
+#define ADWIN_RB(KK, I) fb[((KK) + 1) & 1][I] = ((LdsFragPtr)xb)[(I) * 32 * kRowBytes / 16]; ADWIN_FENCE
 #define ADWIN_MM(KK, FMI, FNI)                                                                  \
   acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
                                                           (FRESH && (KK) == 0) ? kZeroTile : acc[FMI][FNI], 0, 0, 0); \
   ADWIN_FENCE
-#define ADWIN_DMA(I) dma_one<I>(lds_wave, voffw, sA, sB); ADWIN_FENCE
-  // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from (TA, TB) when READ
-#define ADWIN_SUB(KK, READ, TA, TB, D0, D1, D2)                         \
-  ADWIN_MM(KK, 0, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 0) }        \
-  ADWIN_MM(KK, 0, 1) if constexpr (READ) { ADWIN_RB(TB, KK, 0) }        \
-  ADWIN_MM(KK, 1, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 1) }        \
-  ADWIN_MM(KK, 1, 1) if constexpr (READ) { ADWIN_RB(TB, KK, 1) }        \
-  ADWIN_MM(KK, 2, 0) if constexpr (READ) { ADWIN_RA(TA, KK, 2) }        \
-  ADWIN_MM(KK, 2, 1) if constexpr (READ) { ADWIN_RA(TA, KK, 3) } ADWIN_DMA(D0) \
-  ADWIN_MM(KK, 3, 0) ADWIN_DMA(D1)                                      \
-  ADWIN_MM(KK, 3, 1) ADWIN_DMA(D2)
+#define ADWIN_DMA(I) dma_one<I>(r_wr, voffw, addr_of(a_lo, a_hi), addr_of(b_lo, b_hi)); ADWIN_FENCE
+  // sub-step KK: 8 MFMAs; reads of the next sub-step's fragments from slot R when READ; H0..H3:
+  // bookkeeping in the shadows of the first four MFMAs.  xa, xb: the lane's LDS addresses of its
+  // first A and B fragment, formed once (and kept from being re-associated with the fragments'
+  // constant offsets, which belong in the read instructions).
+#define ADWIN_SUB(KK, READ, R, D0, D1, D2, H0, H1, H2, H3)                    \
+  {                                                                     \
+    uint32_t xa = 0, xb = 0;                                            \
+    ADWIN_MM(KK, 0, 0)                                                  \
+    if constexpr (READ) {                                               \
+      xa = (R) + swA[((KK) + 1) & 3]; xb = (R) + swB[((KK) + 1) & 3];   \
+      asm volatile("" : "+v"(xa), "+v"(xb));                            \
+      ADWIN_RA(KK, 0)                                                   \
+    }                                                                   \
+    H0 ADWIN_FENCE                                                      \
+    ADWIN_MM(KK, 0, 1) if constexpr (READ) { ADWIN_RB(KK, 0) } H1 ADWIN_FENCE \
+    ADWIN_MM(KK, 1, 0) if constexpr (READ) { ADWIN_RA(KK, 1) } H2 ADWIN_FENCE \
+    ADWIN_MM(KK, 1, 1) if constexpr (READ) { ADWIN_RB(KK, 1) } H3 ADWIN_FENCE \
+    ADWIN_MM(KK, 2, 0) if constexpr (READ) { ADWIN_RA(KK, 2) }          \
+    ADWIN_MM(KK, 2, 1) if constexpr (READ) { ADWIN_RA(KK, 3) } ADWIN_DMA(D0) \
+    ADWIN_MM(KK, 3, 0) ADWIN_DMA(D1)                                    \
+    ADWIN_MM(KK, 3, 1) ADWIN_DMA(D2)                                    \
+  }
   ADWIN_FENCE
-  ADWIN_SUB(0, true, curA, curB, 0, 1, 2)
-  ADWIN_SUB(1, true, curA, curB, 3, 4, 5)
-  ADWIN_SUB(2, true, curA, curB, 6, 7, 8)
+  ADWIN_SUB(0, true, r_rd, 0, 1, 2,
+            { r_nx = ring_next(r_rd, ring_begin, ring_end); }, { r_wr = ring_next(r_nx, ring_begin, ring_end); },
+            { addr_advance<kImgABytes>(a_lo, a_hi); }, { addr_advance<kImgBBytes>(b_lo, b_hi); })
+  ADWIN_SUB(1, true, r_rd, 3, 4, 5, {}, {}, {}, {})
+  ADWIN_SUB(2, true, r_rd, 6, 7, 8, {}, {}, {}, {})
   if constexpr (!LAST) {
     // loads issued after those of the next stage: the 9 above
     if constexpr (RELAXED > 0) {
@@ -562,7 +598,8 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
     __syncthreads();
   }
   ADWIN_FENCE
-  ADWIN_SUB(3, !LAST, nxtA, nxtB, 9, 10, 11)
+  ADWIN_SUB(3, !LAST, r_nx, 9, 10, 11, {}, {}, {}, {})
+  r_rd = r_nx;
 #undef ADWIN_SUB
 #undef ADWIN_DMA
 #undef ADWIN_MM
@@ -593,7 +630,18 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     voffw[j] = (uint32_t)lane * 16u + (uint32_t)(wave + 4 * j) * 1024u;
     asm volatile("" : "+v"(voffw[j]));   // kept in registers, not recomputed at every load
   }
-  const int waveA = 0, waveB = kTileVocab * kRowBytes + wave * 64 * kRowBytes;
+  // ring slot addresses carry the wave's KiB (for the loads); the fragment offsets take it out again
+  const uint32_t ring_begin = lds0 + (uint32_t)wave * 1024u, ring_end = ring_begin + kDmaStages * kLogitStage;
+  uint32_t swA[4], swB[4];
+  {
+    const int key = (lane >> 1) & 7, half = lane >> 5;
+    const uint32_t rowoff = (uint32_t)(lane & 31) * kRowBytes - (uint32_t)wave * 1024u;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      swA[kk] = rowoff + (uint32_t)(((kk * 2 + half) ^ key) << 4);
+      swB[kk] = swA[kk] + (uint32_t)(kTileVocab * kRowBytes + wave * 64 * kRowBytes);
+    }
+  }
   const int nk_t = a.H_t / kBK, nk_s = a.H_s / kBK, nk = nk_t + nk_s;   // each >= 2 on this path
   // blocks of this token tile (fixed) and of vocabulary tile vt, teacher and student
   const char* sHt = a.ht_img + (int64_t)tt * nk_t * kImgBBytes;
@@ -631,60 +679,62 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
   // teacher steps, then nk_s student steps; step g is staged into ring slot g % 3 two steps
   // before it is consumed, also across head and tile boundaries (the next tile's first two steps
   // are loaded during this tile's last two, i.e. before and under the epilogue).  ld*: the step
-  // that the next loads are for; past the strip's last step the walk wraps to the strip's first
+  // whose loads were issued last; past the strip's last step the walk wraps to the strip's first
   // tile, so that every k-step loads (those last blocks land in slots nobody reads any more).
-  uint32_t wr = 0, rd = 0;     // ring slots of the next step to load / to consume
-  auto slot_inc = [](uint32_t x) { return x + 1 == kDmaStages ? 0u : x + 1; };
-  int ld_vt = vt_begin, ld_k = 0;
+  // (a, b) = the blocks of that step; a k-step moves them on by one block before it loads, so
+  // at the start of a head they are set one block in front of it.
+  uint32_t r_rd = ring_begin;  // ring slot (address) of the next step to consume
+  int ld_vt = vt_begin, ld_k = 0, ld_lim = nk_t;
   bool ld_student = false;
-  const char* ldA = blocks_wt(vt_begin);
-  const char* ldB = sHt;
-#define ADWIN_ADVANCE_LOADS()                                              \
+  uint32_t a_lo, a_hi, b_lo, b_hi;
+#define ADWIN_SET_BLOCKS(A, B)                                             \
   {                                                                        \
-    ++ld_k;                                                                \
-    ldA += kImgABytes;                                                     \
-    ldB += kImgBBytes;                                                     \
-    if (ld_k == (ld_student ? nk_s : nk_t)) {                              \
+    const uint64_t pa = (uint64_t)(A) - kImgABytes, pb = (uint64_t)(B) - kImgBBytes; \
+    a_lo = (uint32_t)pa; a_hi = (uint32_t)(pa >> 32);                      \
+    b_lo = (uint32_t)pb; b_hi = (uint32_t)(pb >> 32);                      \
+  }
+#define ADWIN_COUNT_LOADS()                                                \
+  {                                                                        \
+    if (++ld_k == ld_lim) {                                                \
       ld_k = 0;                                                            \
       if (!ld_student) {                                                   \
-        ld_student = true;                                                 \
-        ldA = blocks_ws(ld_vt); ldB = sHs;                                 \
+        ld_student = true; ld_lim = nk_s;                                  \
+        ADWIN_SET_BLOCKS(blocks_ws(ld_vt), sHs)                            \
       } else {                                                             \
-        ld_student = false;                                                \
+        ld_student = false; ld_lim = nk_t;                                 \
         ld_vt = ld_vt + 1 < vt_end ? ld_vt + 1 : vt_begin;                 \
-        ldA = blocks_wt(ld_vt); ldB = sHt;                                 \
+        ADWIN_SET_BLOCKS(blocks_wt(ld_vt), sHt)                            \
       }                                                                    \
     }                                                                      \
   }
+  ADWIN_SET_BLOCKS(blocks_wt(vt_begin), sHt)
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const uint32_t dst = lds0 + wr * kLogitStage + (uint32_t)wave * 1024u;
+    const uint32_t dst = ring_begin + (uint32_t)i * kLogitStage;
+    addr_advance<kImgABytes>(a_lo, a_hi);
+    addr_advance<kImgBBytes>(b_lo, b_hi);
+    const char* ldA = addr_of(a_lo, a_hi);
+    const char* ldB = addr_of(b_lo, b_hi);
     dma_one<0>(dst, voffw, ldA, ldB); dma_one<1>(dst, voffw, ldA, ldB);
     dma_one<2>(dst, voffw, ldA, ldB); dma_one<3>(dst, voffw, ldA, ldB);
     dma_one<4>(dst, voffw, ldA, ldB); dma_one<5>(dst, voffw, ldA, ldB);
     dma_one<6>(dst, voffw, ldA, ldB); dma_one<7>(dst, voffw, ldA, ldB);
     dma_one<8>(dst, voffw, ldA, ldB); dma_one<9>(dst, voffw, ldA, ldB);
     dma_one<10>(dst, voffw, ldA, ldB); dma_one<11>(dst, voffw, ldA, ldB);
-    wr = slot_inc(wr);
-    ADWIN_ADVANCE_LOADS()
+    ADWIN_COUNT_LOADS()
   }
   // 16-byte stores a wave issues per tile in its epilogue, at the least (see sweep_kstep, RELAXED)
   constexpr int kEpilogueStores = MODE == kModeDz ? 16 : (kWriteE2 && kSingle ? 16 : 0) + (kWriteD ? 16 : 0);
   f32x16 zt[4][2], zs[4][2];
   bf16x8 fa[2][4], fb[2][2];
-  // one k-step: consume slot rd, prefetch fragments from the following slot, load into wr
+  // one k-step: consume slot r_rd, prefetch fragments from the following slot, load into the one after
   auto step = [&](auto last_c, auto fresh_c, auto relaxed_c, f32x16 (&acc)[4][2], bool relaxed)
                   __attribute__((always_inline)) {
     constexpr bool kLast = decltype(last_c)::value, kFresh = decltype(fresh_c)::value;
     constexpr int kRelaxed = decltype(relaxed_c)::value;
-    const char* cur = lds + rd * kLogitStage;
-    const uint32_t rn = slot_inc(rd);
-    const char* nxt = lds + rn * kLogitStage;
-    sweep_kstep<kLast, kFresh, kRelaxed>(acc, fa, fb, cur + waveA, cur + waveB, nxt + waveA, nxt + waveB,
-                                               lane, lds0 + wr * kLogitStage + (uint32_t)wave * 1024u, voffw, ldA, ldB, relaxed);
-    wr = slot_inc(wr);
-    rd = rn;
-    ADWIN_ADVANCE_LOADS()
+    sweep_kstep<kLast, kFresh, kRelaxed>(acc, fa, fb, r_rd, ring_begin, ring_end, swA, swB, voffw,
+                                         a_lo, a_hi, b_lo, b_hi, relaxed);
+    ADWIN_COUNT_LOADS()
   };
   const std::true_type yes{};
   const std::false_type no{};
@@ -698,15 +748,10 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     // so a wait placed here would also wait for nearly all of that epilogue's stores.
     if (vt == vt_begin) wait_vm<kDmaPerWave>();
     __syncthreads();
-    {
-      const char* cur = lds + rd * kLogitStage;
-      const int key = (lane >> 1) & 7, half = lane >> 5;
-      const int sw0 = (lane & 31) * kRowBytes + ((half ^ key) << 4);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fa[0][i] = *(const bf16x8*)(cur + waveA + i * 32 * kRowBytes + sw0);
+    for (int i = 0; i < 4; ++i) fa[0][i] = *(LdsFragPtr)(r_rd + swA[0] + i * 32 * kRowBytes);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fb[0][i] = *(const bf16x8*)(cur + waveB + i * 32 * kRowBytes + sw0);
-    }
+    for (int i = 0; i < 2; ++i) fb[0][i] = *(LdsFragPtr)(r_rd + swB[0] + i * 32 * kRowBytes);
     // teacher: nk_t k-steps (the first on a zero addend; after an epilogue its wait leaves that
     // epilogue's stores in flight), then student: nk_s k-steps, the last without a barrier
     step(no, yes, after_epilogue, zt, vt != vt_begin);
@@ -732,7 +777,8 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
       }
     }
   }
-#undef ADWIN_ADVANCE_LOADS
+#undef ADWIN_COUNT_LOADS
+#undef ADWIN_SET_BLOCKS
   wait_vm<0>();      // the strip's last two k-steps loaded blocks nobody reads: landed before the LDS is released
   const int64_t row0 = (int64_t)tt * kTileTokens + wave * 64;
   if (MODE == kModeStats) write_partials(st, a.part, a.strips, strip, a.n_pad, row0, lane);
