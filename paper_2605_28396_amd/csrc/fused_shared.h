@@ -25,22 +25,41 @@ __device__ __forceinline__ int xcd_contiguous_id(int bid, int nb) {
 }
 
 // One wave instruction of a direct global->LDS load: lane l moves the 16 bytes at
-// sbase + voff(l) to LDS address lds_dst + 16 l (M0 = LDS destination of the wave, scalar
-// base + 32-bit lane offset).  Such loads return in order and are waited for with an
-// explicit s_waitcnt vmcnt(N).
-__device__ __forceinline__ void dma16(uint32_t lds_dst, uint32_t voff, const char* sbase) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_dst), "v"(voff), "s"(sbase) : "memory");
-}
-
-// The same with the wave's LDS destination given as scalar base + literal, added straight into
-// M0, so that the load costs three instructions: a wave issues one instruction at a time and
-// the loads share the shadow of an MFMA with LDS reads.
+// sbase + voff(l) to LDS address lds_base + IMM + 16 l (M0 = LDS destination of the wave;
+// scalar base + 32-bit lane offset).  Such loads return in order and are waited for with an
+// explicit s_waitcnt vmcnt(N).  The destination is given as scalar base + literal and added
+// straight into M0, and the callers keep the wave's share of both addresses in operands that
+// are set up once, so that a load costs three instructions: a wave issues one instruction at a
+// time and the loads share the shadow of an MFMA with LDS reads.
 template <int IMM>
 __device__ __forceinline__ void dma16_at(uint32_t lds_base, uint32_t voff, const char* sbase) {
   asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :: "s"(lds_base), "v"(voff), "s"(sbase), "n"(IMM) : "memory", "scc");
 }
+
+// Wave-uniform bookkeeping of a k-step pipeline, written as instructions at a fixed place:
+// plain scalar arithmetic has no place of its own in the pinned instruction order of a k-step
+// and would be gathered in front of the k-step's first MFMA, where the wave, which issues one
+// instruction at a time, keeps the matrix pipe waiting.
+// Ring slot after slot x (LDS addresses; the ring is [begin, end), slots STEP bytes apart).
+template <int STEP>
+__device__ __forceinline__ uint32_t ring_next(uint32_t x, uint32_t ring_begin, uint32_t ring_end) {
+  uint32_t y;
+  asm volatile("s_add_u32 %0, %1, %4\n\ts_cmp_lg_u32 %0, %2\n\ts_cselect_b32 %0, %0, %3"
+               : "=&s"(y) : "s"(x), "s"(ring_end), "s"(ring_begin), "n"(STEP) : "scc");
+  return y;
+}
+// 64-bit address, kept as two halves, += BYTES.
+template <int BYTES>
+__device__ __forceinline__ void addr_advance(uint32_t& lo, uint32_t& hi) {
+  asm volatile("s_add_u32 %0, %0, %2\n\ts_addc_u32 %1, %1, 0" : "+s"(lo), "+s"(hi) : "n"(BYTES) : "scc");
+}
+__device__ __forceinline__ const char* addr_of(uint32_t lo, uint32_t hi) {
+  return (const char*)(((uint64_t)hi << 32) | lo);
+}
+
+// a fragment (8 bf16 of one row) in the LDS, addressed by its 32-bit LDS address
+typedef const __attribute__((address_space(3))) bf16x8* LdsFragPtr;
 
 template <int N>
 __device__ __forceinline__ void wait_vm() {

@@ -8,6 +8,7 @@
 // Finalize : scale by grad_scale * alpha, scatter to dh_prefix / dh_full, row norms.
 // Pool     : per-rollout column sums of g over the window and over the rollout (Sec. 4.2).
 #include "fused_shared.h"
+#include <utility>
 
 namespace adwin {
 
@@ -231,43 +232,50 @@ constexpr int kGradLds = (kGradRing3 + 2) * kImgBytes;        // 160 KiB
 // round of tiles while a slab block (A) is fetched by one XCD only, and the deeper lead on
 // B is worth 2 % (on A 4 % against no third buffer at all).  Loads return in order: the wait
 // before the barrier leaves the youngest eight, this step's early loads, in flight.
+// Ring state (wave-uniform, LDS addresses that include the wave's KiB, which the loads want and
+// the fragment offsets swA/swB take out again): r_a, r_b = the A and B buffers this k-step
+// reads, on return those of the next k-step.  (pa, pb) = the blocks loaded by the previous
+// k-step, on return those loaded by this one.  voffd[d] = 16 lane + 1024 wave + 4096 d.  The
+// ring and address arithmetic sits in the shadows of the first MFMAs (see ring_next).
 template <bool LOADS, bool LAST>
 __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][4], bf16x8 (&fb)[2][4],
-                                           const char* curA, const char* curB, const char* nxtA,
-                                           const char* nxtB, int lane, uint32_t lds_early, uint32_t lds_late,
-                                           uint32_t voff, const char* s_late, const char* s_early) {
-  const int key = (lane >> 1) & 7, half = lane >> 5;
-  const int rowoff = (lane & 31) * kRowBytes;
-  int sw[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) sw[kk] = rowoff + (((kk * 2 + half) ^ key) << 4);
+                                           uint32_t& r_a, uint32_t& r_b, uint32_t a_begin, uint32_t a_end,
+                                           uint32_t b_begin, uint32_t b_end, const uint32_t (&swA)[4],
+                                           const uint32_t (&swB)[4], const uint32_t (&voffd)[8],
+                                           uint32_t& pa_lo, uint32_t& pa_hi, uint32_t& pb_lo, uint32_t& pb_hi) {
+  uint32_t r_a_nx = 0, r_b_nx = 0, r_b_wr = 0;
+  uint32_t xa = 0, xb = 0;      // the lane's LDS addresses of its first A and B fragment of a sub-step
 #define ADWIN_FENCE __builtin_amdgcn_sched_barrier(0);
 #define ADWIN_MM(KK, I, J)                                                                    \
   acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][I], fb[(KK) & 1][J],       \
                                                       acc[I][J], 0, 0, 0);                    \
   ADWIN_FENCE
   // side operation M (0..15) in the shadow of MFMA M of sub-step KK: fragment reads of the
-  // next sub-step, then (sub-steps 1, 2 and 3) the wave-loads of the k-step after next: 4 KiB
-  // groups d = 0..7 of the early block, then of the late block, each offset by this wave's 1 KiB
+  // next sub-step (from this step's buffers, in sub-step 3 from the next step's), the ring and
+  // address arithmetic (sub-step 0), then (sub-steps 1, 2 and 3) the wave-loads of the k-step
+  // after next: 4 KiB groups d = 0..7 of the early block, then of the late block
 #define ADWIN_SIDE(KK, M)                                                                           \
-  if constexpr ((KK) < 3 && (M) < 8) {                                                              \
+  if constexpr ((M) < 8 && ((KK) < 3 || !LAST)) {                                                   \
+    if constexpr ((M) == 0) {                                                                       \
+      xa = ((KK) < 3 ? r_a : r_a_nx) + swA[((KK) + 1) & 3];                                         \
+      xb = ((KK) < 3 ? r_b : r_b_nx) + swB[((KK) + 1) & 3];                                         \
+      asm volatile("" : "+v"(xa), "+v"(xb));                                                        \
+    }                                                                                               \
     if constexpr (((M) & 1) == 0)                                                                   \
-      fa[((KK) + 1) & 1][((M) >> 1) & 3] = *(const bf16x8*)(curA + (((M) >> 1) & 3) * 32 * kRowBytes + sw[(KK) + 1]); \
+      fa[((KK) + 1) & 1][((M) >> 1) & 3] = ((LdsFragPtr)xa)[(((M) >> 1) & 3) * 32 * kRowBytes / 16]; \
     else                                                                                            \
-      fb[((KK) + 1) & 1][((M) >> 1) & 3] = *(const bf16x8*)(curB + (((M) >> 1) & 3) * 32 * kRowBytes + sw[(KK) + 1]); \
+      fb[((KK) + 1) & 1][((M) >> 1) & 3] = ((LdsFragPtr)xb)[(((M) >> 1) & 3) * 32 * kRowBytes / 16]; \
+    if constexpr ((KK) == 0 && (M) == 0 && !LAST) r_b_nx = ring_next<kImgBytes>(r_b, b_begin, b_end); \
+    if constexpr ((KK) == 0 && (M) == 1 && !LAST) r_a_nx = ring_next<kImgBytes>(r_a, a_begin, a_end); \
+    if constexpr ((KK) == 0 && (M) == 2 && LOADS) r_b_wr = ring_next<kImgBytes>(r_b_nx, b_begin, b_end); \
+    if constexpr ((KK) == 0 && (M) == 3 && LOADS) addr_advance<kImgBytes>(pb_lo, pb_hi);            \
+    if constexpr ((KK) == 0 && (M) == 4 && LOADS) addr_advance<kImgBytes>(pa_lo, pa_hi);            \
     ADWIN_FENCE                                                                                     \
   } else if constexpr (((KK) == 1 || (KK) == 2) && (M) >= 12 && LOADS) {                            \
-    dma16(lds_early + (uint32_t)(((KK) - 1) * 4 + (M) - 12) * 4096u, voff,                          \
-          s_early + (((KK) - 1) * 4 + (M) - 12) * 4096);                                            \
+    dma16_at<(((KK) - 1) * 4 + (M) - 12) * 4096>(r_b_wr, voffd[(((KK) - 1) * 4 + (M) - 12) & 7], addr_of(pb_lo, pb_hi)); \
     ADWIN_FENCE                                                                                     \
   } else if constexpr ((KK) == 3 && (M) >= 8 && LOADS) {                                            \
-    dma16(lds_late + (uint32_t)((M) - 8) * 4096u, voff, s_late + ((M) - 8) * 4096);                  \
-    ADWIN_FENCE                                                                                     \
-  } else if constexpr ((KK) == 3 && (M) < 8 && !LAST) {                                             \
-    if constexpr (((M) & 1) == 0)                                                                   \
-      fa[0][((M) >> 1) & 3] = *(const bf16x8*)(nxtA + (((M) >> 1) & 3) * 32 * kRowBytes + sw[0]);               \
-    else                                                                                            \
-      fb[0][((M) >> 1) & 3] = *(const bf16x8*)(nxtB + (((M) >> 1) & 3) * 32 * kRowBytes + sw[0]);               \
+    dma16_at<((M) - 8) * 4096>(r_a, voffd[((M) - 8) & 7], addr_of(pa_lo, pa_hi));                         \
     ADWIN_FENCE                                                                                     \
   }
 #define ADWIN_ROW(KK, I, M0)                                                    \
@@ -287,11 +295,19 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
   }
   ADWIN_FENCE
   ADWIN_SUB(3)
+  if constexpr (!LAST) { r_a = r_a_nx; r_b = r_b_nx; }
 #undef ADWIN_SUB
 #undef ADWIN_ROW
 #undef ADWIN_SIDE
 #undef ADWIN_MM
 #undef ADWIN_FENCE
+}
+
+// The eight wave-loads of one 32 KiB block into the buffer at lds_wave (its address + 1024 wave).
+template <int... D>
+__device__ __forceinline__ void dma_block(uint32_t lds_wave, const uint32_t (&voffd)[8], const char* blk,
+                                          std::integer_sequence<int, D...>) {
+  (dma16_at<D * 4096>(lds_wave, voffd[D], blk), ...);
 }
 
 __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
@@ -311,10 +327,19 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 
   // wave-load d of a block covers its bytes [4096 d + 1024 wave, + 1024): lane l moves the
   // 16 bytes at offset 16 l of that KiB to the same place of the LDS stage
-  const uint32_t voff = (uint32_t)lane * 16u;
-  const char* sA = (const char*)a.slab + ((int64_t)rt * a.nk_total + k_begin) * kImgBytes + wave * 1024;
-  const char* sB = (const char*)a.WsT + ((int64_t)ht * a.nk_total + k_begin) * kImgBytes + wave * 1024;
+  uint32_t voffd[8];
+#pragma unroll
+  for (int d = 0; d < 8; ++d) {
+    voffd[d] = (uint32_t)lane * 16u + (uint32_t)wave * 1024u + (uint32_t)d * 4096u;
+    asm volatile("" : "+v"(voffd[d]));   // kept in registers, not recomputed at every load
+  }
+  const char* sA = (const char*)a.slab + ((int64_t)rt * a.nk_total + k_begin) * kImgBytes;
+  const char* sB = (const char*)a.WsT + ((int64_t)ht * a.nk_total + k_begin) * kImgBytes;
   const uint32_t ldsw = lds0 + (uint32_t)wave * 1024u;
+  // the ring of three (offset 0) holds the W_s^T blocks, the ring of two the slab blocks
+  const uint32_t b_begin = ldsw, b_end = ldsw + kGradRing3 * kImgBytes;
+  const uint32_t a_begin = ldsw + kGradRing2Off, a_end = a_begin + 2 * kImgBytes;
+  const std::make_integer_sequence<int, 8> all8{};
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -325,58 +350,46 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       for (int e = 0; e < 16; ++e) acc[fm][fn][e] = 0.f;
 
   if (nk > 0) {
-    // the ring of three (offset 0) holds the W_s^T blocks, the ring of two the slab blocks;
     // first the blocks of k-step 0, then its first fragments
-#pragma unroll
-    for (int d = 0; d < 8; ++d) {
-      dma16(ldsw + (uint32_t)d * 4096u, voff, sB + d * 4096);
-      dma16(ldsw + (uint32_t)kGradRing2Off + (uint32_t)d * 4096u, voff, sA + d * 4096);
-    }
+    dma_block(b_begin, voffd, sB, all8);
+    dma_block(a_begin, voffd, sA, all8);
     wait_vm<0>();
     __syncthreads();
     bf16x8 fa[2][4], fb[2][4];
-    const int waveA = kGradRing2Off + wm * 128 * kRowBytes, waveB = wn * 128 * kRowBytes;
+    uint32_t swA[4], swB[4];
     {
       const int key = (lane >> 1) & 7, half = lane >> 5;
-      const int sw0 = (lane & 31) * kRowBytes + ((half ^ key) << 4);
+      const uint32_t rowoff = (uint32_t)(lane & 31) * kRowBytes - (uint32_t)wave * 1024u;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        fa[0][i] = *(const bf16x8*)(lds + waveA + i * 32 * kRowBytes + sw0);
-        fb[0][i] = *(const bf16x8*)(lds + waveB + i * 32 * kRowBytes + sw0);
+      for (int kk = 0; kk < 4; ++kk) {
+        const uint32_t x = rowoff + (uint32_t)(((kk * 2 + half) ^ key) << 4);
+        swA[kk] = x + (uint32_t)(wm * 128 * kRowBytes);
+        swB[kk] = x + (uint32_t)(wn * 128 * kRowBytes);
       }
     }
+    uint32_t r_a = a_begin, r_b = b_begin;     // k-step s reads B buffer s % 3 and A buffer s % 2
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      fa[0][i] = ((LdsFragPtr)(r_a + swA[0]))[i * 32 * kRowBytes / 16];
+      fb[0][i] = ((LdsFragPtr)(r_b + swB[0]))[i * 32 * kRowBytes / 16];
+    }
     // blocks of k-step 1 (k-step s of the loop loads those of k-step s + 2)
+    uint64_t pa = (uint64_t)sA, pb = (uint64_t)sB;
     if (nk > 1) {
-#pragma unroll
-      for (int d = 0; d < 8; ++d) dma16(ldsw + kImgBytes + (uint32_t)d * 4096u, voff, sB + kImgBytes + d * 4096);
-#pragma unroll
-      for (int d = 0; d < 8; ++d)
-        dma16(ldsw + kGradRing2Off + kImgBytes + (uint32_t)d * 4096u, voff, sA + kImgBytes + d * 4096);
+      pa += kImgBytes; pb += kImgBytes;
+      dma_block(b_begin + kImgBytes, voffd, (const char*)pb, all8);
+      dma_block(a_begin + kImgBytes, voffd, (const char*)pa, all8);
     }
-    // k-step s reads B buffer s % 3 and A buffer s % 2
-    int s = 0, ib = 0;
-    for (; s + 2 < nk; ++s) {
-      const int ib1 = ib == kGradRing3 - 1 ? 0 : ib + 1, ib2 = ib1 == kGradRing3 - 1 ? 0 : ib1 + 1;
-      const int ia = (s & 1) * kImgBytes, ia1 = kImgBytes - ia;
-      grad_kstep<true, false>(acc, fa, fb, lds + ia + waveA, lds + ib * kImgBytes + waveB,
-                              lds + ia1 + waveA, lds + ib1 * kImgBytes + waveB, lane,
-                              ldsw + ib2 * kImgBytes, ldsw + kGradRing2Off + ia, voff,
-                              sA + (int64_t)(s + 2) * kImgBytes, sB + (int64_t)(s + 2) * kImgBytes);
-      ib = ib1;
-    }
-    if (s + 1 < nk) {
-      const int ib1 = ib == kGradRing3 - 1 ? 0 : ib + 1;
-      const int ia = (s & 1) * kImgBytes, ia1 = kImgBytes - ia;
-      grad_kstep<false, false>(acc, fa, fb, lds + ia + waveA, lds + ib * kImgBytes + waveB,
-                               lds + ia1 + waveA, lds + ib1 * kImgBytes + waveB, lane, ldsw, ldsw, voff, sA, sB);
-      ib = ib1;
-      ++s;
-    }
-    {
-      const int ia = (s & 1) * kImgBytes;
-      grad_kstep<false, true>(acc, fa, fb, lds + ia + waveA, lds + ib * kImgBytes + waveB, lds, lds, lane,
-                              ldsw, ldsw, voff, sA, sB);
-    }
+    uint32_t pa_lo = (uint32_t)pa, pa_hi = (uint32_t)(pa >> 32), pb_lo = (uint32_t)pb, pb_hi = (uint32_t)(pb >> 32);
+    int s = 0;
+    for (; s + 2 < nk; ++s)
+      grad_kstep<true, false>(acc, fa, fb, r_a, r_b, a_begin, a_end, b_begin, b_end, swA, swB, voffd,
+                              pa_lo, pa_hi, pb_lo, pb_hi);
+    if (s + 1 < nk)
+      grad_kstep<false, false>(acc, fa, fb, r_a, r_b, a_begin, a_end, b_begin, b_end, swA, swB, voffd,
+                               pa_lo, pa_hi, pb_lo, pb_hi);
+    grad_kstep<false, true>(acc, fa, fb, r_a, r_b, a_begin, a_end, b_begin, b_end, swA, swB, voffd,
+                            pa_lo, pa_hi, pb_lo, pb_hi);
   }
   float* g = a.g + (int64_t)split * a.g_rows * a.H;
   const int64_t out_row0 = rt < a.half_tiles ? a.slab_row0 + (int64_t)rt * kGradTile

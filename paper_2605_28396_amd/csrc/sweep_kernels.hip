@@ -500,28 +500,6 @@ __device__ __forceinline__ void dma_one(uint32_t lds_wave, const uint32_t (&voff
     dma16_at<(kTileVocab / 8 + 4 * (I - kTileVocab / 32)) * 1024>(lds_wave, voffw[I - kTileVocab / 32], sB);
 }
 
-// Wave-uniform bookkeeping of the k-step pipeline, written as instructions at a fixed place:
-// plain scalar arithmetic has no place of its own in the pinned order below and would be
-// gathered in front of the k-step's first MFMA, where the wave, which issues one instruction at
-// a time, keeps the matrix pipe waiting.
-// Ring slot after slot x (addresses; the ring is [begin, end), slots kLogitStage apart).
-__device__ __forceinline__ uint32_t ring_next(uint32_t x, uint32_t ring_begin, uint32_t ring_end) {
-  uint32_t y;
-  asm volatile("s_add_u32 %0, %1, %4\n\ts_cmp_lg_u32 %0, %2\n\ts_cselect_b32 %0, %0, %3"
-               : "=&s"(y) : "s"(x), "s"(ring_end), "s"(ring_begin), "n"(kLogitStage) : "scc");
-  return y;
-}
-// 64-bit address, kept as two halves, += BYTES.
-template <int BYTES>
-__device__ __forceinline__ void addr_advance(uint32_t& lo, uint32_t& hi) {
-  asm volatile("s_add_u32 %0, %0, %2\n\ts_addc_u32 %1, %1, 0" : "+s"(lo), "+s"(hi) : "n"(BYTES) : "scc");
-}
-__device__ __forceinline__ const char* addr_of(uint32_t lo, uint32_t hi) {
-  return (const char*)(((uint64_t)hi << 32) | lo);
-}
-
-typedef const __attribute__((address_space(3))) bf16x8* LdsFragPtr;
-
 // One staged k-step (4 sub-steps of 8 MFMAs) of the 128 x 64 wave tile.  On entry fa[0],
 // fb[0] hold the fragments of sub-step 0.  The instruction order is pinned: after each MFMA
 // one or two side operations are issued in its shadow -- an LDS read of a fragment of the
@@ -583,7 +561,7 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
   }
   ADWIN_FENCE
   ADWIN_SUB(0, true, r_rd, 0, 1, 2,
-            { r_nx = ring_next(r_rd, ring_begin, ring_end); }, { r_wr = ring_next(r_nx, ring_begin, ring_end); },
+            { r_nx = ring_next<kLogitStage>(r_rd, ring_begin, ring_end); }, { r_wr = ring_next<kLogitStage>(r_nx, ring_begin, ring_end); },
             { addr_advance<kImgABytes>(a_lo, a_hi); }, { addr_advance<kImgBBytes>(b_lo, b_hi); })
   ADWIN_SUB(1, true, r_rd, 3, 4, 5, {}, {}, {}, {})
   ADWIN_SUB(2, true, r_rd, 6, 7, 8, {}, {}, {}, {})
