@@ -60,6 +60,7 @@ __device__ __forceinline__ const char* addr_of(uint32_t lo, uint32_t hi) {
 
 // a fragment (8 bf16 of one row) in the LDS, addressed by its 32-bit LDS address
 typedef const __attribute__((address_space(3))) bf16x8* LdsFragPtr;
+__device__ __forceinline__ LdsFragPtr lds_frag(uint32_t addr) { return (LdsFragPtr)(uintptr_t)addr; }
 
 template <int N>
 __device__ __forceinline__ void wait_vm() {

@@ -262,9 +262,9 @@ __device__ __forceinline__ void grad_kstep(f32x16 (&acc)[4][4], bf16x8 (&fa)[2][
       asm volatile("" : "+v"(xa), "+v"(xb));                                                        \
     }                                                                                               \
     if constexpr (((M) & 1) == 0)                                                                   \
-      fa[((KK) + 1) & 1][((M) >> 1) & 3] = ((LdsFragPtr)xa)[(((M) >> 1) & 3) * 32 * kRowBytes / 16]; \
+      fa[((KK) + 1) & 1][((M) >> 1) & 3] = lds_frag(xa)[(((M) >> 1) & 3) * 32 * kRowBytes / 16]; \
     else                                                                                            \
-      fb[((KK) + 1) & 1][((M) >> 1) & 3] = ((LdsFragPtr)xb)[(((M) >> 1) & 3) * 32 * kRowBytes / 16]; \
+      fb[((KK) + 1) & 1][((M) >> 1) & 3] = lds_frag(xb)[(((M) >> 1) & 3) * 32 * kRowBytes / 16]; \
     if constexpr ((KK) == 0 && (M) == 0 && !LAST) r_b_nx = ring_next<kImgBytes>(r_b, b_begin, b_end); \
     if constexpr ((KK) == 0 && (M) == 1 && !LAST) r_a_nx = ring_next<kImgBytes>(r_a, a_begin, a_end); \
     if constexpr ((KK) == 0 && (M) == 2 && LOADS) r_b_wr = ring_next<kImgBytes>(r_b_nx, b_begin, b_end); \
@@ -370,8 +370,8 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     uint32_t r_a = a_begin, r_b = b_begin;     // k-step s reads B buffer s % 3 and A buffer s % 2
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      fa[0][i] = ((LdsFragPtr)(r_a + swA[0]))[i * 32 * kRowBytes / 16];
-      fb[0][i] = ((LdsFragPtr)(r_b + swB[0]))[i * 32 * kRowBytes / 16];
+      fa[0][i] = lds_frag(r_a + swA[0])[i * 32 * kRowBytes / 16];
+      fb[0][i] = lds_frag(r_b + swB[0])[i * 32 * kRowBytes / 16];
     }
     // blocks of k-step 1 (k-step s of the loop loads those of k-step s + 2)
     uint64_t pa = (uint64_t)sA, pb = (uint64_t)sB;

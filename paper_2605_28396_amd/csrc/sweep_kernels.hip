@@ -530,8 +530,8 @@ __device__ __forceinline__ void sweep_kstep(f32x16 (&acc)[4][2], bf16x8 (&fa)[2]
   const f32x16 kZeroTile = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   uint32_t r_nx, r_wr;
 #define ADWIN_FENCE __builtin_amdgcn_sched_barrier(0);
-#define ADWIN_RA(KK, I) fa[((KK) + 1) & 1][I] = ((LdsFragPtr)xa)[(I) * 32 * kRowBytes / 16]; ADWIN_FENCE
-#define ADWIN_RB(KK, I) fb[((KK) + 1) & 1][I] = ((LdsFragPtr)xb)[(I) * 32 * kRowBytes / 16]; ADWIN_FENCE
+#define ADWIN_RA(KK, I) fa[((KK) + 1) & 1][I] = lds_frag(xa)[(I) * 32 * kRowBytes / 16]; ADWIN_FENCE
+#define ADWIN_RB(KK, I) fb[((KK) + 1) & 1][I] = lds_frag(xb)[(I) * 32 * kRowBytes / 16]; ADWIN_FENCE
 #define ADWIN_MM(KK, FMI, FNI)                                                                  \
   acc[FMI][FNI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[(KK) & 1][FMI], fb[(KK) & 1][FNI], \
                                                           (FRESH && (KK) == 0) ? kZeroTile : acc[FMI][FNI], 0, 0, 0); \
@@ -727,9 +727,9 @@ __global__ __launch_bounds__(256) void logit_pass_dma_kernel(LogitPassArgs a) {
     if (vt == vt_begin) wait_vm<kDmaPerWave>();
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[0][i] = *(LdsFragPtr)(r_rd + swA[0] + i * 32 * kRowBytes);
+    for (int i = 0; i < 4; ++i) fa[0][i] = lds_frag(r_rd + swA[0])[i * 32 * kRowBytes / 16];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) fb[0][i] = *(LdsFragPtr)(r_rd + swB[0] + i * 32 * kRowBytes);
+    for (int i = 0; i < 2; ++i) fb[0][i] = lds_frag(r_rd + swB[0])[i * 32 * kRowBytes / 16];
     // teacher: nk_t k-steps (the first on a zero addend; after an epilogue its wait leaves that
     // epilogue's stores in flight), then student: nk_s k-steps, the last without a barrier
     step(no, yes, after_epilogue, zt, vt != vt_begin);
