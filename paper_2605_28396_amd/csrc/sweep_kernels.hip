@@ -445,16 +445,16 @@ __global__ __launch_bounds__(256) void logit_pass_kernel(LogitPassArgs a) {
 //
 // Same tile, MFMA roles and epilogues as logit_pass_kernel, but the k-tiles are moved by
 // global_load_lds_dwordx4 (no register staging) into a three-stage LDS ring, two k-steps
-// ahead of the MFMAs.  One wave instruction moves 8 rows x 128 B: lane l lands at
-// base + 16 l, i.e. row l/8, chunk position l%8, and therefore fetches global chunk
-// (l%8) ^ swizzle(row).  The teacher and student k-loops form one pipeline of
-// H_t/64 + H_s/64 steps per vocabulary tile.
+// ahead of the MFMAs, from tile images that already have the LDS layout (row_image_kernel
+// below): one wave instruction moves 1 KiB of consecutive bytes, lane l its 16 bytes at 16 l.
+// The teacher and student k-loops form one pipeline of H_t/64 + H_s/64 steps per vocabulary
+// tile.
 //
-// The loads are written as inline assembly (M0 = LDS destination of the wave, scalar base
-// + 32-bit lane offset) and waited for with explicit s_waitcnt vmcnt(N): the loads return
-// in order, so "at most the 12 loads of the next stage outstanding" means this stage has
-// landed.  Compiler-issued loads in between only make the count larger, i.e. the wait
-// longer.  Requires rows * H * 2 bytes < 4 GiB per operand (32-bit lane offsets).
+// The loads are written as inline assembly (M0 = LDS destination of the wave, 64-bit scalar
+// base + 32-bit lane offset within the block) and waited for with explicit
+// s_waitcnt vmcnt(N): the loads return in order, so "at most the 12 loads of the next stage
+// outstanding" means this stage has landed.  Compiler-issued loads in between only make the
+// count larger, i.e. the wait longer.
 // ---------------------------------------------------------------------------------------
 constexpr int kDmaStages = 3;
 constexpr int kDmaLds = kDmaStages * kLogitStage;           // 144 KiB
